@@ -1,0 +1,254 @@
+"""Seeded synthetic inputs: decoding graphs, log-likelihoods, biasing contexts.
+
+This module only draws random numbers and lays them out.  It holds none of the
+decoder's arithmetic, imports neither the HIP binding nor the CPU checker, and is
+the one piece both of them are fed from, so that they always see the same bytes.
+
+The inputs stand in for the paper's online workloads (Sec. 5: 2K clients, 30 ms
+frames after one-third subsampling, biasing lists of a few hundred up to 1013
+entities, Table 2): random HCLG-like transducers, log-softmax Gaussian scores and
+per-channel lists of word-arc indices that lie along connected walks, like the
+arc sets Algorithm 1 returns for word sequences.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field, replace
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+BASE_SEED = 230615685
+
+FRAME_SHIFT_S = 0.030  # Sec. 5.2: 10 ms features, one-third frame subsampling
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One benchmark configuration (sizes and decoder settings)."""
+
+    name: str
+    num_states: int
+    num_pdfs: int
+    num_words: int
+    eps_prob: float
+    channels: int
+    frames: int  # frames per segment (utterance)
+    chunk: int  # frames handed to one advance call
+    beam: float
+    max_active: int  # 0 = off
+    sigma: float  # standard deviation of the pre-softmax scores
+    ctx_min: int  # context size range (arcs)
+    ctx_max: int
+    offset_lo: float  # offset range; lo == hi means fixed
+    offset_hi: float
+    segments: int = 1  # utterances per channel, each with a fresh context
+    ctx_walks: bool = True  # arcs along connected walks (False: independent word arcs)
+    lookup_mode: int = 0  # 0 sorted list, 1 hashed bitmap + confirm
+    partial_every_chunk: bool = False
+    mean_degree: float = 3.0
+    word_frac: float = 0.25
+    config_id: int = 0
+
+
+WORKLOADS: Dict[str, Workload] = {
+    "tiny": Workload("tiny", 2_000, 200, 600, 0.15, 1, 100, 100, 10.0, 0, 3.0,
+                     20, 20, -3.0, -3.0, ctx_walks=False, config_id=0),
+    "medium": Workload("medium", 1_000_000, 3_000, 20_000, 0.10, 32, 333, 333, 13.0, 7_000, 4.0,
+                       50, 50, -5.0, -5.0, config_id=1),
+    "large": Workload("large", 10_000_000, 6_000, 200_000, 0.10, 256, 500, 50, 15.0, 10_000, 4.0,
+                      100, 500, -5.0, -5.0, partial_every_chunk=True, config_id=2),
+    "dynamic": Workload("dynamic", 10_000_000, 6_000, 200_000, 0.10, 512, 100, 100, 15.0, 10_000, 4.0,
+                        10, 1_000, -8.0, -2.0, segments=20, config_id=3),
+    "stress": Workload("stress", 10_000_000, 6_000, 200_000, 0.10, 2_048, 300, 50, 16.0, 20_000, 4.0,
+                       1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A copy of a workload with some fields replaced (smaller test variants)."""
+    return replace(w, **kw)
+
+
+def _rng(*stream: int) -> np.random.Generator:
+    """Counter-based generator keyed by (base seed, stream ids)."""
+    ss = np.random.SeedSequence([BASE_SEED, *[int(x) & 0xFFFFFFFF for x in stream]])
+    return np.random.Generator(np.random.Philox(ss))
+
+
+@dataclass
+class Graph:
+    """A transducer in the caller's arc numbering: plain CSR rows over states.
+
+    Arc ``a`` of state ``s`` has ``row_offsets[s] <= a < row_offsets[s+1]``.
+    ``ilabel`` 0 marks an epsilon-input arc, otherwise it is pdf id + 1.
+    ``olabel`` 0 means no word.  ``weight`` is a cost (-log probability), fp32.
+    """
+
+    num_states: int
+    num_arcs: int
+    num_pdfs: int
+    num_words: int
+    start_state: int
+    row_offsets: np.ndarray  # int32 [S+1]
+    dst: np.ndarray  # int32 [A]
+    ilabel: np.ndarray  # int32 [A]
+    olabel: np.ndarray  # int32 [A]
+    weight: np.ndarray  # float32 [A]
+    final_cost: Optional[np.ndarray] = None  # float32 [S] or None (all final, cost 0)
+    _src: Optional[np.ndarray] = field(default=None, repr=False)
+
+    @property
+    def src(self) -> np.ndarray:
+        if self._src is None:
+            deg = np.diff(self.row_offsets.astype(np.int64))
+            self._src = np.repeat(np.arange(self.num_states, dtype=np.int32), deg)
+        return self._src
+
+
+def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
+               seed_stream: Tuple[int, ...] = (0,), mean_degree: float = 3.0,
+               word_frac: float = 0.25, with_finals: bool = False,
+               self_loop_frac: float = 0.0) -> Graph:
+    """Random HCLG-like graph.
+
+    Out-degree is Poisson(mean_degree) clipped to at least 1.  Each arc is an
+    epsilon-input arc with probability ``eps_prob``; such arcs always lead to a
+    higher-numbered state, so the epsilon subgraph is acyclic (the last state has
+    none).  Emitting arcs go to a uniformly random state and carry a uniformly
+    random pdf.  A fraction ``word_frac`` of all arcs carry a uniformly random
+    word.  Weights are -ln U(0.05, 1).  Epsilon and emitting arcs are interleaved
+    within a row, in no particular order.
+    """
+    S = int(num_states)
+    rng = _rng(1, *seed_stream)
+    deg = np.maximum(rng.poisson(mean_degree, S), 1).astype(np.int64)
+    row = np.zeros(S + 1, dtype=np.int64)
+    np.cumsum(deg, out=row[1:])
+    A = int(row[-1])
+    assert A < 2**31 - 1
+    src = np.repeat(np.arange(S, dtype=np.int64), deg)
+    is_eps = rng.random(A) < eps_prob
+    is_eps &= src < S - 1
+    dst = rng.integers(0, S, A, dtype=np.int64)
+    u = rng.random(A)
+    eps_dst = src + 1 + np.floor(u * (S - 1 - src)).astype(np.int64)
+    eps_dst = np.minimum(eps_dst, S - 1)
+    dst = np.where(is_eps, eps_dst, dst)
+    if self_loop_frac > 0.0:
+        loop = (~is_eps) & (rng.random(A) < self_loop_frac)
+        dst = np.where(loop, src, dst)
+    pdf = rng.integers(0, num_pdfs, A, dtype=np.int64)
+    ilabel = np.where(is_eps, 0, pdf + 1)
+    word = rng.integers(1, num_words + 1, A, dtype=np.int64)
+    olabel = np.where(rng.random(A) < word_frac, word, 0)
+    weight = (-np.log(rng.uniform(0.05, 1.0, A))).astype(np.float32)
+    final = None
+    if with_finals:
+        final = (-np.log(rng.uniform(0.05, 1.0, S))).astype(np.float32)
+    return Graph(S, A, int(num_pdfs), int(num_words), 0, row.astype(np.int32),
+                 dst.astype(np.int32), ilabel.astype(np.int32), olabel.astype(np.int32),
+                 weight, final, src.astype(np.int32))
+
+
+def graph_for(w: Workload, with_finals: bool = False) -> Graph:
+    return make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob,
+                      seed_stream=(w.config_id,), mean_degree=w.mean_degree,
+                      word_frac=w.word_frac, with_finals=with_finals)
+
+
+def make_loglikes(channels: int, frames: int, num_pdfs: int, sigma: float,
+                  seed_stream: Tuple[int, ...] = (0,), device: str = "cpu"):
+    """fp32 tensor [channels, frames, num_pdfs]: log_softmax over pdfs of N(0, sigma^2).
+
+    Drawn with torch's generator for ``device`` (the streams differ between
+    devices; whoever consumes the tensor sees the same bytes either way).
+    """
+    import torch
+
+    seed = int(np.random.SeedSequence([BASE_SEED, 2, *seed_stream]).generate_state(1, np.uint64)[0] >> 1)
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    x = torch.randn((channels, frames, num_pdfs), generator=g, device=device, dtype=torch.float32)
+    x.mul_(sigma)
+    return torch.log_softmax(x, dim=-1)
+
+
+def word_arcs(g: Graph) -> np.ndarray:
+    return np.nonzero(g.olabel != 0)[0].astype(np.int32)
+
+
+def context_random_word_arcs(g: Graph, k: int, seed_stream: Tuple[int, ...]) -> np.ndarray:
+    """k distinct word-arc indices, uniform over the graph's word arcs."""
+    rng = _rng(3, *seed_stream)
+    wa = word_arcs(g)
+    k = min(k, wa.size)
+    return rng.choice(wa, size=k, replace=False).astype(np.int32)
+
+
+def context_walks(g: Graph, n_walks: int, words_per_walk: int, seed_stream: Tuple[int, ...],
+                  rng: Optional[np.random.Generator] = None) -> np.ndarray:
+    """Word arcs crossed by random walks through the graph.
+
+    Each walk starts at a uniformly random state and follows uniformly random
+    out-arcs until it has crossed ``words_per_walk`` word arcs; the word arcs it
+    crossed are returned (all walks concatenated, duplicates removed, any order).
+    The arcs of one walk lie on a connected path, like the arc sets found for a
+    word sequence (Algorithm 1).
+    """
+    if rng is None:
+        rng = _rng(4, *seed_stream)
+    row = g.row_offsets.astype(np.int64)
+    cur = rng.integers(0, g.num_states, n_walks, dtype=np.int64)
+    need = np.full(n_walks, words_per_walk, dtype=np.int64)
+    out: List[np.ndarray] = []
+    for _ in range(words_per_walk * 64):
+        live = need > 0
+        if not live.any():
+            break
+        s = cur[live]
+        deg = row[s + 1] - row[s]
+        ok = deg > 0
+        pick = row[s] + np.floor(rng.random(s.size) * np.maximum(deg, 1)).astype(np.int64)
+        pick = np.minimum(pick, row[s + 1] - 1)
+        pick = np.where(ok, pick, 0)
+        isw = ok & (g.olabel[pick] != 0)
+        out.append(pick[isw].astype(np.int32))
+        nxt = np.where(ok, g.dst[pick].astype(np.int64), rng.integers(0, g.num_states, s.size))
+        cur[live] = nxt
+        nl = need[live]
+        nl -= isw.astype(np.int64)
+        need[live] = nl
+    if not out:
+        return np.zeros(0, dtype=np.int32)
+    return np.unique(np.concatenate(out)).astype(np.int32)
+
+
+def make_contexts(w: Workload, g: Graph, segment: int = 0,
+                  channels: Optional[int] = None) -> Tuple[List[np.ndarray], np.ndarray]:
+    """Per-channel arc-index lists and offsets for one segment of a workload.
+
+    Lists are returned shuffled (the decoder treats them as sets).  Sizes are
+    drawn uniformly from [ctx_min, ctx_max]; with ``ctx_walks`` a list is built
+    from size/10 walks of 10 word arcs each and cut to size.
+    """
+    C = w.channels if channels is None else channels
+    lists: List[np.ndarray] = []
+    offs = np.zeros(C, dtype=np.float32)
+    for c in range(C):
+        rng = _rng(5, w.config_id, c, segment)
+        k = int(rng.integers(w.ctx_min, w.ctx_max + 1))
+        if w.offset_lo == w.offset_hi:
+            offs[c] = np.float32(w.offset_lo)
+        else:
+            offs[c] = np.float32(rng.uniform(w.offset_lo, w.offset_hi))
+        if w.ctx_walks:
+            n_walks = max(1, (k + 9) // 10)
+            arcs = context_walks(g, n_walks + 1, 10, (), rng=rng)
+            if arcs.size > k:
+                arcs = arcs[rng.permutation(arcs.size)[:k]]
+        else:
+            wa = word_arcs(g)
+            arcs = rng.choice(wa, size=min(k, wa.size), replace=False).astype(np.int32)
+        arcs = arcs[rng.permutation(arcs.size)].astype(np.int32)
+        lists.append(arcs)
+    return lists, offs
