@@ -1,0 +1,208 @@
+/*
+ * cbd.h -- C ABI of the contextual-biasing beam-search decoder for MI355X (gfx950).
+ *
+ * The library decodes many audio channels at once over one shared, read-only
+ * decoding graph.  Each channel carries its own context: a set of arc indices
+ * and a discount offset that is added to a listed arc's weight at the moment
+ * the arc is expanded (paper Sec. 1: only a list of arc indices is stored per
+ * context and the offset is added during decoding; Sec. 4.1: boosted weight =
+ * original weight + discount factor).  The graph is never modified, so
+ * contexts can be replaced between calls (Sec. 4.3) and partial best-path
+ * hypotheses are read without building lattices (Sec. 1, Sec. 2.2).
+ *
+ * Conventions
+ *   - Every function returns 0 (CBD_OK) or a negative cbd_status.  On error the
+ *     out-parameters are left untouched unless a function says otherwise.
+ *   - "HOST" pointers are ordinary process memory, "DEVICE" pointers are HIP
+ *     device memory on the decoder's GPU.  The caller owns every pointer it
+ *     passes; the library owns everything behind its handles and copies what
+ *     it needs before returning, except DEVICE inputs of cbd_advance (below).
+ *   - Handles are not thread-safe: one host thread per decoder at a time.
+ *     A graph may be shared by several decoders.
+ *   - All work of a decoder is enqueued on the HIP stream given at creation.
+ *   - Arc indices at this boundary are positions in the arrays given to
+ *     cbd_graph_load (the caller's numbering).
+ *   - No exceptions cross this boundary.  There is no CPU fallback.
+ *
+ * Decoding rule (fp32, every choice independent of thread order): tokens are
+ * (cost, arc) keys per state; lower cost wins, ties go to the arc with the lower
+ * source state, then emitting before epsilon-input arcs, then the lower arc
+ * index.  Per frame: tokens whose cost exceeds the frame's best by more than
+ * `beam` are dropped; if more than `max_active` remain, a 256-bin histogram over
+ * (cost - best) * 256 / beam keeps the largest prefix of bins that fits.  Every
+ * emitting arc of every survivor is expanded, cand = (cost + w') - loglike, the
+ * minimum m over candidates fixes the frame's cutoff (cand - m > beam is
+ * dropped), epsilon-input arcs are relaxed to a fixed point under the same
+ * cutoff, and the predecessor of a token is the final token of its arc's
+ * source state.
+ */
+#ifndef CBD_H_
+#define CBD_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cbd_status {
+  CBD_OK = 0,
+  CBD_E_INVALID = -1,      /* bad argument, index or shape; checked on the host before any enqueue */
+  CBD_E_CAPACITY = -2,     /* a channel overflowed its token table, change log or back-pointer buffer */
+  CBD_E_EPS_DIVERGED = -3, /* epsilon closure did not settle within max_eps_iters rounds */
+  CBD_E_NO_TOKENS = -4,    /* nothing survived (dead end) or channel never reset */
+  CBD_E_BUFFER = -5,       /* caller's output buffer too small */
+  CBD_E_HIP = -6,          /* HIP runtime error; text via cbd_last_error() */
+  CBD_E_NOMEM = -7
+} cbd_status;
+
+typedef struct cbd_graph cbd_graph;     /* opaque; immutable; device resident */
+typedef struct cbd_decoder cbd_decoder; /* opaque; owns all per-channel device state */
+
+/*
+ * The decoding graph as per-arc vectors grouped into rows by source state (the
+ * vectors Sec. 4.1 lists: input labels, output labels, next states, weights;
+ * Sec. 2.2: compressed sparse rows).  All pointers HOST.
+ */
+typedef struct cbd_graph_desc {
+  int32_t num_states;
+  int32_t num_arcs;
+  int32_t num_pdfs;           /* log-likelihood row length */
+  int32_t start_state;
+  const int32_t *row_offsets; /* [num_states+1]; arcs of state s are [row_offsets[s], row_offsets[s+1]) */
+  const int32_t *dst;         /* [num_arcs] next state */
+  const int32_t *ilabel;      /* [num_arcs] 0 = epsilon input, else pdf id + 1 (1..num_pdfs) */
+  const int32_t *olabel;      /* [num_arcs] 0 = no word, else word id */
+  const float *weight;        /* [num_arcs] cost (-log probability), finite */
+  const float *final_cost;    /* [num_states] or NULL = every state final at cost 0 */
+} cbd_graph_desc;
+
+/*
+ * Copies the graph to the current HIP device (rows are re-packed so that each
+ * state's emitting arcs precede its epsilon-input arcs; the caller's numbering
+ * stays the one used at this boundary).  CBD_E_INVALID for inconsistent rows,
+ * labels outside range, non-finite weights.
+ */
+int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out);
+int32_t cbd_graph_free(cbd_graph *g);
+
+typedef struct cbd_config {
+  int32_t num_channels;       /* >= 1 */
+  float beam;                 /* >= 0; may be +inf */
+  int32_t max_active;         /* 0 = off (needs 0 < beam < inf to act) */
+  int32_t max_frames;         /* frames per utterance the back-pointer buffer is sized for */
+  int32_t max_context_arcs;   /* largest context list after de-duplication */
+  int32_t lookup_mode;        /* 0 sorted list + binary search (Sec. 4.2); 1 hashed bitmap filter, then the search */
+  int32_t hash_capacity_log2; /* per-channel state table slots = 2^this; a frame may hold at most half as many tokens */
+  int32_t max_eps_iters;      /* epsilon-closure round limit; 0 = default 64 */
+  int32_t records_per_frame;  /* average back-pointer records per frame to reserve; 0 = table capacity / 2 */
+  int32_t table_location;     /* 0 = choose; 1 = token tables in LDS; 2 = token tables in device memory */
+} cbd_config;
+
+/*
+ * Allocates all per-channel state on the graph's device.  `hip_stream` is a
+ * hipStream_t (NULL = the null stream); it must outlive the decoder.
+ */
+int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_stream, cbd_decoder **out);
+int32_t cbd_decoder_free(cbd_decoder *d);
+
+/*
+ * Starts a new utterance on the listed channels (HOST, n entries, each in
+ * [0, num_channels), no duplicates): one start token at cost 0 followed by
+ * the epsilon closure under the channel's current context.  Clears the
+ * channel's back-pointers, counters and sticky error status.  Enqueues only.
+ */
+int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n);
+
+/*
+ * Replaces one channel's context (Sec. 4.3 dynamic context update).  arc_idx:
+ * HOST, n entries, any order, duplicates allowed (the list is a set; Algorithm 1
+ * returns a set); n = 0 clears.  Takes effect for arcs expanded by later
+ * cbd_advance / cbd_reset_channels calls; existing tokens are never re-scored.
+ * CBD_E_INVALID for an index outside [0, num_arcs) or more than
+ * max_context_arcs distinct entries.
+ */
+int32_t cbd_set_context(cbd_decoder *d, int32_t channel, const int32_t *arc_idx, int32_t n, float offset);
+
+/*
+ * The same for many channels with one upload.  list_offsets: HOST [n_channels+1],
+ * channel i's list is arc_idx[list_offsets[i] .. list_offsets[i+1]); offsets:
+ * HOST [n_channels].  Nothing is changed if any list is invalid.
+ */
+int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const int32_t *arc_idx,
+                         const int32_t *list_offsets, const float *offsets);
+
+/*
+ * Decodes n_frames frames on the listed channels (Sec. 2.2, Sec. 3.2: a chunk
+ * arrives, every outgoing arc of every queued token is expanded, candidates are
+ * pruned and re-queued).  loglikes: DEVICE fp32; the row of channel i (position
+ * in `channels`), frame f is at loglikes + i*channel_stride + f*num_pdfs, and
+ * holds log-likelihoods already scaled by the caller.  The memory must stay
+ * valid and unchanged until the stream has passed this call.  Enqueues only;
+ * channels in an error state are skipped on the device.
+ */
+int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const float *loglikes,
+                    int64_t channel_stride, int32_t n_frames);
+
+/*
+ * Best token of the channel's current frame and its back-pointer path (the
+ * partial hypothesis of Sec. 1; with use_final != 0 the state's final cost is
+ * added before the minimum is taken).  words: HOST [capacity] word ids in time
+ * order; arcs: HOST [capacity] or NULL, the arc path in the caller's numbering.
+ * Synchronises the stream.  Returns the channel's sticky error if it has one;
+ * CBD_E_BUFFER if the path has more than `capacity` arcs (then *n_arcs and
+ * *n_words hold the needed sizes).
+ */
+int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_t *words, int32_t *arcs,
+                      int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost);
+
+/*
+ * The same for many channels with one kernel and one copy.  Row i of words /
+ * arcs ([n][capacity], HOST) belongs to channels[i]; status[i] (HOST [n])
+ * receives that channel's result code; the function itself fails only for
+ * invalid arguments or HIP errors.
+ */
+int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                       int32_t *status);
+
+/*
+ * The channel's current token table (any order): state, cost, arc (caller's
+ * numbering, -1 for the start token).  For tests and inspection.  Synchronises.
+ * *n receives the table size; at most `capacity` entries are written.
+ */
+int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *costs, int32_t *arcs,
+                       int32_t capacity, int32_t *n);
+
+typedef struct cbd_stats {
+  int64_t frames;         /* frames decoded since reset */
+  int64_t active_tokens;  /* tokens that survived pruning and were expanded */
+  int64_t emit_arcs;      /* emitting arcs expanded */
+  int64_t eps_arcs;       /* epsilon-input arcs expanded (every relaxation round counts) */
+  int64_t candidates;     /* candidates that passed the cutoff and reached the state table */
+  int64_t improvements;   /* table updates (change-log entries) */
+  int64_t tokens;         /* sum over frames of the table size */
+  int64_t eps_rounds;     /* closure rounds */
+  int64_t records;        /* back-pointer records in use */
+  int32_t status;         /* sticky cbd_status of the channel */
+  int32_t max_tokens;     /* largest table so far */
+} cbd_stats;
+
+/* Counters of one channel since its last reset (channel >= 0) or summed over all (-1; status = first error).
+ * Synchronises. */
+int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out);
+
+/* Bytes of device memory the decoder holds; LDS bytes and threads per workgroup of the decode kernel. */
+int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *lds_bytes, int32_t *block_threads,
+                         int32_t *tables_in_lds);
+
+int32_t cbd_synchronize(cbd_decoder *d);
+
+const char *cbd_strerror(int32_t status);
+/* Text of the last CBD_E_HIP / CBD_E_INVALID on this thread. */
+const char *cbd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CBD_H_ */

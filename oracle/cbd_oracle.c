@@ -457,6 +457,8 @@ int32_t orc_best_path(const orc_chan *ch, int32_t use_final, int32_t *words, int
     if (a == ARC_NONE) break;
     na++;
     if (g->olabel[a] != 0) nw++;
+    /* zero-weight epsilon cycles can tie into a predecessor cycle: no path is that long */
+    if (na > ch->n_rec) { *cost = INFINITY; return ORC_EPS_DIVERGED; }
   }
   *n_arcs = na; *n_words = nw;
   if (na > cap) return ORC_BUFFER;

@@ -1,0 +1,616 @@
+// Host runtime and C ABI of the decoder: buffer ownership, validation, context
+// upload, kernel sequencing.  See include/cbd.h for the contract of each call.
+#include "../../include/cbd.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "cbd_device.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int32_t fail(int32_t code, const std::string &msg) {
+  g_last_error = msg;
+  return code;
+}
+
+#define HIPCHK(expr)                                                                              \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess)                                                                         \
+      return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));                  \
+  } while (0)
+
+template <typename T> hipError_t dmalloc(T **p, size_t n, size_t *total) {
+  size_t bytes = std::max<size_t>(n, 1) * sizeof(T);
+  hipError_t e = hipMalloc((void **)p, bytes);
+  if (e == hipSuccess && total) *total += bytes;
+  return e;
+}
+
+// A small ring of pinned host buffers with matching device buffers, so that
+// argument lists can be uploaded asynchronously without racing their reuse.
+struct StageRing {
+  static constexpr int kSlots = 8;
+  void *host[kSlots] = {};
+  void *dev[kSlots] = {};
+  hipEvent_t ev[kSlots] = {};
+  bool busy[kSlots] = {};
+  size_t cap = 0;
+  int next = 0;
+
+  hipError_t init(size_t bytes) {
+    cap = bytes;
+    for (int i = 0; i < kSlots; ++i) {
+      hipError_t e = hipHostMalloc(&host[i], bytes, hipHostMallocDefault);
+      if (e != hipSuccess) return e;
+      e = hipMalloc(&dev[i], bytes);
+      if (e != hipSuccess) return e;
+      e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  void destroy() {
+    for (int i = 0; i < kSlots; ++i) {
+      if (host[i]) (void)hipHostFree(host[i]);
+      if (dev[i]) (void)hipFree(dev[i]);
+      if (ev[i]) (void)hipEventDestroy(ev[i]);
+    }
+  }
+  // Returns a slot whose previous upload has been consumed.
+  hipError_t acquire(int *slot) {
+    int s = next;
+    next = (next + 1) % kSlots;
+    if (busy[s]) {
+      hipError_t e = hipEventSynchronize(ev[s]);
+      if (e != hipSuccess) return e;
+      busy[s] = false;
+    }
+    *slot = s;
+    return hipSuccess;
+  }
+  // Upload `bytes` of the slot's host buffer; call release() after the consumer is enqueued.
+  hipError_t upload(int s, size_t bytes, hipStream_t st) {
+    return hipMemcpyAsync(dev[s], host[s], bytes, hipMemcpyHostToDevice, st);
+  }
+  hipError_t release(int s, hipStream_t st) {
+    busy[s] = true;
+    return hipEventRecord(ev[s], st);
+  }
+};
+
+}  // namespace
+
+struct cbd_graph {
+  int device = 0;
+  int32_t S = 0, A = 0, P = 0, start = 0;
+  int2 *d_off2 = nullptr;
+  cbd::ArcRec *d_arcs = nullptr;
+  int32_t *d_int2pub = nullptr;
+  float *d_final = nullptr;
+  std::vector<int32_t> pub2int, int2pub;
+  size_t bytes = 0;
+};
+
+struct cbd_decoder {
+  const cbd_graph *g = nullptr;
+  cbd_config cfg{};
+  hipStream_t stream = nullptr;
+  int32_t C = 0, log_h = 0, tok_cap = 0, log_cap = 0, bp_cap = 0, max_ctx = 0, ctx_lds_cap = 0;
+  bool lds_tables = false;
+  int block = 1024;
+  uint32_t lds_bytes = 0;
+  cbd::ChanState *d_chan = nullptr;
+  int32_t *d_tok_state = nullptr;
+  float *d_tok_cost = nullptr;
+  int2 *d_bp = nullptr;
+  cbd::LogEntry *d_log = nullptr;
+  int32_t *d_ctx = nullptr;
+  uint32_t *d_hkey = nullptr;
+  uint64_t *d_hval = nullptr;
+  uint32_t *d_haux = nullptr;
+  int32_t *d_out_arcs = nullptr, *d_out_words = nullptr, *d_out_meta = nullptr;
+  int32_t out_capacity = 0, out_rows = 0;
+  StageRing ids;   // channel lists
+  StageRing ctxs;  // context uploads
+  std::vector<int32_t> h_tmp;
+  size_t bytes = 0;
+};
+
+namespace {
+
+using cbd::AdvanceParams;
+
+template <bool kLds, int kBlock> hipError_t launch_advance_t(const AdvanceParams &p, int grid, uint32_t lds, hipStream_t st) {
+  hipLaunchKernelGGL((cbd::advance_kernel<kLds, kBlock>), dim3(grid), dim3(kBlock), lds, st, p);
+  return hipGetLastError();
+}
+
+template <bool kLds, int kBlock> hipError_t set_attr_t(uint32_t lds) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_kernel<kLds, kBlock>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+}
+
+hipError_t set_attr(bool lds_tables, int block, uint32_t lds) {
+  if (lds_tables) {
+    if (block == 256) return set_attr_t<true, 256>(lds);
+    if (block == 512) return set_attr_t<true, 512>(lds);
+    return set_attr_t<true, 1024>(lds);
+  }
+  if (block == 256) return set_attr_t<false, 256>(lds);
+  if (block == 512) return set_attr_t<false, 512>(lds);
+  return set_attr_t<false, 1024>(lds);
+}
+
+hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {
+  if (d->lds_tables) {
+    if (d->block == 256) return launch_advance_t<true, 256>(p, grid, d->lds_bytes, d->stream);
+    if (d->block == 512) return launch_advance_t<true, 512>(p, grid, d->lds_bytes, d->stream);
+    return launch_advance_t<true, 1024>(p, grid, d->lds_bytes, d->stream);
+  }
+  if (d->block == 256) return launch_advance_t<false, 256>(p, grid, d->lds_bytes, d->stream);
+  if (d->block == 512) return launch_advance_t<false, 512>(p, grid, d->lds_bytes, d->stream);
+  return launch_advance_t<false, 1024>(p, grid, d->lds_bytes, d->stream);
+}
+
+AdvanceParams base_params(const cbd_decoder *d) {
+  AdvanceParams p{};
+  p.off2 = d->g->d_off2; p.arcs = d->g->d_arcs; p.start_state = d->g->start; p.num_pdfs = d->g->P;
+  p.chan = d->d_chan;
+  p.beam = d->cfg.beam; p.max_active = d->cfg.max_active; p.max_eps_iters = d->cfg.max_eps_iters;
+  p.lookup_mode = d->cfg.lookup_mode;
+  p.log_h = d->log_h; p.tok_cap = d->tok_cap; p.log_cap = d->log_cap; p.bp_cap = d->bp_cap;
+  p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap;
+  p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost; p.bp = d->d_bp; p.log = d->d_log; p.ctx = d->d_ctx;
+  p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_haux = d->d_haux;
+  return p;
+}
+
+// Validates a channel list and uploads it; *dev receives the device copy.
+int32_t stage_channels(cbd_decoder *d, const int32_t *channels, int32_t n, const int32_t **dev, int *slot) {
+  if (!channels || n <= 0 || n > d->C) return fail(CBD_E_INVALID, "channel list: bad length");
+  d->h_tmp.assign((size_t)d->C, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t c = channels[i];
+    if (c < 0 || c >= d->C) return fail(CBD_E_INVALID, "channel list: index out of range");
+    if (d->h_tmp[c]) return fail(CBD_E_INVALID, "channel list: duplicate channel");
+    d->h_tmp[c] = 1;
+  }
+  HIPCHK(d->ids.acquire(slot));
+  memcpy(d->ids.host[*slot], channels, sizeof(int32_t) * (size_t)n);
+  HIPCHK(d->ids.upload(*slot, sizeof(int32_t) * (size_t)n, d->stream));
+  *dev = (const int32_t *)d->ids.dev[*slot];
+  return CBD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *cbd_strerror(int32_t status) {
+  switch (status) {
+    case CBD_OK: return "ok";
+    case CBD_E_INVALID: return "invalid argument";
+    case CBD_E_CAPACITY: return "channel capacity exceeded (token table, change log or back-pointers)";
+    case CBD_E_EPS_DIVERGED: return "epsilon closure did not converge";
+    case CBD_E_NO_TOKENS: return "no tokens (dead end or channel not reset)";
+    case CBD_E_BUFFER: return "output buffer too small";
+    case CBD_E_HIP: return "HIP runtime error";
+    case CBD_E_NOMEM: return "out of memory";
+    default: return "unknown status";
+  }
+}
+
+const char *cbd_last_error(void) { return g_last_error.c_str(); }
+
+int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
+  if (!desc || !out) return fail(CBD_E_INVALID, "graph: null argument");
+  const int32_t S = desc->num_states, A = desc->num_arcs, P = desc->num_pdfs;
+  if (S <= 0 || A < 0 || P <= 0 || desc->start_state < 0 || desc->start_state >= S)
+    return fail(CBD_E_INVALID, "graph: bad sizes");
+  if (!desc->row_offsets || (A > 0 && (!desc->dst || !desc->ilabel || !desc->olabel || !desc->weight)))
+    return fail(CBD_E_INVALID, "graph: null array");
+  const int32_t *row = desc->row_offsets;
+  if (row[0] != 0 || row[S] != A) return fail(CBD_E_INVALID, "graph: row_offsets must span [0, num_arcs]");
+  for (int32_t s = 0; s < S; ++s)
+    if (row[s + 1] < row[s]) return fail(CBD_E_INVALID, "graph: row_offsets not monotone");
+  for (int32_t a = 0; a < A; ++a) {
+    if (desc->dst[a] < 0 || desc->dst[a] >= S) return fail(CBD_E_INVALID, "graph: dst out of range");
+    if (desc->ilabel[a] < 0 || desc->ilabel[a] > P) return fail(CBD_E_INVALID, "graph: ilabel out of range");
+    if (desc->olabel[a] < 0) return fail(CBD_E_INVALID, "graph: negative olabel");
+    if (!std::isfinite(desc->weight[a])) return fail(CBD_E_INVALID, "graph: non-finite weight");
+  }
+  cbd_graph *g = new (std::nothrow) cbd_graph();
+  if (!g) return fail(CBD_E_NOMEM, "graph: host allocation");
+  g->S = S; g->A = A; g->P = P; g->start = desc->start_state;
+  if (hipGetDevice(&g->device) != hipSuccess) { delete g; return fail(CBD_E_HIP, "hipGetDevice failed"); }
+  // library order: per state, emitting arcs first, then epsilon-input arcs, each in the caller's order
+  std::vector<int2> off2((size_t)S + 1);
+  std::vector<cbd::ArcRec> arcs((size_t)std::max(A, 1));
+  g->pub2int.resize((size_t)std::max(A, 1));
+  g->int2pub.resize((size_t)std::max(A, 1));
+  std::vector<uint8_t> has_eps((size_t)S, 0);
+  int32_t k = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    off2[s].x = k;
+    for (int32_t a = row[s]; a < row[s + 1]; ++a)
+      if (desc->ilabel[a] != 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; }
+    off2[s].y = k;
+    for (int32_t a = row[s]; a < row[s + 1]; ++a)
+      if (desc->ilabel[a] == 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; has_eps[s] = 1; }
+  }
+  off2[S].x = k; off2[S].y = k;
+  for (int32_t i = 0; i < A; ++i) {
+    int32_t a = g->int2pub[i];
+    cbd::ArcRec r;
+    r.dst = desc->dst[a];
+    r.weight = desc->weight[a];
+    r.meta = (uint32_t)desc->ilabel[a] | (has_eps[desc->dst[a]] ? cbd::kMetaDstHasEps : 0u);
+    r.olabel = desc->olabel[a];
+    arcs[i] = r;
+  }
+#define GCHK(expr)                                                                     \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      cbd_graph_free(g);                                                               \
+      return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));       \
+    }                                                                                  \
+  } while (0)
+  GCHK(dmalloc(&g->d_off2, (size_t)S + 1, &g->bytes));
+  GCHK(dmalloc(&g->d_arcs, (size_t)A, &g->bytes));
+  GCHK(dmalloc(&g->d_int2pub, (size_t)A, &g->bytes));
+  GCHK(hipMemcpy(g->d_off2, off2.data(), sizeof(int2) * ((size_t)S + 1), hipMemcpyHostToDevice));
+  if (A > 0) {
+    GCHK(hipMemcpy(g->d_arcs, arcs.data(), sizeof(cbd::ArcRec) * (size_t)A, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_int2pub, g->int2pub.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
+  }
+  if (desc->final_cost) {
+    GCHK(dmalloc(&g->d_final, (size_t)S, &g->bytes));
+    GCHK(hipMemcpy(g->d_final, desc->final_cost, sizeof(float) * (size_t)S, hipMemcpyHostToDevice));
+  }
+#undef GCHK
+  *out = g;
+  return CBD_OK;
+}
+
+int32_t cbd_graph_free(cbd_graph *g) {
+  if (!g) return CBD_OK;
+  if (g->d_off2) (void)hipFree(g->d_off2);
+  if (g->d_arcs) (void)hipFree(g->d_arcs);
+  if (g->d_int2pub) (void)hipFree(g->d_int2pub);
+  if (g->d_final) (void)hipFree(g->d_final);
+  delete g;
+  return CBD_OK;
+}
+
+int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_stream, cbd_decoder **out) {
+  if (!g || !cfg || !out) return fail(CBD_E_INVALID, "decoder: null argument");
+  if (cfg->num_channels < 1) return fail(CBD_E_INVALID, "decoder: num_channels < 1");
+  if (!(cfg->beam >= 0.0f)) return fail(CBD_E_INVALID, "decoder: beam must be >= 0");
+  if (cfg->max_active < 0 || cfg->max_frames < 1 || cfg->max_context_arcs < 0)
+    return fail(CBD_E_INVALID, "decoder: negative size");
+  if (cfg->lookup_mode < 0 || cfg->lookup_mode > 1) return fail(CBD_E_INVALID, "decoder: lookup_mode");
+  if (cfg->hash_capacity_log2 < 6 || cfg->hash_capacity_log2 > 24)
+    return fail(CBD_E_INVALID, "decoder: hash_capacity_log2 must be in [6, 24]");
+  if (cfg->table_location < 0 || cfg->table_location > 2) return fail(CBD_E_INVALID, "decoder: table_location");
+  cbd_decoder *d = new (std::nothrow) cbd_decoder();
+  if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
+  d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
+  if (d->cfg.max_eps_iters <= 0) d->cfg.max_eps_iters = 64;
+  d->C = cfg->num_channels;
+  d->log_h = cfg->hash_capacity_log2;
+  const int64_t H = (int64_t)1 << d->log_h;
+  d->tok_cap = (int32_t)(H / 2);
+  d->log_cap = (int32_t)H;
+  int64_t rpf = cfg->records_per_frame > 0 ? cfg->records_per_frame : d->tok_cap;
+  int64_t bp = rpf * ((int64_t)cfg->max_frames + 1) + d->tok_cap;
+  if (bp > 0x7FFFFFF0) { delete d; return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel"); }
+  d->bp_cap = (int32_t)bp;
+  d->max_ctx = std::max(cfg->max_context_arcs, 1);
+  d->ctx_lds_cap = std::min((d->max_ctx + 15) / 16 * 16, 4096);
+
+#define DCHK(expr)                                                                     \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      cbd_decoder_free(d);                                                             \
+      return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));       \
+    }                                                                                  \
+  } while (0)
+  DCHK(hipSetDevice(g->device));
+  int lds_limit = 0, n_cu = 0;
+  DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
+  DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
+  cbd::LdsLayout with = cbd::make_layout(g->P, d->ctx_lds_cap, d->log_h, d->tok_cap, true);
+  cbd::LdsLayout without = cbd::make_layout(g->P, d->ctx_lds_cap, d->log_h, d->tok_cap, false);
+  if (cfg->table_location == 1 && (int64_t)with.total > lds_limit) {
+    delete d;
+    return fail(CBD_E_INVALID, "decoder: tables of this capacity do not fit LDS");
+  }
+  if ((int64_t)without.total > lds_limit) {
+    delete d;
+    return fail(CBD_E_INVALID, "decoder: log-likelihood row and context do not fit LDS");
+  }
+  d->lds_tables = cfg->table_location == 1 || (cfg->table_location == 0 && (int64_t)with.total <= lds_limit);
+  d->lds_bytes = d->lds_tables ? with.total : without.total;
+  // workgroup size: the more channels share a compute unit, the smaller the groups
+  {
+    int per_cu = (d->C + std::max(n_cu, 1) - 1) / std::max(n_cu, 1);
+    int by_lds = std::max(1, lds_limit / (int)std::max<uint32_t>(d->lds_bytes, 1));
+    int resident = std::min(per_cu, by_lds);
+    d->block = resident >= 4 ? 256 : (resident >= 2 ? 512 : 1024);
+    const char *env = getenv("CBD_BLOCK");
+    if (env) {
+      int b = atoi(env);
+      if (b == 256 || b == 512 || b == 1024) d->block = b;
+    }
+  }
+  DCHK(set_attr(d->lds_tables, d->block, d->lds_bytes));
+
+  const size_t C = (size_t)d->C;
+  DCHK(dmalloc(&d->d_chan, C, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_state, C * d->tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_cost, C * d->tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_bp, C * (size_t)d->bp_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_log, C * (size_t)d->log_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_ctx, C * (size_t)d->max_ctx, &d->bytes));
+  if (!d->lds_tables) {
+    DCHK(dmalloc(&d->d_hkey, C * (size_t)H, &d->bytes));
+    DCHK(dmalloc(&d->d_hval, C * (size_t)H, &d->bytes));
+    DCHK(dmalloc(&d->d_haux, C * (size_t)H, &d->bytes));
+    size_t n = C * (size_t)H;
+    hipLaunchKernelGGL(cbd::init_tables_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, d->stream,
+                       d->d_hkey, d->d_hval, n);
+    DCHK(hipGetLastError());
+  }
+  hipLaunchKernelGGL(cbd::init_chan_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, d->stream, d->d_chan,
+                     d->C);
+  DCHK(hipGetLastError());
+  DCHK(d->ids.init(sizeof(int32_t) * C));
+  // context staging: [channels n][list offsets n+1][offsets n][lists ...]
+  DCHK(d->ctxs.init(sizeof(int32_t) * (C * 3 + 1 + C * (size_t)d->max_ctx)));
+  DCHK(hipStreamSynchronize(d->stream));
+#undef DCHK
+  *out = d;
+  return CBD_OK;
+}
+
+int32_t cbd_decoder_free(cbd_decoder *d) {
+  if (!d) return CBD_OK;
+  (void)hipStreamSynchronize(d->stream);
+  void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_bp, d->d_log, d->d_ctx, d->d_hkey, d->d_hval,
+                  d->d_haux, d->d_out_arcs, d->d_out_words, d->d_out_meta};
+  for (void *p : ptrs)
+    if (p) (void)hipFree(p);
+  d->ids.destroy();
+  d->ctxs.destroy();
+  delete d;
+  return CBD_OK;
+}
+
+int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *lds_bytes, int32_t *block_threads,
+                         int32_t *tables_in_lds) {
+  if (!d) return fail(CBD_E_INVALID, "info: null decoder");
+  if (device_bytes) *device_bytes = (int64_t)d->bytes;
+  if (lds_bytes) *lds_bytes = (int32_t)d->lds_bytes;
+  if (block_threads) *block_threads = d->block;
+  if (tables_in_lds) *tables_in_lds = d->lds_tables ? 1 : 0;
+  return CBD_OK;
+}
+
+int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
+  if (!d) return fail(CBD_E_INVALID, "reset: null decoder");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  AdvanceParams p = base_params(d);
+  p.chan_ids = dev; p.loglikes = nullptr; p.channel_stride = 0; p.n_frames = 0; p.do_reset = 1;
+  HIPCHK(launch_advance(d, p, n));
+  HIPCHK(d->ids.release(slot, d->stream));
+  return CBD_OK;
+}
+
+int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const int32_t *arc_idx,
+                         const int32_t *list_offsets, const float *offsets) {
+  if (!d || !channels || !list_offsets || !offsets) return fail(CBD_E_INVALID, "set_contexts: null argument");
+  if (n_channels <= 0 || n_channels > d->C) return fail(CBD_E_INVALID, "set_contexts: bad channel count");
+  if (list_offsets[0] != 0) return fail(CBD_E_INVALID, "set_contexts: list_offsets[0] != 0");
+  // validate everything before anything changes
+  d->h_tmp.assign((size_t)d->C, 0);
+  for (int32_t i = 0; i < n_channels; ++i) {
+    int32_t c = channels[i];
+    if (c < 0 || c >= d->C) return fail(CBD_E_INVALID, "set_contexts: channel out of range");
+    if (d->h_tmp[c]) return fail(CBD_E_INVALID, "set_contexts: duplicate channel");
+    d->h_tmp[c] = 1;
+    if (list_offsets[i + 1] < list_offsets[i]) return fail(CBD_E_INVALID, "set_contexts: list_offsets not monotone");
+    if (!std::isfinite(offsets[i])) return fail(CBD_E_INVALID, "set_contexts: non-finite offset");
+  }
+  const int32_t total = list_offsets[n_channels];
+  if (total > 0 && !arc_idx) return fail(CBD_E_INVALID, "set_contexts: null list");
+  for (int32_t k = 0; k < total; ++k)
+    if (arc_idx[k] < 0 || arc_idx[k] >= d->g->A) return fail(CBD_E_INVALID, "set_contexts: arc index out of range");
+  // sort + de-duplicate in the library's arc order (the list is a set)
+  std::vector<int32_t> packed;
+  packed.reserve((size_t)total);
+  std::vector<int32_t> new_off((size_t)n_channels + 1, 0);
+  std::vector<int32_t> one;
+  for (int32_t i = 0; i < n_channels; ++i) {
+    one.clear();
+    for (int32_t k = list_offsets[i]; k < list_offsets[i + 1]; ++k) one.push_back(d->g->pub2int[arc_idx[k]]);
+    std::sort(one.begin(), one.end());
+    one.erase(std::unique(one.begin(), one.end()), one.end());
+    if ((int32_t)one.size() > d->cfg.max_context_arcs)
+      return fail(CBD_E_INVALID, "set_contexts: more than max_context_arcs distinct arcs");
+    packed.insert(packed.end(), one.begin(), one.end());
+    new_off[i + 1] = (int32_t)packed.size();
+  }
+  int slot = 0;
+  HIPCHK(d->ctxs.acquire(&slot));
+  int32_t *h = (int32_t *)d->ctxs.host[slot];
+  const size_t n = (size_t)n_channels;
+  memcpy(h, channels, sizeof(int32_t) * n);
+  memcpy(h + n, new_off.data(), sizeof(int32_t) * (n + 1));
+  memcpy(h + 2 * n + 1, offsets, sizeof(float) * n);
+  if (!packed.empty()) memcpy(h + 3 * n + 1, packed.data(), sizeof(int32_t) * packed.size());
+  HIPCHK(d->ctxs.upload(slot, sizeof(int32_t) * (3 * n + 1 + packed.size()), d->stream));
+  const int32_t *dv = (const int32_t *)d->ctxs.dev[slot];
+  hipLaunchKernelGGL(cbd::scatter_contexts_kernel, dim3((unsigned)n_channels), dim3(256), 0, d->stream, dv, dv + n,
+                     (const float *)(dv + 2 * n + 1), dv + 3 * n + 1, d->d_ctx, d->max_ctx, d->d_chan);
+  HIPCHK(hipGetLastError());
+  HIPCHK(d->ctxs.release(slot, d->stream));
+  return CBD_OK;
+}
+
+int32_t cbd_set_context(cbd_decoder *d, int32_t channel, const int32_t *arc_idx, int32_t n, float offset) {
+  if (n < 0) return fail(CBD_E_INVALID, "set_context: negative length");
+  int32_t lo[2] = {0, n};
+  return cbd_set_contexts(d, &channel, 1, arc_idx, lo, &offset);
+}
+
+int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const float *loglikes,
+                    int64_t channel_stride, int32_t n_frames) {
+  if (!d) return fail(CBD_E_INVALID, "advance: null decoder");
+  if (n_frames < 0) return fail(CBD_E_INVALID, "advance: negative frame count");
+  if (n_frames == 0) return CBD_OK;
+  if (!loglikes) return fail(CBD_E_INVALID, "advance: null log-likelihoods");
+  if (n_channels > 1 && channel_stride < (int64_t)n_frames * d->g->P)
+    return fail(CBD_E_INVALID, "advance: channel_stride shorter than a channel's rows");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n_channels, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  AdvanceParams p = base_params(d);
+  p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
+  HIPCHK(launch_advance(d, p, n_channels));
+  HIPCHK(d->ids.release(slot, d->stream));
+  return CBD_OK;
+}
+
+int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                       int32_t *status) {
+  if (!d || !words || !n_words || !n_arcs || !cost || !status) return fail(CBD_E_INVALID, "best_paths: null argument");
+  if (capacity < 1) return fail(CBD_E_INVALID, "best_paths: capacity < 1");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  if (d->out_capacity < capacity || d->out_rows < n) {
+    HIPCHK(hipStreamSynchronize(d->stream));
+    if (d->d_out_arcs) (void)hipFree(d->d_out_arcs);
+    if (d->d_out_words) (void)hipFree(d->d_out_words);
+    if (d->d_out_meta) (void)hipFree(d->d_out_meta);
+    d->d_out_arcs = d->d_out_words = d->d_out_meta = nullptr;
+    int32_t rows = std::max(n, d->out_rows), cap = std::max(capacity, d->out_capacity);
+    HIPCHK(dmalloc(&d->d_out_arcs, (size_t)rows * cap, nullptr));
+    HIPCHK(dmalloc(&d->d_out_words, (size_t)rows * cap, nullptr));
+    HIPCHK(dmalloc(&d->d_out_meta, (size_t)rows * 4, nullptr));
+    d->out_rows = rows; d->out_capacity = cap;
+  }
+  cbd::BestParams bp{};
+  bp.chan = d->d_chan; bp.chan_ids = dev; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost; bp.bp = d->d_bp;
+  bp.arcs = d->g->d_arcs; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
+  bp.tok_cap = d->tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
+  bp.out_arcs = d->d_out_arcs; bp.out_words = d->d_out_words; bp.out_meta = d->d_out_meta;
+  hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
+  HIPCHK(hipGetLastError());
+  HIPCHK(d->ids.release(slot, d->stream));
+  std::vector<int32_t> meta((size_t)n * 4);
+  HIPCHK(hipMemcpyAsync(meta.data(), d->d_out_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, d->stream));
+  HIPCHK(hipMemcpyAsync(words, d->d_out_words, sizeof(int32_t) * (size_t)n * capacity, hipMemcpyDeviceToHost,
+                        d->stream));
+  if (arcs)
+    HIPCHK(hipMemcpyAsync(arcs, d->d_out_arcs, sizeof(int32_t) * (size_t)n * capacity, hipMemcpyDeviceToHost,
+                          d->stream));
+  HIPCHK(hipStreamSynchronize(d->stream));
+  for (int32_t i = 0; i < n; ++i) {
+    status[i] = meta[(size_t)i * 4 + 0];
+    n_arcs[i] = meta[(size_t)i * 4 + 1];
+    n_words[i] = meta[(size_t)i * 4 + 2];
+    uint32_t bits = (uint32_t)meta[(size_t)i * 4 + 3];
+    memcpy(&cost[i], &bits, 4);
+  }
+  return CBD_OK;
+}
+
+int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_t *words, int32_t *arcs,
+                      int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost) {
+  if (!n_words || !n_arcs || !cost) return fail(CBD_E_INVALID, "best_path: null argument");
+  int32_t nw = 0, na = 0, st = 0;
+  float c = 0.0f;
+  int32_t rc = cbd_best_paths(d, &channel, 1, use_final, words, arcs, capacity, &nw, &na, &c, &st);
+  if (rc != CBD_OK) return rc;
+  if (st == CBD_OK || st == CBD_E_BUFFER) { *n_words = nw; *n_arcs = na; *cost = c; }
+  return st;
+}
+
+int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *costs, int32_t *arcs,
+                       int32_t capacity, int32_t *n) {
+  if (!d || !n) return fail(CBD_E_INVALID, "get_tokens: null argument");
+  if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_tokens: channel out of range");
+  HIPCHK(hipStreamSynchronize(d->stream));
+  cbd::ChanState cs;
+  HIPCHK(hipMemcpy(&cs, d->d_chan + channel, sizeof(cs), hipMemcpyDeviceToHost));
+  if (cs.status != CBD_OK) { *n = 0; return cs.status; }
+  const int32_t nt = cs.n_tok;
+  std::vector<int32_t> st((size_t)std::max(nt, 1));
+  std::vector<float> co((size_t)std::max(nt, 1));
+  std::vector<int2> bp((size_t)std::max(nt, 1));
+  if (nt > 0) {
+    HIPCHK(hipMemcpy(st.data(), d->d_tok_state + (size_t)channel * d->tok_cap, sizeof(int32_t) * nt,
+                     hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(co.data(), d->d_tok_cost + (size_t)channel * d->tok_cap, sizeof(float) * nt,
+                     hipMemcpyDeviceToHost));
+    HIPCHK(hipMemcpy(bp.data(), d->d_bp + (size_t)channel * d->bp_cap + cs.frame_base, sizeof(int2) * nt,
+                     hipMemcpyDeviceToHost));
+  }
+  int32_t k = 0;
+  for (int32_t i = 0; i < nt; ++i) {
+    if (st[i] < 0) continue;
+    if (k < capacity && states && costs && arcs) {
+      states[k] = st[i];
+      costs[k] = co[i];
+      arcs[k] = (uint32_t)bp[i].x == cbd::kArcNone ? -1 : d->g->int2pub[bp[i].x];
+    }
+    ++k;
+  }
+  *n = k;
+  return CBD_OK;
+}
+
+int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
+  if (!d || !out) return fail(CBD_E_INVALID, "get_stats: null argument");
+  if (channel < -1 || channel >= d->C) return fail(CBD_E_INVALID, "get_stats: channel out of range");
+  HIPCHK(hipStreamSynchronize(d->stream));
+  const int32_t lo = channel < 0 ? 0 : channel, hi = channel < 0 ? d->C : channel + 1;
+  std::vector<cbd::ChanState> cs((size_t)(hi - lo));
+  HIPCHK(hipMemcpy(cs.data(), d->d_chan + lo, sizeof(cbd::ChanState) * cs.size(), hipMemcpyDeviceToHost));
+  cbd_stats s{};
+  for (const cbd::ChanState &c : cs) {
+    s.frames += c.frames; s.active_tokens += c.active_tokens; s.emit_arcs += c.emit_arcs; s.eps_arcs += c.eps_arcs;
+    s.candidates += c.candidates; s.improvements += c.improvements; s.tokens += c.tokens;
+    s.eps_rounds += c.eps_rounds; s.records += c.n_rec;
+    if (s.status == CBD_OK && c.status != CBD_OK) s.status = c.status;
+    s.max_tokens = std::max(s.max_tokens, c.max_tokens);
+  }
+  *out = s;
+  return CBD_OK;
+}
+
+int32_t cbd_synchronize(cbd_decoder *d) {
+  if (!d) return fail(CBD_E_INVALID, "synchronize: null decoder");
+  HIPCHK(hipStreamSynchronize(d->stream));
+  return CBD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+"""CPU-side checks of the boundary: the library loads, exports what the header declares,
+and rejects bad arguments on the host before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cbd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cbd_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary_calls():
+    names = declared_functions()
+    for must in ("cbd_graph_load", "cbd_set_context", "cbd_advance", "cbd_best_path"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2306_15685_amd import binding
+    assert os.path.exists(binding.LIB_PATH), "libcbdec.so not built (run paper_2306_15685_amd/build.py)"
+    lib = C.CDLL(binding.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in cbd.h but not exported"
+    assert set(binding.EXPORTS) == set(declared_functions())
+
+
+def test_strerror_and_invalid_graphs_are_rejected_on_host():
+    from paper_2306_15685_amd import binding as B
+    assert B.cbd_strerror(0) == "ok"
+    assert "capacity" in B.cbd_strerror(B.CBD_E_CAPACITY)
+    row = np.array([0, 1, 2], np.int32)
+    one = np.array([1, 0], np.int32)
+    w = np.array([0.5, 0.5], np.float32)
+    bad = [
+        dict(num_states=2, row_offsets=np.array([0, 2, 1], np.int32)),          # not monotone / wrong span
+        dict(num_states=2, dst=np.array([1, 5], np.int32)),                      # dst out of range
+        dict(num_states=2, ilabel=np.array([1, 9], np.int32)),                   # ilabel > num_pdfs
+        dict(num_states=2, weight=np.array([0.5, np.inf], np.float32)),          # non-finite weight
+        dict(num_states=2, start_state=7),
+    ]
+    for kw in bad:
+        args = dict(num_states=2, num_pdfs=1, start_state=0, row_offsets=row, dst=one, ilabel=np.array([1, 1], np.int32),
+                    olabel=np.array([0, 0], np.int32), weight=w)
+        args.update(kw)
+        with pytest.raises(B.CbdError) as ei:
+            B.cbd_graph_load(**args)
+        assert ei.value.status == B.CBD_E_INVALID
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2306_15685_amd import binding as B
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libcbdec.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()
+
+
+def test_product_code_does_not_touch_the_checker():
+    pkg = os.path.join(ROOT, "paper_2306_15685_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the checker"
