@@ -601,10 +601,13 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         sh->frame_base = sh->n_rec;
         sh->n_rec += sh->n_claim;
         sh->best = ord2f(sh->best_ord);
-        if (f >= 0) st_frames++;
+        if (f >= 0) {  // the table made at reset is not a decoded frame
+          st_frames++;
+          st_tok += sh->n_live;
+          if (sh->n_live > st_maxtok) st_maxtok = sh->n_live;
+        }
         st_active += sh->c_active; st_emit += sh->c_emit; st_eps += sh->c_eps; st_cand += sh->c_cand;
-        st_impr += sh->log_n; st_tok += sh->n_live; st_rounds += sh->rounds;
-        if (sh->n_live > st_maxtok) st_maxtok = sh->n_live;
+        st_impr += sh->log_n; st_rounds += sh->rounds;
         sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
       }
     }
