@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the biased multi-channel beam-search decoder on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic workload: context upload,
+utterance start, every chunk's advance, partial best paths where the workload asks for
+them, final best paths.  Inputs are resident in HBM before the timed region starts.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(inp, n_channels, budget_frames):
+    """The CPU checker, as it stands, on a bounded sample of the same workload: the first
+    n_channels channels of segment 0, all host cores, one channel per task."""
+    from oracle import OracleGraph, OracleChannel
+    w, g = inp.w, inp.g
+    cores = min(len(os.sched_getaffinity(0)), n_channels)
+    frames = min(w.frames, budget_frames)
+    og = OracleGraph.from_graph(g)
+    Lh = inp.loglikes[0][:n_channels, :frames].cpu().numpy()
+    lists, offs = inp.contexts[0]
+    chans = []
+    for c in range(n_channels):
+        ch = OracleChannel(og, w.beam, w.max_active)
+        ch.set_context(lists[c], offs[c])
+        chans.append(ch)
+
+    def work(c):
+        ch = chans[c]
+        ch.reset()
+        t = 0
+        while t < frames:
+            n = min(w.chunk, frames - t)
+            ch.advance(Lh[c, t:t + n])
+            t += n
+            if w.partial_every_chunk:
+                ch.best_path(False)
+        ch.best_path(True)
+        return ch.emit_arcs
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        arcs = list(ex.map(work, range(n_channels)))
+    dt = time.perf_counter() - t0
+    audio = n_channels * frames * 0.030
+    return {"value": audio / dt, "unit": "x real time (RTFx)", "cores": cores, "kind": "oracle",
+            "sample": f"{n_channels} of {w.channels} channels x {frames} of {w.frames} frames of segment 0, "
+                      f"one channel per task on {cores} threads, {dt:.2f} s",
+            "emit_arcs_per_s": sum(arcs) / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "dynamic", "stress"])
+    ap.add_argument("--channels", type=int, default=0, help="override the channel count (smaller trial runs)")
+    ap.add_argument("--hash-log2", type=int, default=0)
+    ap.add_argument("--table-location", type=int, default=0)
+    ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-channels", type=int, default=32)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build decodes on one GPU only; channels are independent, so more GPUs would each "
+            "hold the graph and a share of the channels (no exchange). Run with --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_2306_15685_amd import synth, runner
+    from paper_2306_15685_amd import binding as B
+
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    if args.channels:
+        w = synth.scaled(w, channels=args.channels)
+    t0 = time.perf_counter()
+    inp = runner.make_inputs(w)
+    torch.cuda.synchronize()
+    log(f"inputs: graph {inp.g.num_states} states {inp.g.num_arcs} arcs, {w.channels} channels x "
+        f"{w.segments} x {w.frames} frames x {w.num_pdfs} pdfs in {time.perf_counter() - t0:.1f} s")
+    sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
+                          biased=not args.unbiased)
+    info = B.cbd_decoder_info(sess.dh)
+    log(f"decoder: {info}")
+
+    for _ in range(max(args.warmup, 0)):
+        sess.step()
+    torch.cuda.synchronize()
+    # one untimed pass with counters (they do not change between passes: the decode is deterministic)
+    sess.step(collect_stats=True)
+    st = sess.step_stats
+    if st["status"] != 0:
+        log(f"bench.py: a channel ended in error state {st['status']} ({B.cbd_strerror(st['status'])})")
+        sys.exit(1)
+
+    sess.time_kernels = True
+    sess.advance_events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sess.step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kms = sess.kernel_ms()
+    sess.time_kernels = False
+
+    ms_per_step = wall / args.steps * 1e3
+    audio_s = w.channels * w.segments * w.frames * synth.FRAME_SHIFT_S
+    rtfx = audio_s / (wall / args.steps)
+    arcs = st["emit_arcs"] + st["eps_arcs"]
+    launches_per_step = len(kms) // args.steps
+    ctx_ints = sum(int(sum(len(x) for x in lists)) for lists, _ in inp.contexts) * ((w.frames + w.chunk - 1) // w.chunk)
+    alg_bytes_step = runner.algorithmic_bytes(st, w, ctx_ints if not args.unbiased else 0)
+    avg_launch_ms = float(np.mean(kms))
+    achieved = alg_bytes_step / launches_per_step / (avg_launch_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "RTFx and arcs expanded/sec (1 MI355X, N channels) + % peak HBM BW",
+        "value": rtfx, "unit": "x real time (RTFx)", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "channels": w.channels, "segments": w.segments, "frames": w.frames,
+                   "chunk": w.chunk, "states": inp.g.num_states, "arcs": inp.g.num_arcs, "pdfs": w.num_pdfs,
+                   "beam": w.beam, "max_active": w.max_active, "biased": not args.unbiased,
+                   "lookup_mode": w.lookup_mode, "tables_in_lds": info["tables_in_lds"],
+                   "block_threads": info["block_threads"]},
+        "arcs_per_s": arcs / (wall / args.steps),
+        "frames_per_s": w.channels * w.segments * w.frames / (wall / args.steps),
+        "tokens_per_frame": st["tokens"] / max(st["frames"], 1),
+        "counters": {k: int(v) for k, v in st.items()},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "advance_kernel", "launches_per_step": launches_per_step,
+                     "avg_launch_ms": avg_launch_ms, "algorithmic_bytes_per_launch": alg_bytes_step / launches_per_step,
+                     "kernel_time_share": sum(kms) / (wall * 1e3)},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp, min(args.cpu_channels, w.channels), w.frames)
+    sess.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

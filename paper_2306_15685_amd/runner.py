@@ -1,0 +1,152 @@
+"""Drives a synthetic workload through the HIP library: the launch configuration that
+bench.py times and that the full-size parity tests check.
+
+torch is used for device memory, streams and events only.
+"""
+from __future__ import annotations
+
+import time
+from dataclasses import dataclass, field
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+
+from . import binding as B
+from . import synth
+
+
+def default_hash_log2(w: synth.Workload) -> int:
+    """Table size: the LDS tables hold 2048 tokens per frame at 12, which the beam-limited
+    workloads here stay well below; bigger tables move to device memory."""
+    return 12
+
+
+@dataclass
+class Inputs:
+    w: synth.Workload
+    g: synth.Graph
+    loglikes: list  # per segment: device tensor [C, frames, P]
+    contexts: list  # per segment: (lists, offsets)
+
+
+def make_inputs(w: synth.Workload, g: Optional[synth.Graph] = None, device: str = "cuda") -> Inputs:
+    g = g if g is not None else synth.graph_for(w)
+    L = [synth.make_loglikes(w.channels, w.frames, w.num_pdfs, w.sigma, seed_stream=(w.config_id, s), device=device)
+         for s in range(w.segments)]
+    ctx = [synth.make_contexts(w, g, segment=s) for s in range(w.segments)]
+    return Inputs(w, g, L, ctx)
+
+
+class Session:
+    """A decoder sized for a workload, bound to torch's current stream."""
+
+    def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
+                 records_per_frame: int = 0, graph_handle=None, biased: bool = True):
+        import torch
+        self.torch = torch
+        self.inp = inp
+        w, g = inp.w, inp.g
+        self.w = w
+        self.biased = biased
+        self.own_graph = graph_handle is None
+        self.gh = graph_handle if graph_handle is not None else B.cbd_graph_load(
+            g.num_states, g.num_pdfs, g.start_state, g.row_offsets, g.dst, g.ilabel, g.olabel, g.weight, g.final_cost)
+        self.stream = torch.cuda.current_stream()
+        self.dh = B.cbd_decoder_create(
+            self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
+            hash_log2 if hash_log2 is not None else default_hash_log2(w), 0, records_per_frame, table_location,
+            hip_stream=self.stream.cuda_stream)
+        self.all = np.arange(w.channels, dtype=np.int32)
+        self.capacity = 4 * w.frames + 64
+        self.advance_events: List = []
+        self.time_kernels = False
+        self.on_partial: Optional[Callable] = None  # called with (segment, frames_done, best_paths result)
+        self.partials: list = []
+
+    def close(self):
+        if self.dh is not None:
+            B.cbd_decoder_free(self.dh)
+            self.dh = None
+        if self.own_graph and self.gh is not None:
+            B.cbd_graph_free(self.gh)
+            self.gh = None
+
+    def _advance(self, L, t0, n):
+        C, T, P = L.shape
+        if self.time_kernels:
+            e0 = self.torch.cuda.Event(enable_timing=True)
+            e1 = self.torch.cuda.Event(enable_timing=True)
+            e0.record(self.stream)
+        B.cbd_advance(self.dh, self.all, L.data_ptr() + 4 * t0 * P, T * P, n)
+        if self.time_kernels:
+            e1.record(self.stream)
+            self.advance_events.append((e0, e1))
+
+    def step(self, keep_results: bool = False, collect_stats: bool = False):
+        """One pass of the workload: per segment, upload contexts, start the utterances, advance
+        chunk by chunk (with a partial best path per chunk where the workload says so), read the
+        final best paths.  With collect_stats the per-utterance counters are summed over the
+        segments into self.step_stats (adds a synchronisation per segment)."""
+        w = self.w
+        finals = []
+        self.step_stats = None
+        for s in range(w.segments):
+            lists, offs = self.inp.contexts[s]
+            if self.biased:
+                B.cbd_set_contexts(self.dh, self.all, lists, offs)
+            elif s == 0:
+                B.cbd_set_contexts(self.dh, self.all, [np.zeros(0, np.int32)] * w.channels,
+                                   np.zeros(w.channels, np.float32))
+            B.cbd_reset_channels(self.dh, self.all)
+            L = self.inp.loglikes[s]
+            t = 0
+            while t < w.frames:
+                n = min(w.chunk, w.frames - t)
+                self._advance(L, t, n)
+                t += n
+                if w.partial_every_chunk and t < w.frames:
+                    r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
+                    if keep_results:
+                        self.partials.append((s, t, r))
+            r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results)
+            if keep_results:
+                finals.append(r)
+            if collect_stats:
+                st = self.stats(-1)
+                if self.step_stats is None:
+                    self.step_stats = dict(st)
+                else:
+                    for k, v in st.items():
+                        if k == "status":
+                            self.step_stats[k] = self.step_stats[k] or v
+                        elif k == "max_tokens":
+                            self.step_stats[k] = max(self.step_stats[k], v)
+                        else:
+                            self.step_stats[k] += v
+        return finals
+
+    def stats(self, c: int = -1) -> Dict:
+        return B.cbd_get_stats(self.dh, c)
+
+    def kernel_ms(self) -> List[float]:
+        self.torch.cuda.synchronize()
+        out = [a.elapsed_time(b) for a, b in self.advance_events]
+        self.advance_events = []
+        return out
+
+
+# Algorithmic bytes the method must move, per unit of work (HBM side).
+BYTES_PER_ACTIVE_TOKEN = 16     # token (state, cost) + the two row offsets of its state
+BYTES_PER_ARC = 12              # dst, ilabel, weight of an expanded arc (emitting or epsilon)
+BYTES_PER_CANDIDATE = 24        # key probe + 64-bit read-modify-write of the state table
+BYTES_PER_TOKEN = 44            # table read, token write, back-pointer write, prune re-read, slot clear
+
+
+def algorithmic_bytes(st: Dict, w: synth.Workload, ctx_ints: int = 0) -> int:
+    """Bytes implied by the counters of cbd_get_stats for the frames they cover."""
+    return (BYTES_PER_ACTIVE_TOKEN * st["active_tokens"]
+            + BYTES_PER_ARC * (st["emit_arcs"] + st["eps_arcs"])
+            + BYTES_PER_CANDIDATE * st["candidates"]
+            + BYTES_PER_TOKEN * st["tokens"]
+            + 4 * w.num_pdfs * st["frames"]
+            + 4 * ctx_ints)
