@@ -76,6 +76,7 @@ def main():
     ap.add_argument("--channels", type=int, default=0, help="override the channel count (smaller trial runs)")
     ap.add_argument("--hash-log2", type=int, default=0)
     ap.add_argument("--table-location", type=int, default=0)
+    ap.add_argument("--lds-token-cap", type=int, default=0)
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-channels", type=int, default=32)
@@ -99,7 +100,7 @@ def main():
     log(f"inputs: graph {inp.g.num_states} states {inp.g.num_arcs} arcs, {w.channels} channels x "
         f"{w.segments} x {w.frames} frames x {w.num_pdfs} pdfs in {time.perf_counter() - t0:.1f} s")
     sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
-                          biased=not args.unbiased)
+                          biased=not args.unbiased, lds_token_cap=args.lds_token_cap)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -142,8 +143,8 @@ def main():
         "config": {"workload": w.name, "channels": w.channels, "segments": w.segments, "frames": w.frames,
                    "chunk": w.chunk, "states": inp.g.num_states, "arcs": inp.g.num_arcs, "pdfs": w.num_pdfs,
                    "beam": w.beam, "max_active": w.max_active, "biased": not args.unbiased,
-                   "lookup_mode": w.lookup_mode, "tables_in_lds": info["tables_in_lds"],
-                   "block_threads": info["block_threads"]},
+                   "lookup_mode": w.lookup_mode, "lds_token_cap": info["lds_token_cap"],
+                   "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"]},
         "arcs_per_s": arcs / (wall / args.steps),
         "frames_per_s": w.channels * w.segments * w.frames / (wall / args.steps),
         "tokens_per_frame": st["tokens"] / max(st["frames"], 1),

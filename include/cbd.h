@@ -67,7 +67,7 @@ typedef struct cbd_decoder cbd_decoder; /* opaque; owns all per-channel device s
 typedef struct cbd_graph_desc {
   int32_t num_states;
   int32_t num_arcs;
-  int32_t num_pdfs;           /* log-likelihood row length */
+  int32_t num_pdfs;           /* log-likelihood row length, at most 65535 */
   int32_t start_state;
   const int32_t *row_offsets; /* [num_states+1]; arcs of state s are [row_offsets[s], row_offsets[s+1]) */
   const int32_t *dst;         /* [num_arcs] next state */
@@ -93,10 +93,13 @@ typedef struct cbd_config {
   int32_t max_frames;         /* frames per utterance the back-pointer buffer is sized for */
   int32_t max_context_arcs;   /* largest context list after de-duplication */
   int32_t lookup_mode;        /* 0 sorted list + binary search (Sec. 4.2); 1 hashed bitmap filter, then the search */
-  int32_t hash_capacity_log2; /* per-channel state table slots = 2^this; a frame may hold at most half as many tokens */
+  int32_t hash_capacity_log2; /* device-memory state table slots per channel = 2^this; a frame may hold at most
+                                 half as many tokens (frames that fit the LDS tables never touch this table) */
   int32_t max_eps_iters;      /* epsilon-closure round limit; 0 = default 64 */
   int32_t records_per_frame;  /* average back-pointer records per frame to reserve; 0 = table capacity / 2 */
-  int32_t table_location;     /* 0 = choose; 1 = token tables in LDS; 2 = token tables in device memory */
+  int32_t table_location;     /* 0 or 1 = LDS tables, frames that outgrow them are redone in device memory;
+                                 2 = device-memory tables only */
+  int32_t lds_token_cap;      /* tokens per frame the LDS tables hold; 0 = as many as fit beside the row */
 } cbd_config;
 
 /*
@@ -184,6 +187,7 @@ typedef struct cbd_stats {
   int64_t tokens;         /* sum over frames of the table size */
   int64_t eps_rounds;     /* closure rounds */
   int64_t records;        /* back-pointer records in use */
+  int64_t slow_frames;    /* frames decoded with the device-memory tables */
   int32_t status;         /* sticky cbd_status of the channel */
   int32_t max_tokens;     /* largest table so far */
 } cbd_stats;
@@ -192,9 +196,10 @@ typedef struct cbd_stats {
  * Synchronises. */
 int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out);
 
-/* Bytes of device memory the decoder holds; LDS bytes and threads per workgroup of the decode kernel. */
+/* Bytes of device memory the decoder holds; LDS bytes and threads per workgroup of the decode kernel;
+ * tokens per frame its LDS tables hold (0 = device-memory tables only).  Any pointer may be NULL. */
 int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *lds_bytes, int32_t *block_threads,
-                         int32_t *tables_in_lds);
+                         int32_t *lds_token_cap);
 
 int32_t cbd_synchronize(cbd_decoder *d);
 

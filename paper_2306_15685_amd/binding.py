@@ -37,14 +37,14 @@ class cbd_config(C.Structure):
     _fields_ = [("num_channels", C.c_int32), ("beam", C.c_float), ("max_active", C.c_int32),
                 ("max_frames", C.c_int32), ("max_context_arcs", C.c_int32), ("lookup_mode", C.c_int32),
                 ("hash_capacity_log2", C.c_int32), ("max_eps_iters", C.c_int32),
-                ("records_per_frame", C.c_int32), ("table_location", C.c_int32)]
+                ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32)]
 
 
 class cbd_stats(C.Structure):
     _fields_ = [("frames", C.c_int64), ("active_tokens", C.c_int64), ("emit_arcs", C.c_int64),
                 ("eps_arcs", C.c_int64), ("candidates", C.c_int64), ("improvements", C.c_int64),
                 ("tokens", C.c_int64), ("eps_rounds", C.c_int64), ("records", C.c_int64),
-                ("status", C.c_int32), ("max_tokens", C.c_int32)]
+                ("slow_frames", C.c_int64), ("status", C.c_int32), ("max_tokens", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -139,11 +139,11 @@ def cbd_graph_free(g):
 
 
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,
-                       hash_capacity_log2=12, max_eps_iters=0, records_per_frame=0, table_location=0,
-                       hip_stream=0):
+                       hash_capacity_log2=14, max_eps_iters=0, records_per_frame=0, table_location=0,
+                       lds_token_cap=0, hip_stream=0):
     cfg = cbd_config(int(num_channels), float(beam), int(max_active), int(max_frames), int(max_context_arcs),
                      int(lookup_mode), int(hash_capacity_log2), int(max_eps_iters), int(records_per_frame),
-                     int(table_location))
+                     int(table_location), int(lds_token_cap))
     h = C.c_void_p()
     _check(lib().cbd_decoder_create(g, C.byref(cfg), C.c_void_p(int(hip_stream)), C.byref(h)), "cbd_decoder_create")
     return h
@@ -241,7 +241,8 @@ def cbd_get_stats(d, channel=-1) -> dict:
 def cbd_decoder_info(d) -> dict:
     b, l, t, i = C.c_int64(0), C.c_int32(0), C.c_int32(0), C.c_int32(0)
     _check(lib().cbd_decoder_info(d, C.byref(b), C.byref(l), C.byref(t), C.byref(i)), "cbd_decoder_info")
-    return {"device_bytes": b.value, "lds_bytes": l.value, "block_threads": t.value, "tables_in_lds": bool(i.value)}
+    return {"device_bytes": b.value, "lds_bytes": l.value, "block_threads": t.value, "lds_token_cap": i.value,
+            "tables_in_lds": i.value > 0}
 
 
 def cbd_synchronize(d):

@@ -95,6 +95,7 @@ struct cbd_graph {
   int2 *d_off2 = nullptr;
   cbd::ArcRec *d_arcs = nullptr;
   int32_t *d_int2pub = nullptr;
+  int32_t *d_olabel = nullptr;
   float *d_final = nullptr;
   std::vector<int32_t> pub2int, int2pub;
   size_t bytes = 0;
@@ -104,19 +105,21 @@ struct cbd_decoder {
   const cbd_graph *g = nullptr;
   cbd_config cfg{};
   hipStream_t stream = nullptr;
-  int32_t C = 0, log_h = 0, tok_cap = 0, log_cap = 0, bp_cap = 0, max_ctx = 0, ctx_lds_cap = 0;
-  bool lds_tables = false;
+  int32_t C = 0, bp_cap = 0, max_ctx = 0, ctx_lds_cap = 0;
+  int32_t lds_tok_cap = 0, lds_slots = 0, lds_log_cap = 0;  // LDS tables (0: unused)
+  int32_t g_tok_cap = 0, g_slots = 0, g_log_cap = 0;        // device-memory tables
   int block = 1024;
   uint32_t lds_bytes = 0;
   cbd::ChanState *d_chan = nullptr;
   int32_t *d_tok_state = nullptr;
   float *d_tok_cost = nullptr;
+  int32_t *d_tok_first = nullptr, *d_tok_eps = nullptr, *d_tok_end = nullptr;
   int2 *d_bp = nullptr;
-  cbd::LogEntry *d_log = nullptr;
+  cbd::LogT<false> *d_log = nullptr;
   int32_t *d_ctx = nullptr;
   uint32_t *d_hkey = nullptr;
   uint64_t *d_hval = nullptr;
-  uint32_t *d_haux = nullptr;
+  uint32_t *d_hidx = nullptr;
   int32_t *d_out_arcs = nullptr, *d_out_words = nullptr, *d_out_meta = nullptr;
   int32_t out_capacity = 0, out_rows = 0;
   StageRing ids;   // channel lists
@@ -129,36 +132,26 @@ namespace {
 
 using cbd::AdvanceParams;
 
-template <bool kLds, int kBlock> hipError_t launch_advance_t(const AdvanceParams &p, int grid, uint32_t lds, hipStream_t st) {
-  hipLaunchKernelGGL((cbd::advance_kernel<kLds, kBlock>), dim3(grid), dim3(kBlock), lds, st, p);
+template <int kBlock> hipError_t launch_advance_t(const AdvanceParams &p, int grid, uint32_t lds, hipStream_t st) {
+  hipLaunchKernelGGL((cbd::advance_kernel<kBlock>), dim3(grid), dim3(kBlock), lds, st, p);
   return hipGetLastError();
 }
 
-template <bool kLds, int kBlock> hipError_t set_attr_t(uint32_t lds) {
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_kernel<kLds, kBlock>),
+template <int kBlock> hipError_t set_attr_t(uint32_t lds) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_kernel<kBlock>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
 }
 
-hipError_t set_attr(bool lds_tables, int block, uint32_t lds) {
-  if (lds_tables) {
-    if (block == 256) return set_attr_t<true, 256>(lds);
-    if (block == 512) return set_attr_t<true, 512>(lds);
-    return set_attr_t<true, 1024>(lds);
-  }
-  if (block == 256) return set_attr_t<false, 256>(lds);
-  if (block == 512) return set_attr_t<false, 512>(lds);
-  return set_attr_t<false, 1024>(lds);
+hipError_t set_attr(int block, uint32_t lds) {
+  if (block == 256) return set_attr_t<256>(lds);
+  if (block == 512) return set_attr_t<512>(lds);
+  return set_attr_t<1024>(lds);
 }
 
 hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {
-  if (d->lds_tables) {
-    if (d->block == 256) return launch_advance_t<true, 256>(p, grid, d->lds_bytes, d->stream);
-    if (d->block == 512) return launch_advance_t<true, 512>(p, grid, d->lds_bytes, d->stream);
-    return launch_advance_t<true, 1024>(p, grid, d->lds_bytes, d->stream);
-  }
-  if (d->block == 256) return launch_advance_t<false, 256>(p, grid, d->lds_bytes, d->stream);
-  if (d->block == 512) return launch_advance_t<false, 512>(p, grid, d->lds_bytes, d->stream);
-  return launch_advance_t<false, 1024>(p, grid, d->lds_bytes, d->stream);
+  if (d->block == 256) return launch_advance_t<256>(p, grid, d->lds_bytes, d->stream);
+  if (d->block == 512) return launch_advance_t<512>(p, grid, d->lds_bytes, d->stream);
+  return launch_advance_t<1024>(p, grid, d->lds_bytes, d->stream);
 }
 
 AdvanceParams base_params(const cbd_decoder *d) {
@@ -167,10 +160,13 @@ AdvanceParams base_params(const cbd_decoder *d) {
   p.chan = d->d_chan;
   p.beam = d->cfg.beam; p.max_active = d->cfg.max_active; p.max_eps_iters = d->cfg.max_eps_iters;
   p.lookup_mode = d->cfg.lookup_mode;
-  p.log_h = d->log_h; p.tok_cap = d->tok_cap; p.log_cap = d->log_cap; p.bp_cap = d->bp_cap;
-  p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap;
-  p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost; p.bp = d->d_bp; p.log = d->d_log; p.ctx = d->d_ctx;
-  p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_haux = d->d_haux;
+  p.lds_tok_cap = d->lds_tok_cap; p.lds_slots = d->lds_slots; p.lds_log_cap = d->lds_log_cap;
+  p.g_tok_cap = d->g_tok_cap; p.g_slots = d->g_slots; p.g_log_cap = d->g_log_cap;
+  p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap;
+  p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost;
+  p.tok_first = d->d_tok_first; p.tok_eps = d->d_tok_eps; p.tok_end = d->d_tok_end;
+  p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx;
+  p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_hidx = d->d_hidx;
   return p;
 }
 
@@ -216,6 +212,7 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   const int32_t S = desc->num_states, A = desc->num_arcs, P = desc->num_pdfs;
   if (S <= 0 || A < 0 || P <= 0 || desc->start_state < 0 || desc->start_state >= S)
     return fail(CBD_E_INVALID, "graph: bad sizes");
+  if (P > 65535) return fail(CBD_E_INVALID, "graph: more than 65535 pdfs (the arc record keeps ilabel in 16 bits)");
   if (!desc->row_offsets || (A > 0 && (!desc->dst || !desc->ilabel || !desc->olabel || !desc->weight)))
     return fail(CBD_E_INVALID, "graph: null array");
   const int32_t *row = desc->row_offsets;
@@ -237,7 +234,6 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   std::vector<cbd::ArcRec> arcs((size_t)std::max(A, 1));
   g->pub2int.resize((size_t)std::max(A, 1));
   g->int2pub.resize((size_t)std::max(A, 1));
-  std::vector<uint8_t> has_eps((size_t)S, 0);
   int32_t k = 0;
   for (int32_t s = 0; s < S; ++s) {
     off2[s].x = k;
@@ -245,17 +241,22 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
       if (desc->ilabel[a] != 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; }
     off2[s].y = k;
     for (int32_t a = row[s]; a < row[s + 1]; ++a)
-      if (desc->ilabel[a] == 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; has_eps[s] = 1; }
+      if (desc->ilabel[a] == 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; }
   }
   off2[S].x = k; off2[S].y = k;
+  std::vector<int32_t> olab((size_t)std::max(A, 1));
   for (int32_t i = 0; i < A; ++i) {
     int32_t a = g->int2pub[i];
+    int32_t dst = desc->dst[a];
+    int32_t ed = off2[dst].y - off2[dst].x, xd = off2[dst + 1].x - off2[dst].y;
     cbd::ArcRec r;
-    r.dst = desc->dst[a];
+    r.dst = dst;
     r.weight = desc->weight[a];
-    r.meta = (uint32_t)desc->ilabel[a] | (has_eps[desc->dst[a]] ? cbd::kMetaDstHasEps : 0u);
-    r.olabel = desc->olabel[a];
+    r.row = off2[dst].x;
+    r.meta = (uint32_t)desc->ilabel[a] | ((uint32_t)std::min<int32_t>(ed, (int32_t)cbd::kDegEscape) << 16) |
+             ((uint32_t)std::min<int32_t>(xd, (int32_t)cbd::kDegEscape) << 24);
     arcs[i] = r;
+    olab[i] = desc->olabel[a];
   }
 #define GCHK(expr)                                                                     \
   do {                                                                                 \
@@ -268,10 +269,12 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   GCHK(dmalloc(&g->d_off2, (size_t)S + 1, &g->bytes));
   GCHK(dmalloc(&g->d_arcs, (size_t)A, &g->bytes));
   GCHK(dmalloc(&g->d_int2pub, (size_t)A, &g->bytes));
+  GCHK(dmalloc(&g->d_olabel, (size_t)A, &g->bytes));
   GCHK(hipMemcpy(g->d_off2, off2.data(), sizeof(int2) * ((size_t)S + 1), hipMemcpyHostToDevice));
   if (A > 0) {
     GCHK(hipMemcpy(g->d_arcs, arcs.data(), sizeof(cbd::ArcRec) * (size_t)A, hipMemcpyHostToDevice));
     GCHK(hipMemcpy(g->d_int2pub, g->int2pub.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_olabel, olab.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
   }
   if (desc->final_cost) {
     GCHK(dmalloc(&g->d_final, (size_t)S, &g->bytes));
@@ -287,6 +290,7 @@ int32_t cbd_graph_free(cbd_graph *g) {
   if (g->d_off2) (void)hipFree(g->d_off2);
   if (g->d_arcs) (void)hipFree(g->d_arcs);
   if (g->d_int2pub) (void)hipFree(g->d_int2pub);
+  if (g->d_olabel) (void)hipFree(g->d_olabel);
   if (g->d_final) (void)hipFree(g->d_final);
   delete g;
   return CBD_OK;
@@ -302,21 +306,21 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->hash_capacity_log2 < 6 || cfg->hash_capacity_log2 > 24)
     return fail(CBD_E_INVALID, "decoder: hash_capacity_log2 must be in [6, 24]");
   if (cfg->table_location < 0 || cfg->table_location > 2) return fail(CBD_E_INVALID, "decoder: table_location");
+  if (cfg->lds_token_cap < 0) return fail(CBD_E_INVALID, "decoder: lds_token_cap");
   cbd_decoder *d = new (std::nothrow) cbd_decoder();
   if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
   d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
   if (d->cfg.max_eps_iters <= 0) d->cfg.max_eps_iters = 64;
   d->C = cfg->num_channels;
-  d->log_h = cfg->hash_capacity_log2;
-  const int64_t H = (int64_t)1 << d->log_h;
-  d->tok_cap = (int32_t)(H / 2);
-  d->log_cap = (int32_t)H;
-  int64_t rpf = cfg->records_per_frame > 0 ? cfg->records_per_frame : d->tok_cap;
-  int64_t bp = rpf * ((int64_t)cfg->max_frames + 1) + d->tok_cap;
+  d->g_slots = (int32_t)1 << cfg->hash_capacity_log2;
+  d->g_tok_cap = d->g_slots / 2;
+  d->g_log_cap = d->g_slots;
+  int64_t rpf = cfg->records_per_frame > 0 ? cfg->records_per_frame : d->g_tok_cap;
+  int64_t bp = rpf * ((int64_t)cfg->max_frames + 1) + d->g_tok_cap;
   if (bp > 0x7FFFFFF0) { delete d; return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel"); }
   d->bp_cap = (int32_t)bp;
   d->max_ctx = std::max(cfg->max_context_arcs, 1);
-  d->ctx_lds_cap = std::min((d->max_ctx + 15) / 16 * 16, 4096);
+  d->ctx_lds_cap = std::min((d->max_ctx + 15) / 16 * 16, 2048);
 
 #define DCHK(expr)                                                                     \
   do {                                                                                 \
@@ -330,18 +334,31 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   int lds_limit = 0, n_cu = 0;
   DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
   DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
-  cbd::LdsLayout with = cbd::make_layout(g->P, d->ctx_lds_cap, d->log_h, d->tok_cap, true);
-  cbd::LdsLayout without = cbd::make_layout(g->P, d->ctx_lds_cap, d->log_h, d->tok_cap, false);
-  if (cfg->table_location == 1 && (int64_t)with.total > lds_limit) {
-    delete d;
-    return fail(CBD_E_INVALID, "decoder: tables of this capacity do not fit LDS");
+  {
+    cbd::LdsLayout none = cbd::make_layout(g->P, d->ctx_lds_cap, 0, 0, 0);
+    if ((int64_t)none.total > lds_limit) {
+      delete d;
+      return fail(CBD_E_INVALID, "decoder: log-likelihood row and context do not fit LDS");
+    }
+    // LDS tables: the largest token capacity (multiple of 64) that fits beside the row and the context
+    int cap = 0;
+    if (cfg->table_location != 2) {
+      int want = cfg->lds_token_cap > 0 ? cfg->lds_token_cap : cbd::kLdsTokLimit;
+      want = std::min(want, std::min<int>(d->g_tok_cap, cbd::kLdsTokLimit));
+      for (int t = want / 64 * 64; t >= 64; t -= 64) {
+        cbd::LdsLayout l = cbd::make_layout(g->P, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t));
+        if ((int64_t)l.total <= lds_limit) { cap = t; break; }
+      }
+      if (cap == 0 && cfg->table_location == 1) {
+        delete d;
+        return fail(CBD_E_INVALID, "decoder: no room for token tables in LDS");
+      }
+    }
+    d->lds_tok_cap = cap;
+    d->lds_slots = cap ? cbd::lds_slots_for(cap) : 0;
+    d->lds_log_cap = cap ? cbd::lds_log_for(cap) : 0;
+    d->lds_bytes = cbd::make_layout(g->P, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap).total;
   }
-  if ((int64_t)without.total > lds_limit) {
-    delete d;
-    return fail(CBD_E_INVALID, "decoder: log-likelihood row and context do not fit LDS");
-  }
-  d->lds_tables = cfg->table_location == 1 || (cfg->table_location == 0 && (int64_t)with.total <= lds_limit);
-  d->lds_bytes = d->lds_tables ? with.total : without.total;
   // workgroup size: the more channels share a compute unit, the smaller the groups
   {
     int per_cu = (d->C + std::max(n_cu, 1) - 1) / std::max(n_cu, 1);
@@ -354,20 +371,23 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
       if (b == 256 || b == 512 || b == 1024) d->block = b;
     }
   }
-  DCHK(set_attr(d->lds_tables, d->block, d->lds_bytes));
+  DCHK(set_attr(d->block, d->lds_bytes));
 
   const size_t C = (size_t)d->C;
   DCHK(dmalloc(&d->d_chan, C, &d->bytes));
-  DCHK(dmalloc(&d->d_tok_state, C * d->tok_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_tok_cost, C * d->tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_state, C * d->g_tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_cost, C * d->g_tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_first, C * 2 * d->g_tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_eps, C * 2 * d->g_tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_end, C * 2 * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_bp, C * (size_t)d->bp_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_log, C * (size_t)d->log_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_log, C * (size_t)d->g_log_cap, &d->bytes));
   DCHK(dmalloc(&d->d_ctx, C * (size_t)d->max_ctx, &d->bytes));
-  if (!d->lds_tables) {
-    DCHK(dmalloc(&d->d_hkey, C * (size_t)H, &d->bytes));
-    DCHK(dmalloc(&d->d_hval, C * (size_t)H, &d->bytes));
-    DCHK(dmalloc(&d->d_haux, C * (size_t)H, &d->bytes));
-    size_t n = C * (size_t)H;
+  DCHK(dmalloc(&d->d_hkey, C * (size_t)d->g_slots, &d->bytes));
+  DCHK(dmalloc(&d->d_hval, C * (size_t)d->g_slots, &d->bytes));
+  DCHK(dmalloc(&d->d_hidx, C * (size_t)d->g_slots, &d->bytes));
+  {
+    size_t n = C * (size_t)d->g_slots;
     hipLaunchKernelGGL(cbd::init_tables_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, d->stream,
                        d->d_hkey, d->d_hval, n);
     DCHK(hipGetLastError());
@@ -387,8 +407,8 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
 int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
-  void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_bp, d->d_log, d->d_ctx, d->d_hkey, d->d_hval,
-                  d->d_haux, d->d_out_arcs, d->d_out_words, d->d_out_meta};
+  void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_first, d->d_tok_eps, d->d_tok_end, d->d_bp,
+                  d->d_log, d->d_ctx, d->d_hkey, d->d_hval, d->d_hidx, d->d_out_arcs, d->d_out_words, d->d_out_meta};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   d->ids.destroy();
@@ -398,12 +418,12 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
 }
 
 int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *lds_bytes, int32_t *block_threads,
-                         int32_t *tables_in_lds) {
+                         int32_t *lds_token_cap) {
   if (!d) return fail(CBD_E_INVALID, "info: null decoder");
   if (device_bytes) *device_bytes = (int64_t)d->bytes;
   if (lds_bytes) *lds_bytes = (int32_t)d->lds_bytes;
   if (block_threads) *block_threads = d->block;
-  if (tables_in_lds) *tables_in_lds = d->lds_tables ? 1 : 0;
+  if (lds_token_cap) *lds_token_cap = d->lds_tok_cap;
   return CBD_OK;
 }
 
@@ -519,8 +539,8 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   }
   cbd::BestParams bp{};
   bp.chan = d->d_chan; bp.chan_ids = dev; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost; bp.bp = d->d_bp;
-  bp.arcs = d->g->d_arcs; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
-  bp.tok_cap = d->tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
+  bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
+  bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
   bp.out_arcs = d->d_out_arcs; bp.out_words = d->d_out_words; bp.out_meta = d->d_out_meta;
   hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
   HIPCHK(hipGetLastError());
@@ -567,16 +587,16 @@ int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *
   std::vector<float> co((size_t)std::max(nt, 1));
   std::vector<int2> bp((size_t)std::max(nt, 1));
   if (nt > 0) {
-    HIPCHK(hipMemcpy(st.data(), d->d_tok_state + (size_t)channel * d->tok_cap, sizeof(int32_t) * nt,
+    HIPCHK(hipMemcpy(st.data(), d->d_tok_state + (size_t)channel * d->g_tok_cap, sizeof(int32_t) * nt,
                      hipMemcpyDeviceToHost));
-    HIPCHK(hipMemcpy(co.data(), d->d_tok_cost + (size_t)channel * d->tok_cap, sizeof(float) * nt,
+    HIPCHK(hipMemcpy(co.data(), d->d_tok_cost + (size_t)channel * d->g_tok_cap, sizeof(float) * nt,
                      hipMemcpyDeviceToHost));
     HIPCHK(hipMemcpy(bp.data(), d->d_bp + (size_t)channel * d->bp_cap + cs.frame_base, sizeof(int2) * nt,
                      hipMemcpyDeviceToHost));
   }
   int32_t k = 0;
   for (int32_t i = 0; i < nt; ++i) {
-    if (st[i] < 0) continue;
+    if (!(co[i] < INFINITY)) continue;  // dropped by the frame cutoff
     if (k < capacity && states && costs && arcs) {
       states[k] = st[i];
       costs[k] = co[i];
@@ -599,7 +619,7 @@ int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
   for (const cbd::ChanState &c : cs) {
     s.frames += c.frames; s.active_tokens += c.active_tokens; s.emit_arcs += c.emit_arcs; s.eps_arcs += c.eps_arcs;
     s.candidates += c.candidates; s.improvements += c.improvements; s.tokens += c.tokens;
-    s.eps_rounds += c.eps_rounds; s.records += c.n_rec;
+    s.eps_rounds += c.eps_rounds; s.records += c.n_rec; s.slow_frames += c.slow_frames;
     if (s.status == CBD_OK && c.status != CBD_OK) s.status = c.status;
     s.max_tokens = std::max(s.max_tokens, c.max_tokens);
   }

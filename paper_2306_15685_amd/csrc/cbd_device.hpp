@@ -6,16 +6,20 @@
 // Per frame the workgroup runs, separated by workgroup barriers only:
 //   emit     wave-level prefix scan over the surviving tokens' emitting
 //            out-degrees, one lane per arc (the "load balancing expand" of
-//            Sec. 3.2), bias lookup per arc (Sec. 4.2), candidate cost, cutoff
-//            against the running minimum, recombination by a 64-bit atomic min
-//            on (orderable cost << 32 | arc) in an open-addressing state table;
+//            Sec. 3.2), bias lookup per arc (Sec. 4.2), candidate cost.  A
+//            batch's candidates wait in registers until the batch minimum is
+//            known, then pass the cutoff and are recombined by a 64-bit atomic
+//            min on (orderable cost << 32 | arc) in an open-addressing table;
 //   closure  rounds over the change log: states whose value changed and that
 //            have epsilon-input arcs are expanded again until nothing changes;
 //   compact  the change log names each state's winning update exactly once;
 //            the winner writes the token, its back-pointer record and the
-//            pruning histogram, and clears its table slot.
-// The state table, the token list and the log-likelihood row live in LDS when
-// they fit (kLds), otherwise the tables are per-channel arrays in device memory.
+//            pruning histogram, and frees its table slot.
+// Every arc record carries the row of its destination state, so expanding a
+// token needs no offset lookup: the only dependent HBM access of a phase is the
+// arc read itself.  Table, tokens, change log and the log-likelihood row live in
+// LDS (kLds); a frame that outgrows them is redone with per-channel tables in
+// device memory, and decoding returns to LDS once the token list fits again.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -26,11 +30,6 @@ namespace cbd {
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;   // state table: free slot
 constexpr uint64_t kEmptyVal = ~0ull;
 constexpr uint32_t kArcNone = 0xFFFFFFFFu;    // start token's arc; sorts after every real arc
-constexpr uint32_t kSrcEps = 0x80000000u;     // change-log src: index into the current frame's tokens
-constexpr uint32_t kSrcHasEps = 0x40000000u;  // change-log src: the updated state has epsilon-input arcs
-constexpr uint32_t kSrcMask = 0x3FFFFFFFu;
-constexpr uint32_t kSrcNone = 0x3FFFFFFFu;    // start token: no predecessor
-constexpr uint32_t kMetaDstHasEps = 0x80000000u;
 
 constexpr int kStatusOk = 0;
 constexpr int kStatusCapacity = -2;
@@ -38,20 +37,36 @@ constexpr int kStatusEpsDiverged = -3;
 constexpr int kStatusNoTokens = -4;
 constexpr int kStatusBuffer = -5;
 
+// frame outcomes inside the kernel
+constexpr int kFrameOk = 0, kFrameOverflow = 1, kFrameNoTokens = 2, kFrameDiverged = 3, kFrameRecordsFull = 4;
+
 // One arc in the library's own order (per state: emitting arcs, then epsilon-input arcs).
 struct __attribute__((aligned(16))) ArcRec {
   int32_t dst;
   float weight;
-  uint32_t meta;   // bits 0..30 ilabel (0 = epsilon input, else pdf + 1); bit 31: dst has epsilon-input arcs
-  int32_t olabel;
+  int32_t row;     // first arc of dst
+  uint32_t meta;   // bits 0..15 ilabel (0 = epsilon input, else pdf + 1)
+                   // bits 16..23 number of emitting arcs of dst, 24..31 number of epsilon-input arcs of dst;
+                   // 255 in either field: look the row up in the offsets array
 };
+constexpr uint32_t kDegEscape = 255;
 
-// One table update: slot h took the value `key` through an arc leaving token `src`.
-struct __attribute__((aligned(16))) LogEntry {
-  uint64_t key;
-  uint32_t h;
-  uint32_t src;
+// Change-log entry: slot h took a value through arc `arc` leaving token `src`.
+// LDS form: 8 bytes; device-memory form: wide indices.
+template <bool kLds> struct LogT;
+template <> struct LogT<true> {
+  uint32_t arc; uint16_t h; uint16_t src;
+  static constexpr uint32_t kSrcEps = 0x8000u, kSrcHasEps = 0x4000u, kSrcMask = 0x3FFFu, kSrcNone = 0x3FFFu;
 };
+template <> struct __attribute__((aligned(16))) LogT<false> {
+  uint32_t arc; uint32_t h; uint32_t src; uint32_t pad;
+  static constexpr uint32_t kSrcEps = 0x80000000u, kSrcHasEps = 0x40000000u, kSrcMask = 0x3FFFFFFFu,
+                            kSrcNone = 0x3FFFFFFFu;
+};
+constexpr int kLdsTokLimit = 0x3FFE;  // token indices must fit the 14-bit src field
+
+template <bool kLds> struct IdxT { typedef uint32_t type; };
+template <> struct IdxT<true> { typedef uint16_t type; };
 
 // Per-channel state that survives between calls.
 struct __attribute__((aligned(128))) ChanState {
@@ -65,7 +80,8 @@ struct __attribute__((aligned(128))) ChanState {
   float ctx_offset;
   long long frames, active_tokens, emit_arcs, eps_arcs, candidates, improvements, tokens, eps_rounds;
   int32_t max_tokens;
-  int32_t pad[7];
+  int32_t slow_frames;  // frames decoded with the device-memory tables
+  int32_t pad[6];
 };
 
 struct AdvanceParams {
@@ -83,20 +99,27 @@ struct AdvanceParams {
   int32_t max_active;
   int32_t max_eps_iters;
   int32_t lookup_mode;
-  int32_t log_h;           // table slots = 1 << log_h
-  int32_t tok_cap;
-  int32_t log_cap;
+  int32_t lds_tok_cap;     // token capacity of the LDS tables (0: LDS tables unused)
+  int32_t lds_slots;       // state-table slots in LDS
+  int32_t lds_log_cap;
+  int32_t g_tok_cap;       // the same for the device-memory tables
+  int32_t g_slots;
+  int32_t g_log_cap;
   int32_t bp_cap;
   int32_t max_ctx;         // row length of ctx
   int32_t ctx_lds_cap;     // context entries that fit the LDS copy
-  int32_t *tok_state;      // [C][tok_cap]
-  float *tok_cost;         // [C][tok_cap]
+  // per channel, device memory
+  int32_t *tok_state;      // [C][g_tok_cap] states of the current tokens (written on the last frame of a call)
+  float *tok_cost;         // [C][g_tok_cap]
+  int32_t *tok_first;      // [C][2][g_tok_cap] first emitting arc / first epsilon arc / end of row, two buffers
+  int32_t *tok_eps;
+  int32_t *tok_end;
   int2 *bp;                // [C][bp_cap] (arc, predecessor record or -1)
-  LogEntry *log;           // [C][log_cap]
+  LogT<false> *g_log;      // [C][g_log_cap]
   const int32_t *ctx;      // [C][max_ctx] sorted, library arc order
-  uint32_t *g_hkey;        // [C][H]  tables in device memory (unused with kLds)
-  uint64_t *g_hval;        // [C][H]
-  uint32_t *g_haux;        // [C][H]
+  uint32_t *g_hkey;        // [C][g_slots]
+  uint64_t *g_hval;
+  uint32_t *g_hidx;
 };
 
 // Workgroup-shared scalars.
@@ -112,15 +135,18 @@ struct Shared {
   int32_t n_tok, frame_base, n_rec, status, cut_bin, fr_begin, fr_end, rounds;
   float best;
   uint32_t c_active, c_emit, c_eps, c_cand;
+  int32_t diverged;
+  int32_t a_maxtok, a_slow;   // counters of this call
+  long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
 
 struct LdsLayout {
-  uint32_t sh, hist, bitmap, ctx, L, hval, hkey, haux, tst, tco, total;
+  uint32_t sh, hist, bitmap, ctx, L, hval, hkey, hidx, tfirst, teps, tend, tcost, log, total;
 };
 
 __host__ __device__ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 
-__host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, int log_h, int tok_cap, bool lds_tables) {
+__host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, int tok_cap, int slots, int log_cap) {
   LdsLayout l;
   uint32_t o = 0;
   l.sh = o; o += align_up((uint32_t)sizeof(Shared), 16);
@@ -128,18 +154,21 @@ __host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, 
   l.bitmap = o; o += 256 * 4;
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
   l.L = o; o += align_up((uint32_t)num_pdfs * 4, 16);
-  l.hval = l.hkey = l.haux = l.tst = l.tco = 0;
-  if (lds_tables) {
-    uint32_t H = 1u << log_h;
-    l.hval = o; o += H * 8;
-    l.hkey = o; o += H * 4;
-    l.haux = o; o += H * 4;
-    l.tst = o; o += align_up((uint32_t)tok_cap * 4, 16);
-    l.tco = o; o += align_up((uint32_t)tok_cap * 4, 16);
-  }
+  l.hval = o; o += (uint32_t)slots * 8;
+  l.hkey = o; o += (uint32_t)slots * 4;
+  l.hidx = o; o += align_up((uint32_t)slots * 2, 16);
+  l.tfirst = o; o += align_up((uint32_t)tok_cap * 8, 16);  // two buffers each
+  l.teps = o; o += align_up((uint32_t)tok_cap * 8, 16);
+  l.tend = o; o += align_up((uint32_t)tok_cap * 8, 16);
+  l.tcost = o; o += align_up((uint32_t)tok_cap * 4, 16);
+  l.log = o; o += align_up((uint32_t)log_cap * 8, 16);
   l.total = o;
   return l;
 }
+
+// LDS per token of capacity: 1.5 slots x 14 B + 28 B of token arrays + 1.5 log entries x 8 B = 61 B.
+__host__ __device__ inline int lds_slots_for(int tok_cap) { return tok_cap + tok_cap / 2; }
+__host__ __device__ inline int lds_log_for(int tok_cap) { return tok_cap + tok_cap / 2; }
 
 // ---- small helpers -------------------------------------------------------
 
@@ -172,19 +201,11 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
 }
 
 // Accessors for values that other waves change with atomics.
-template <bool kLds> __device__ __forceinline__ uint32_t ld32(const uint32_t *p) {
-  if (kLds) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+template <bool kLds, typename T> __device__ __forceinline__ T ldv(const T *p) {
+  if (kLds) return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <bool kLds> __device__ __forceinline__ uint64_t ld64(const uint64_t *p) {
-  if (kLds) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <bool kLds> __device__ __forceinline__ void st32(uint32_t *p, uint32_t v) {
-  if (kLds) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <bool kLds> __device__ __forceinline__ void st64(uint64_t *p, uint64_t v) {
+template <bool kLds, typename T> __device__ __forceinline__ void stv(T *p, T v) {
   if (kLds) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -221,39 +242,60 @@ __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
   return sorted_contains(cx.g_list, cx.n, a);
 }
 
-template <bool kLds> struct Tables {
+// Where a frame's working set lives.
+template <bool kLds> struct Mem {
+  typedef typename IdxT<kLds>::type idx_t;
   uint64_t *hval;
   uint32_t *hkey;
-  uint32_t *haux;
-  int32_t *tok_state;
-  float *tok_cost;
-  uint32_t mask;
-  int shift;
+  idx_t *hidx;
+  int32_t *t_first, *t_eps, *t_end;   // two buffers each: buffer b starts at b * tok_cap
+  float *t_cost;
+  LogT<kLds> *log;
+  uint32_t slots;
+  int tok_cap, log_cap;
 };
 
+struct RowInfo { int first, eps, end; };
+
+__device__ __forceinline__ RowInfo row_of(const AdvanceParams &p, const ArcRec &rec) {
+  RowInfo r;
+  uint32_t ed = (rec.meta >> 16) & 255u, xd = rec.meta >> 24;
+  r.first = rec.row;
+  if (ed == kDegEscape || xd == kDegEscape) {
+    int2 o = p.off2[rec.dst], o2 = p.off2[rec.dst + 1];
+    r.eps = o.y; r.end = o2.x;
+  } else {
+    r.eps = r.first + (int)ed; r.end = r.eps + (int)xd;
+  }
+  return r;
+}
+
 // Recombination: E[state] = min key.  Returns true if this call lowered the
-// state's value (old > key); h receives the slot.
+// state's value (old > key); h receives the slot.  The lane that creates the
+// state's entry also files the state's row under the entry's token index
+// (no = offset of the token buffer being built).
 template <bool kLds>
-__device__ __forceinline__ bool table_min(const Tables<kLds> &T, Shared *sh, int tok_cap, uint32_t state, uint64_t key,
-                                          uint32_t &h_out) {
-  uint32_t h = (state * 2654435761u) >> T.shift;
-  for (uint32_t probe = 0; probe <= T.mask; ++probe) {
-    uint32_t k = ld32<kLds>(&T.hkey[h]);
+__device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, int no, uint32_t state, uint64_t key,
+                                          const RowInfo &row, uint32_t &h_out) {
+  uint32_t h = __umulhi(state * 2654435761u, M.slots);
+  for (uint32_t probe = 0; probe < M.slots; ++probe) {
+    uint32_t k = ldv<kLds>(&M.hkey[h]);
     if (k == kEmptyKey) {
-      k = atomicCAS(&T.hkey[h], kEmptyKey, state);
+      k = atomicCAS(&M.hkey[h], kEmptyKey, state);
       if (k == kEmptyKey) {
         int idx = atomicAdd(&sh->n_claim, 1);
-        if (idx >= tok_cap) sh->fault = 1;
-        st32<kLds>(&T.haux[h], (uint32_t)idx);
+        if (idx >= M.tok_cap) { sh->fault = 1; idx = M.tok_cap - 1; }
+        else { M.t_first[no + idx] = row.first; M.t_eps[no + idx] = row.eps; M.t_end[no + idx] = row.end; }
+        stv<kLds>(&M.hidx[h], (typename Mem<kLds>::idx_t)idx);
         k = state;
       }
     }
     if (k == state) {
-      uint64_t old = atomicMin((unsigned long long *)&T.hval[h], (unsigned long long)key);
+      uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
       h_out = h;
       return old > key;
     }
-    h = (h + 1) & T.mask;
+    h = h + 1 == M.slots ? 0 : h + 1;
   }
   sh->fault = 1;
   h_out = 0;
@@ -261,13 +303,14 @@ __device__ __forceinline__ bool table_min(const Tables<kLds> &T, Shared *sh, int
 }
 
 // Append the updates of this wave's lanes to the channel's change log.
-__device__ __forceinline__ void log_append(LogEntry *log, int log_cap, Shared *sh, bool improved, uint64_t key,
-                                           uint32_t h, uint32_t src, int lane) {
+template <bool kLds>
+__device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, bool improved, uint32_t arc, uint32_t h,
+                                           uint32_t src, int lane) {
   unsigned long long mask = __ballot(improved);
   if (mask == 0) return;
   int leader = __ffsll((long long)mask) - 1;
   int n = __popcll(mask);
-  int nf = __popcll(__ballot(improved && (src & kSrcHasEps)));
+  int nf = __popcll(__ballot(improved && (src & LogT<kLds>::kSrcHasEps)));
   int base = 0;
   if (lane == leader) {
     base = atomicAdd(&sh->log_n, n);
@@ -276,111 +319,370 @@ __device__ __forceinline__ void log_append(LogEntry *log, int log_cap, Shared *s
   base = __shfl(base, leader, 64);
   if (improved) {
     int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
-    if (pos < log_cap) {
-      LogEntry e; e.key = key; e.h = h; e.src = src;
-      log[pos] = e;
+    if (pos < M.log_cap) {
+      LogT<kLds> e;
+      e.arc = arc; e.h = (decltype(e.h))h; e.src = (decltype(e.src))src;
+      M.log[pos] = e;
     } else {
       sh->fault = 1;
     }
   }
 }
 
-// Expand `deg` arcs starting at `first` for each lane's item (deg = 0: none),
-// one lane per arc.  kEmit: cand = (cost + w') - L[pdf]; else cand = cost + w'.
-template <bool kLds, bool kEmit>
-__device__ __forceinline__ void expand_rows(const AdvanceParams &p, const Tables<kLds> &T, Shared *sh, const Ctx &cx,
-                                            const float *Lrow, LogEntry *log, int first, int deg, float cost,
-                                            uint32_t src_tag, float m_fixed, int lane) {
+// The wave's arc list: lane i contributes `deg` arcs starting at `first`.
+struct ArcList { int pos, rel, total; };
+
+__device__ __forceinline__ ArcList make_arc_list(int first, int deg, int lane) {
+  ArcList L;
   int incl = wave_incl_scan(deg, lane);
-  int pos = incl - deg;
-  int total = __shfl(incl, 63, 64);
-  if (total == 0) return;
-  if (lane == 0) {
-    if (kEmit) atomicAdd(&sh->c_emit, (uint32_t)total); else atomicAdd(&sh->c_eps, (uint32_t)total);
-  }
-  int rel = first - pos;  // arc index = rel + position in the wave's arc list
-  for (int j0 = 0; j0 < total; j0 += 64) {
-    int jj = j0 + lane;
-    bool act = jj < total;
-    // owner = last lane whose first position is <= jj
-    int owner = 0;
+  L.pos = incl - deg;
+  L.rel = first - L.pos;   // arc index = rel(owner) + position in the list
+  L.total = __shfl(incl, 63, 64);
+  return L;
+}
+
+// owner of list position jj = last lane whose first position is <= jj
+__device__ __forceinline__ int arc_owner(const ArcList &L, int jj) {
+  int owner = 0;
 #pragma unroll
-    for (int step = 32; step >= 1; step >>= 1) {
-      int cand = owner + step;
-      int pc = __shfl(pos, cand & 63, 64);
-      if (cand < 64 && pc <= jj) owner = cand;
-    }
-    int a = __shfl(rel, owner, 64) + jj;
+  for (int step = 32; step >= 1; step >>= 1) {
+    int cand = owner + step;
+    int pc = __shfl(L.pos, cand & 63, 64);
+    if (cand < 64 && pc <= jj) owner = cand;
+  }
+  return owner;
+}
+
+// Cutoff test, recombination and logging of one candidate per lane (called by whole waves).
+template <bool kLds, bool kEmit>
+__device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no, bool act,
+                                       float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed, int lane) {
+  bool pass = false;
+  if (act) {
+    float mref = kEmit ? ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) : m_fixed;
+    pass = !(cand - mref > p.beam);
+  }
+  unsigned long long pmask = __ballot(pass);
+  if (pmask == 0) return;
+  uint32_t co = pass ? f2ord(cand) : 0xFFFFFFFFu;
+  if (!kEmit) {
+    uint32_t wmin = wave_min_u32(co);
+    if (lane == 0) atomicMin(&sh->best_ord, wmin);
+  }
+  if (lane == 0) atomicAdd(&sh->c_cand, (uint32_t)__popcll(pmask));
+  bool improved = false;
+  uint32_t h = 0;
+  uint32_t src = src_tag;
+  if (pass && !__hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
+    RowInfo row = row_of(p, rec);
+    if (row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;
+    uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
+    improved = table_min<kLds>(M, sh, no, (uint32_t)rec.dst, key, row, h);
+  }
+  log_append<kLds>(M, sh, improved, (uint32_t)a, h, src, lane);
+}
+
+// Expand positions [j_begin, total) of the wave's arc list, one lane per arc, committing
+// each candidate at once (closure rounds, and the rare emit overflow beyond the register batch).
+template <bool kLds, bool kEmit>
+__device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
+                                              const float *Lrow, int no, const ArcList &AL, int j_begin, float cost,
+                                              uint32_t src_tag, float m_fixed, int lane) {
+  for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
+    int jj = j0 + lane;
+    bool act = jj < AL.total;
+    int owner = arc_owner(AL, jj);
+    int a = __shfl(AL.rel, owner, 64) + jj;
     float c_own = __shfl(cost, owner, 64);
     uint32_t s_own = (uint32_t)__shfl((int)src_tag, owner, 64);
-    bool pass = false;
     float cand = 0.0f;
-    ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.meta = 0; rec.olabel = 0;
+    ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
     if (act) {
       rec = p.arcs[a];
       float w = rec.weight;
       if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1: boosted weight = weight + discount
-      if (kEmit) {
-        cand = (c_own + w) - Lrow[(rec.meta & 0x7FFFFFFFu) - 1u];
-        float mrun = ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-        pass = !(cand - mrun > p.beam);
-      } else {
-        cand = c_own + w;
-        pass = !(cand - m_fixed > p.beam);
-      }
+      if (kEmit) cand = (c_own + w) - Lrow[(rec.meta & 0xFFFFu) - 1u];
+      else cand = c_own + w;
     }
-    uint32_t co = pass ? f2ord(cand) : 0xFFFFFFFFu;
-    uint32_t wmin = wave_min_u32(co);
-    unsigned long long pmask = __ballot(pass);
-    if (pmask == 0) continue;
-    if (lane == 0) {
-      if (kEmit) atomicMin(&sh->m_ord, wmin); else atomicMin(&sh->best_ord, wmin);
-      atomicAdd(&sh->c_cand, (uint32_t)__popcll(pmask));
+    if (kEmit) {
+      uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
+      if (lane == 0) atomicMin(&sh->m_ord, wmin);
     }
-    bool improved = false;
-    uint32_t h = 0;
-    uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
-    if (pass && !sh->fault) improved = table_min<kLds>(T, sh, p.tok_cap, (uint32_t)rec.dst, key, h);
-    uint32_t src = s_own | ((rec.meta & kMetaDstHasEps) ? kSrcHasEps : 0u);
-    log_append(log, p.log_cap, sh, improved, key, h, src, lane);
+    commit<kLds, kEmit>(p, M, sh, no, act, cand, a, rec, s_own, m_fixed, lane);
   }
 }
 
+constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimum settles
+
+// One frame (f >= 0) or the start of an utterance (f < 0).  Uniform control flow; returns a kFrame* code.
+// Nothing that outlives the frame is written before the capacity checks have passed.
 template <bool kLds, int kBlock>
+__device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
+                                         const float *Lrow, uint32_t *hist, int f, int cur, int2 *bp,
+                                         int32_t *g_tok_state, bool last_frame) {
+  constexpr int NW = kBlock / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int co = cur * M.tok_cap, no = (cur ^ 1) * M.tok_cap;   // token buffer read / built
+  const bool hist_on = p.max_active > 0 && p.beam > 0.0f && p.beam < __builtin_inff();
+  const float inv = 256.0f / p.beam;
+  typedef LogT<kLds> LogE;
+
+  if (tid == 0) {
+    sh->m_ord = f < 0 ? f2ord(0.0f) : 0xFFFFFFFFu;
+    sh->n_claim = 0; sh->log_n = 0; sh->n_front = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
+    sh->fault = 0; sh->diverged = 0;
+    sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
+  }
+  for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
+  __syncthreads();
+
+  if (f < 0) {
+    // reset: one start token at cost 0
+    if (wave == 0) {
+      uint32_t h = 0;
+      uint64_t key = ((uint64_t)f2ord(0.0f) << 32) | kArcNone;
+      bool improved = false;
+      int2 o = p.off2[p.start_state], o2 = p.off2[p.start_state + 1];
+      RowInfo row; row.first = o.x; row.eps = o.y; row.end = o2.x;
+      if (lane == 0) improved = table_min<kLds>(M, sh, no, (uint32_t)p.start_state, key, row, h);
+      uint32_t src = LogE::kSrcNone | ((row.end > row.eps) ? LogE::kSrcHasEps : 0u);
+      log_append<kLds>(M, sh, improved, kArcNone, h, src, lane);
+    }
+  } else {
+    // ---- emit: prune (step 1), expand emitting arcs (step 2), in batches of one tile per wave
+    const int n_tok = sh->n_tok;
+    const float best = sh->best;
+    const int cut = sh->cut_bin;
+    const int n_batches = (n_tok + kBlock - 1) / kBlock;
+    for (int b = 0; b < n_batches; ++b) {
+      const int tile0 = (b * NW + wave) * 64;
+      int i = tile0 + lane;
+      bool alive = false;
+      float cost = 0.0f;
+      int first = 0, deg = 0;
+      if (i < n_tok) {
+        cost = M.t_cost[i];
+        float r = cost - best;
+        alive = !(r > p.beam) && cost < __builtin_inff();
+        if (alive && cut < 255) {
+          int bin = (int)floorf(r * inv);
+          bin = bin > 255 ? 255 : bin;
+          alive = bin <= cut;
+        }
+        if (alive) { first = M.t_first[co + i]; deg = M.t_eps[co + i] - first; }
+      }
+      unsigned long long am = __ballot(alive);
+      ArcList AL = make_arc_list(first, deg, lane);
+      if (lane == 0 && am) { atomicAdd(&sh->c_active, (uint32_t)__popcll(am)); atomicAdd(&sh->c_emit, (uint32_t)AL.total); }
+      // phase A: fetch up to kEmitSlots arcs per lane, keep the candidates in registers
+      float cand[kEmitSlots];
+      int arc[kEmitSlots];
+      ArcRec rec[kEmitSlots];
+      uint32_t srct[kEmitSlots];
+      uint32_t lmin = 0xFFFFFFFFu;
+#pragma unroll
+      for (int r = 0; r < kEmitSlots; ++r) {
+        int jj = r * 64 + lane;
+        bool act = jj < AL.total;
+        cand[r] = 0.0f; arc[r] = 0; srct[r] = 0;
+        rec[r].dst = 0; rec[r].weight = 0.0f; rec[r].row = 0; rec[r].meta = 0;
+        if (r * 64 < AL.total) {   // uniform
+          int owner = arc_owner(AL, jj);
+          arc[r] = __shfl(AL.rel, owner, 64) + jj;
+          float c_own = __shfl(cost, owner, 64);
+          srct[r] = (uint32_t)(tile0 + owner);
+          if (act) {
+            rec[r] = p.arcs[arc[r]];
+            float w = rec[r].weight;
+            if (ctx_contains(cx, arc[r])) w = w + cx.offset;   // Sec. 4.1
+            cand[r] = (c_own + w) - Lrow[(rec[r].meta & 0xFFFFu) - 1u];
+            uint32_t o = f2ord(cand[r]);
+            lmin = o < lmin ? o : lmin;
+          }
+        }
+      }
+      uint32_t wmin = wave_min_u32(lmin);
+      if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
+      __syncthreads();   // the batch minimum is known: few doomed candidates reach the table
+      // phase B: cutoff, recombination
+#pragma unroll
+      for (int r = 0; r < kEmitSlots; ++r) {
+        if (r * 64 < AL.total) {
+          bool act = r * 64 + lane < AL.total;
+          commit<kLds, true>(p, M, sh, no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, lane);
+        }
+      }
+      if (AL.total > kEmitSlots * 64)
+        expand_direct<kLds, true>(p, M, sh, cx, Lrow, no, AL, kEmitSlots * 64, cost, (uint32_t)(tile0 + lane), 0.0f,
+                                  lane);
+    }
+  }
+  __syncthreads();
+
+  // ---- step 3: the emission minimum fixes the frame's cutoff
+  const float m = ord2f(sh->m_ord);
+  if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh->log_n; }
+  __syncthreads();
+  if (sh->fault) return kFrameOverflow;
+  if (sh->n_claim == 0) return kFrameNoTokens;
+
+  // ---- step 4: epsilon closure, one round per barrier pair
+  while (sh->n_front > 0) {
+    const int fb = sh->fr_begin, fe = sh->fr_end;
+    __syncthreads();
+    if (tid == 0) sh->n_front = 0;
+    __syncthreads();
+    for (int tile = wave; fb + tile * 64 < fe; tile += NW) {
+      int j = fb + tile * 64 + lane;
+      float cost = 0.0f;
+      int first = 0, deg = 0;
+      uint32_t src_tag = 0;
+      if (j < fe) {
+        LogE e = M.log[j];
+        if (e.src & LogE::kSrcHasEps) {
+          uint64_t curv = ldv<kLds>(&M.hval[e.h]);
+          cost = ord2f((uint32_t)(curv >> 32));
+          // still this state's value, and not dropped by the emission cutoff
+          if ((uint32_t)curv == e.arc && curv != kEmptyVal && !(cost - m > p.beam)) {
+            uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
+            first = M.t_eps[no + idx];
+            deg = M.t_end[no + idx] - first;
+            src_tag = idx | LogE::kSrcEps;
+          }
+        }
+      }
+      ArcList AL = make_arc_list(first, deg, lane);
+      if (AL.total == 0) continue;
+      if (lane == 0) atomicAdd(&sh->c_eps, (uint32_t)AL.total);
+      expand_direct<kLds, false>(p, M, sh, cx, Lrow, no, AL, 0, cost, src_tag, m, lane);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      sh->fr_begin = fe; sh->fr_end = sh->log_n; sh->rounds++;
+      if (sh->n_front > 0 && sh->rounds >= p.max_eps_iters) sh->diverged = 1;
+    }
+    __syncthreads();
+    if (sh->diverged || sh->fault) break;
+  }
+  if (sh->fault) return kFrameOverflow;
+  if (sh->diverged) return kFrameDiverged;
+  if (sh->n_rec + sh->n_claim > p.bp_cap) return kFrameRecordsFull;
+
+  // ---- step 5 and bookkeeping: every state's winning update writes the token
+  {
+    const float best = ord2f(sh->best_ord);
+    const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh->log_n;
+    int my_surv = 0, my_live = 0;
+    for (int j = tid; j < log_n; j += kBlock) {
+      LogE e = M.log[j];
+      uint64_t curv = ldv<kLds>(&M.hval[e.h]);
+      if ((uint32_t)curv != e.arc || curv == kEmptyVal) continue;
+      // an arc can appear twice for a slot (its source improved in a later round): one of them takes the slot
+      if (atomicCAS((unsigned long long *)&M.hval[e.h], (unsigned long long)curv, (unsigned long long)kEmptyVal) != curv)
+        continue;
+      int idx = (int)ldv<kLds>(&M.hidx[e.h]);
+      float cost = ord2f((uint32_t)(curv >> 32));
+      bool dead = cost - m > p.beam;
+      uint32_t sf = e.src & LogE::kSrcMask;
+      int prev = sf == LogE::kSrcNone ? -1 : ((e.src & LogE::kSrcEps) ? base_cur + (int)sf : base_prev + (int)sf);
+      M.t_cost[idx] = dead ? __builtin_inff() : cost;
+      bp[base_cur + idx] = make_int2((int)e.arc, prev);
+      if (last_frame) g_tok_state[idx] = (int)ldv<kLds>(&M.hkey[e.h]);
+      if (!dead) {
+        my_live++;
+        float r = cost - best;
+        if (!(r > p.beam)) {
+          my_surv++;
+          if (hist_on) {
+            int bin = (int)floorf(r * inv);
+            bin = bin > 255 ? 255 : bin;
+            atomicAdd(&hist[bin], 1u);
+          }
+        }
+      }
+      stv<kLds>(&M.hkey[e.h], kEmptyKey);
+    }
+    if (my_surv) atomicAdd(&sh->n_surv, my_surv);
+    if (my_live) atomicAdd(&sh->n_live, my_live);
+  }
+  __syncthreads();
+
+  // ---- close the frame
+  if (wave == 0) {
+    int cut = 255;
+    if (hist_on && sh->n_surv > p.max_active) {
+      // largest bin B whose cumulative count fits max_active (0 if bin 0 alone does not)
+      int loc[4], sum = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { loc[k] = (int)hist[lane * 4 + k]; sum += loc[k]; }
+      int incl = wave_incl_scan(sum, lane);
+      int run = incl - sum;
+      int myB = -1;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { run += loc[k]; if (run <= p.max_active) myB = lane * 4 + k; }
+      // cumulative counts are monotone, so the bins that fit form a prefix: take the maximum
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) { int t = __shfl_xor(myB, d, 64); myB = t > myB ? t : myB; }
+      cut = myB < 0 ? 0 : myB;
+    }
+    if (lane == 0) {
+      sh->cut_bin = cut;
+      sh->n_tok = sh->n_claim;
+      sh->frame_base = sh->n_rec;
+      sh->n_rec += sh->n_claim;
+      sh->best = ord2f(sh->best_ord);
+      if (f >= 0) {  // the table made at reset is not a decoded frame
+        sh->a_frames++;
+        sh->a_tokens += sh->n_live;
+        if (sh->n_live > sh->a_maxtok) sh->a_maxtok = sh->n_live;
+        if (!kLds) sh->a_slow++;
+      }
+      sh->a_active += sh->c_active; sh->a_emit += sh->c_emit; sh->a_eps += sh->c_eps; sh->a_cand += sh->c_cand;
+      sh->a_impr += sh->log_n; sh->a_rounds += sh->rounds;
+    }
+  }
+  __syncthreads();
+  return kFrameOk;
+}
+
+template <int kBlock>
 __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NW = kBlock / 64;
-  constexpr int kPre = 8;  // log-likelihood values each thread holds while the next row is in flight
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int kPre = kBlock >= 1024 ? 6 : 8;  // log-likelihood values a thread holds while the next row is in flight
+  const int tid = threadIdx.x;
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
-  const LdsLayout lay = make_layout(p.num_pdfs, p.ctx_lds_cap, p.log_h, p.tok_cap, kLds);
+  const LdsLayout lay = make_layout(p.num_pdfs, p.ctx_lds_cap, p.lds_tok_cap, p.lds_slots, p.lds_log_cap);
   Shared *sh = (Shared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
   int32_t *ctx_lds = (int32_t *)(smem + lay.ctx);
   float *Lrow = (float *)(smem + lay.L);
-  const uint32_t H = 1u << p.log_h;
 
-  Tables<kLds> T;
-  T.mask = H - 1; T.shift = 32 - p.log_h;
-  if (kLds) {
-    T.hval = (uint64_t *)(smem + lay.hval);
-    T.hkey = (uint32_t *)(smem + lay.hkey);
-    T.haux = (uint32_t *)(smem + lay.haux);
-    T.tok_state = (int32_t *)(smem + lay.tst);
-    T.tok_cost = (float *)(smem + lay.tco);
-  } else {
-    T.hval = p.g_hval + (size_t)c * H;
-    T.hkey = p.g_hkey + (size_t)c * H;
-    T.haux = p.g_haux + (size_t)c * H;
-    T.tok_state = p.tok_state + (size_t)c * p.tok_cap;
-    T.tok_cost = p.tok_cost + (size_t)c * p.tok_cap;
-  }
-  int32_t *g_tok_state = p.tok_state + (size_t)c * p.tok_cap;
-  float *g_tok_cost = p.tok_cost + (size_t)c * p.tok_cap;
+  Mem<true> ML;
+  ML.hval = (uint64_t *)(smem + lay.hval);
+  ML.hkey = (uint32_t *)(smem + lay.hkey);
+  ML.hidx = (uint16_t *)(smem + lay.hidx);
+  ML.t_first = (int32_t *)(smem + lay.tfirst);
+  ML.t_eps = (int32_t *)(smem + lay.teps);
+  ML.t_end = (int32_t *)(smem + lay.tend);
+  ML.t_cost = (float *)(smem + lay.tcost);
+  ML.log = (LogT<true> *)(smem + lay.log);
+  ML.slots = (uint32_t)p.lds_slots; ML.tok_cap = p.lds_tok_cap; ML.log_cap = p.lds_log_cap;
+
+  Mem<false> MG;
+  MG.hval = p.g_hval + (size_t)c * p.g_slots;
+  MG.hkey = p.g_hkey + (size_t)c * p.g_slots;
+  MG.hidx = p.g_hidx + (size_t)c * p.g_slots;
+  MG.t_first = p.tok_first + (size_t)c * 2 * p.g_tok_cap;
+  MG.t_eps = p.tok_eps + (size_t)c * 2 * p.g_tok_cap;
+  MG.t_end = p.tok_end + (size_t)c * 2 * p.g_tok_cap;
+  MG.t_cost = p.tok_cost + (size_t)c * p.g_tok_cap;
+  MG.log = p.g_log + (size_t)c * p.g_log_cap;
+  MG.slots = (uint32_t)p.g_slots; MG.tok_cap = p.g_tok_cap; MG.log_cap = p.g_log_cap;
+
+  int32_t *g_tok_state = p.tok_state + (size_t)c * p.g_tok_cap;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
-  LogEntry *log = p.log + (size_t)c * p.log_cap;
   const float *Lbase = p.loglikes + (long long)blockIdx.x * p.channel_stride;
 
   if (tid == 0) {
@@ -390,9 +692,8 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     sh->n_rec = p.do_reset ? 0 : cs->n_rec;
     sh->best = p.do_reset ? 0.0f : cs->best;
     sh->cut_bin = p.do_reset ? 255 : cs->cut_bin;
-    sh->fault = 0;
-    sh->n_claim = 1;  // only a decoded frame that produced nothing parks the channel
-    sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
+    sh->a_maxtok = 0; sh->a_slow = 0;
+    sh->a_frames = sh->a_active = sh->a_emit = sh->a_eps = sh->a_cand = sh->a_impr = sh->a_tokens = sh->a_rounds = 0;
   }
   __syncthreads();
   if (sh->status != kStatusOk) return;  // uniform: the channel is parked until reset
@@ -413,26 +714,22 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       atomicOr(&bitmap[b >> 5], 1u << (b & 31));
     }
   }
-  if (kLds) {
-    for (uint32_t i = tid; i < H; i += kBlock) { T.hval[i] = kEmptyVal; T.hkey[i] = kEmptyKey; }
-    for (int i = tid; i < sh->n_tok; i += kBlock) { T.tok_state[i] = g_tok_state[i]; T.tok_cost[i] = g_tok_cost[i]; }
+  // tokens enter through device-memory buffer 0; LDS takes them over when they fit
+  bool fast = p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap;
+  int cur = 0;
+  for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
+  if (fast) {
+    for (int i = tid; i < sh->n_tok; i += kBlock) {
+      ML.t_cost[i] = MG.t_cost[i]; ML.t_first[i] = MG.t_first[i];
+      ML.t_eps[i] = MG.t_eps[i]; ML.t_end[i] = MG.t_end[i];
+    }
   }
   if (p.n_frames > 0) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = Lbase[i];
+  __syncthreads();
 
-  long long st_frames = 0, st_active = 0, st_emit = 0, st_eps = 0, st_cand = 0, st_impr = 0, st_tok = 0, st_rounds = 0;
-  int st_maxtok = 0;
-  const bool hist_on = p.max_active > 0 && p.beam > 0.0f && p.beam < __builtin_inff();
-  const float inv = 256.0f / p.beam;
-
+  int outcome = kFrameOk;
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
-    if (tid == 0) {
-      sh->m_ord = f < 0 ? f2ord(0.0f) : 0xFFFFFFFFu;
-      sh->n_claim = 0; sh->log_n = 0; sh->n_front = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
-    }
-    for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
-    __syncthreads();
-
-    // next frame's row starts its way from HBM now and is parked in registers
+    // next frame's row starts its way from HBM now and waits in registers
     float pre[kPre];
     const bool have_next = f + 1 < p.n_frames && f >= 0;
     const float *Lnext = Lbase + (long long)(f + 1) * p.num_pdfs;
@@ -441,175 +738,33 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       int i = tid + k * kBlock;
       pre[k] = (have_next && i < p.num_pdfs) ? Lnext[i] : 0.0f;
     }
-
-    if (f < 0) {
-      // reset: one start token at cost 0
-      if (wave == 0) {
-        bool me = lane == 0;
-        uint32_t h = 0;
-        uint64_t key = ((uint64_t)f2ord(0.0f) << 32) | kArcNone;
-        bool improved = false;
-        if (me) improved = table_min<kLds>(T, sh, p.tok_cap, (uint32_t)p.start_state, key, h);
-        int2 o = p.off2[p.start_state], o2 = p.off2[p.start_state + 1];
-        uint32_t src = kSrcNone | ((o2.x > o.y) ? kSrcHasEps : 0u);
-        log_append(log, p.log_cap, sh, improved, key, h, src, lane);
-      }
-    } else {
-      // ---- emit: prune (step 1) and expand emitting arcs (step 2)
-      const int n_tok = sh->n_tok;
-      const float best = sh->best;
-      const int cut = sh->cut_bin;
-      for (int tile = wave; tile * 64 < n_tok; tile += NW) {
-        int i = tile * 64 + lane;
-        bool alive = false;
-        float cost = 0.0f;
-        int s = -1;
-        if (i < n_tok) {
-          s = T.tok_state[i];
-          cost = T.tok_cost[i];
-          if (s >= 0) {
-            float r = cost - best;
-            alive = !(r > p.beam);
-            if (alive && cut < 255) {
-              int bin = (int)floorf(r * inv);
-              bin = bin > 255 ? 255 : bin;
-              alive = bin <= cut;
-            }
-          }
+    const bool last = f == p.n_frames - 1;
+    bool slow = !fast;
+    if (fast) {
+      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, hist, f, cur, bp, g_tok_state, last);
+      if (outcome == kFrameOverflow) {
+        // redo the frame with the tables in device memory: wipe the LDS table, hand the tokens over
+        const int lo = cur * p.lds_tok_cap;
+        for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
+        for (int i = tid; i < sh->n_tok; i += kBlock) {
+          MG.t_cost[i] = ML.t_cost[i]; MG.t_first[i] = ML.t_first[lo + i];
+          MG.t_eps[i] = ML.t_eps[lo + i]; MG.t_end[i] = ML.t_end[lo + i];
         }
-        int first = 0, deg = 0;
-        if (alive) {
-          int2 o = p.off2[s];
-          first = o.x; deg = o.y - o.x;
-        }
-        unsigned long long am = __ballot(alive);
-        if (lane == 0 && am) atomicAdd(&sh->c_active, (uint32_t)__popcll(am));
-        expand_rows<kLds, true>(p, T, sh, cx, Lrow, log, first, deg, cost, (uint32_t)i, 0.0f, lane);
+        __syncthreads();
+        fast = false; cur = 0; slow = true;
       }
     }
-    __syncthreads();
-
-    // ---- step 3: the emission minimum fixes the frame's cutoff
-    const float m = ord2f(sh->m_ord);
-    if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh->log_n; }
-    __syncthreads();
-    if (sh->n_claim == 0 || sh->fault) break;
-
-    // ---- step 4: epsilon closure, one round per barrier
-    while (sh->n_front > 0) {
-      const int fb = sh->fr_begin, fe = sh->fr_end;
-      __syncthreads();
-      if (tid == 0) sh->n_front = 0;
-      __syncthreads();
-      for (int tile = wave; fb + tile * 64 < fe; tile += NW) {
-        int j = fb + tile * 64 + lane;
-        bool act = false;
-        float cost = 0.0f;
-        int first = 0, deg = 0;
-        uint32_t src_tag = 0;
-        if (j < fe) {
-          LogEntry e = log[j];
-          if (e.src & kSrcHasEps) {
-            uint64_t cur = ld64<kLds>(&T.hval[e.h]);
-            cost = ord2f((uint32_t)(e.key >> 32));
-            act = cur == e.key && !(cost - m > p.beam);
-            if (act) {
-              uint32_t s = ld32<kLds>(&T.hkey[e.h]);
-              int2 o = p.off2[s], o2 = p.off2[s + 1];
-              first = o.y; deg = o2.x - o.y;
-              src_tag = ld32<kLds>(&T.haux[e.h]) | kSrcEps;
-            }
-          }
-        }
-        expand_rows<kLds, false>(p, T, sh, cx, Lrow, log, first, deg, cost, src_tag, m, lane);
+    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, hist, f, cur, bp, g_tok_state, last);
+    if (outcome != kFrameOk) break;
+    cur ^= 1;
+    if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {
+      // the token list fits LDS again
+      const int go = cur * p.g_tok_cap;
+      for (int i = tid; i < sh->n_tok; i += kBlock) {
+        ML.t_cost[i] = MG.t_cost[i]; ML.t_first[i] = MG.t_first[go + i];
+        ML.t_eps[i] = MG.t_eps[go + i]; ML.t_end[i] = MG.t_end[go + i];
       }
-      __syncthreads();
-      if (tid == 0) {
-        sh->fr_begin = fe; sh->fr_end = sh->log_n; sh->rounds++;
-        if (sh->n_front > 0 && sh->rounds >= p.max_eps_iters) sh->status = kStatusEpsDiverged;
-      }
-      __syncthreads();
-      if (sh->status != kStatusOk || sh->fault) break;
-    }
-    if (sh->status != kStatusOk || sh->fault) break;
-    if (sh->n_rec + sh->n_claim > p.bp_cap || sh->n_claim > p.tok_cap) {
-      __syncthreads();
-      if (tid == 0) sh->fault = 1;
-      __syncthreads();
-      break;
-    }
-
-    // ---- step 5 and bookkeeping: every state's winning update writes the token
-    {
-      const float best = ord2f(sh->best_ord);
-      const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh->log_n;
-      int my_surv = 0, my_live = 0;
-      for (int j = tid; j < log_n; j += kBlock) {
-        LogEntry e = log[j];
-        uint64_t cur = ld64<kLds>(&T.hval[e.h]);
-        if (cur != e.key) continue;
-        int idx = (int)ld32<kLds>(&T.haux[e.h]);
-        int s = (int)ld32<kLds>(&T.hkey[e.h]);
-        float cost = ord2f((uint32_t)(e.key >> 32));
-        bool dead = cost - m > p.beam;
-        uint32_t sf = e.src & kSrcMask;
-        int prev = sf == kSrcNone ? -1 : ((e.src & kSrcEps) ? base_cur + (int)sf : base_prev + (int)sf);
-        T.tok_state[idx] = dead ? -1 : s;
-        T.tok_cost[idx] = cost;
-        bp[base_cur + idx] = make_int2((int)(uint32_t)e.key, prev);
-        if (!dead) {
-          my_live++;
-          float r = cost - best;
-          if (!(r > p.beam)) {
-            my_surv++;
-            if (hist_on) {
-              int bin = (int)floorf(r * inv);
-              bin = bin > 255 ? 255 : bin;
-              atomicAdd(&hist[bin], 1u);
-            }
-          }
-        }
-        st32<kLds>(&T.hkey[e.h], kEmptyKey);
-        st64<kLds>(&T.hval[e.h], kEmptyVal);
-      }
-      if (my_surv) atomicAdd(&sh->n_surv, my_surv);
-      if (my_live) atomicAdd(&sh->n_live, my_live);
-    }
-    __syncthreads();
-
-    // ---- close the frame
-    if (wave == 0) {
-      int cut = 255;
-      if (hist_on && sh->n_surv > p.max_active) {
-        // largest bin B whose cumulative count fits max_active (0 if bin 0 alone does not)
-        int loc[4], sum = 0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { loc[k] = (int)hist[lane * 4 + k]; sum += loc[k]; }
-        int incl = wave_incl_scan(sum, lane);
-        int run = incl - sum;
-        int myB = -1;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { run += loc[k]; if (run <= p.max_active) myB = lane * 4 + k; }
-        // cumulative counts are monotone, so the bins that fit form a prefix: take the maximum
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { int t = __shfl_xor(myB, d, 64); myB = t > myB ? t : myB; }
-        cut = myB < 0 ? 0 : myB;
-      }
-      if (lane == 0) {
-        sh->cut_bin = cut;
-        sh->n_tok = sh->n_claim;
-        sh->frame_base = sh->n_rec;
-        sh->n_rec += sh->n_claim;
-        sh->best = ord2f(sh->best_ord);
-        if (f >= 0) {  // the table made at reset is not a decoded frame
-          st_frames++;
-          st_tok += sh->n_live;
-          if (sh->n_live > st_maxtok) st_maxtok = sh->n_live;
-        }
-        st_active += sh->c_active; st_emit += sh->c_emit; st_eps += sh->c_eps; st_cand += sh->c_cand;
-        st_impr += sh->log_n; st_rounds += sh->rounds;
-        sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
-      }
+      fast = true; cur = 0;
     }
     // park the prefetched row in LDS for the next frame
     if (have_next) {
@@ -623,34 +778,47 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     __syncthreads();
   }
 
-  // ---- leave: a frame that produced nothing or overflowed parks the channel
+  // ---- leave: a frame that produced nothing, overflowed or diverged parks the channel
   __syncthreads();
+  int status = kStatusOk;
+  if (outcome == kFrameOverflow || outcome == kFrameRecordsFull) status = kStatusCapacity;
+  else if (outcome == kFrameNoTokens) status = kStatusNoTokens;
+  else if (outcome == kFrameDiverged) status = kStatusEpsDiverged;
+  if (status == kStatusOk) {
+    // tokens leave through device-memory buffer 0
+    const int n = sh->n_tok;
+    if (fast) {
+      const int lo = cur * p.lds_tok_cap;
+      for (int i = tid; i < n; i += kBlock) {
+        MG.t_cost[i] = ML.t_cost[i]; MG.t_first[i] = ML.t_first[lo + i];
+        MG.t_eps[i] = ML.t_eps[lo + i]; MG.t_end[i] = ML.t_end[lo + i];
+      }
+    } else if (cur != 0) {
+      const int go = p.g_tok_cap;
+      for (int i = tid; i < n; i += kBlock) {
+        MG.t_first[i] = MG.t_first[go + i]; MG.t_eps[i] = MG.t_eps[go + i]; MG.t_end[i] = MG.t_end[go + i];
+      }
+    }
+  } else if (outcome != kFrameNoTokens) {
+    // leave the device-memory table empty for the next utterance
+    for (int i = tid; i < p.g_slots; i += kBlock) { stv<false>(&MG.hkey[i], kEmptyKey); stv<false>(&MG.hval[i], kEmptyVal); }
+  }
   if (tid == 0) {
-    int status = sh->status;
-    if (status == kStatusOk && sh->fault) status = kStatusCapacity;
-    if (status == kStatusOk && sh->n_claim == 0) { status = kStatusNoTokens; sh->n_tok = 0; sh->frame_base = sh->n_rec; }
-    sh->status = status;
     cs->status = status;
     cs->n_tok = status == kStatusOk ? sh->n_tok : 0;
-    cs->frame_base = sh->frame_base;
+    cs->frame_base = status == kStatusOk ? sh->frame_base : sh->n_rec;
     cs->n_rec = sh->n_rec;
     cs->best = sh->best;
     cs->cut_bin = sh->cut_bin;
     if (p.do_reset) {
       cs->frames = 0; cs->active_tokens = 0; cs->emit_arcs = 0; cs->eps_arcs = 0; cs->candidates = 0;
-      cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0;
+      cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0; cs->slow_frames = 0;
     }
-    cs->frames += st_frames; cs->active_tokens += st_active; cs->emit_arcs += st_emit; cs->eps_arcs += st_eps;
-    cs->candidates += st_cand; cs->improvements += st_impr; cs->tokens += st_tok; cs->eps_rounds += st_rounds;
-    if (st_maxtok > cs->max_tokens) cs->max_tokens = st_maxtok;
-  }
-  __syncthreads();
-  if (kLds && sh->status == kStatusOk) {
-    for (int i = tid; i < sh->n_tok; i += kBlock) { g_tok_state[i] = T.tok_state[i]; g_tok_cost[i] = T.tok_cost[i]; }
-  }
-  if (!kLds && sh->status != kStatusOk) {
-    // leave the device-memory table empty for the next utterance
-    for (uint32_t i = tid; i < H; i += kBlock) { st32<false>(&T.hkey[i], kEmptyKey); st64<false>(&T.hval[i], kEmptyVal); }
+    cs->frames += sh->a_frames; cs->active_tokens += sh->a_active; cs->emit_arcs += sh->a_emit;
+    cs->eps_arcs += sh->a_eps; cs->candidates += sh->a_cand; cs->improvements += sh->a_impr;
+    cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
+    if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
+    cs->slow_frames += sh->a_slow;
   }
 }
 
@@ -691,7 +859,7 @@ struct BestParams {
   const int32_t *tok_state;
   const float *tok_cost;
   const int2 *bp;
-  const ArcRec *arcs;
+  const int32_t *olabel;    // library arc order
   const int32_t *int2pub;   // library arc order -> caller's numbering
   const float *final_cost;  // or null
   int32_t tok_cap, bp_cap, use_final, capacity;
@@ -710,8 +878,9 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   int32_t *meta = p.out_meta + (size_t)i * 4;
   int32_t *oarcs = p.out_arcs + (size_t)i * p.capacity;
   int32_t *owords = p.out_words + (size_t)i * p.capacity;
+  const int inf_bits = (int)__float_as_uint(__builtin_inff());
   if (cs->status != kStatusOk) {
-    if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
+    if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
   const int n = cs->n_tok, base = cs->frame_base;
@@ -721,10 +890,9 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   uint64_t bestk = kEmptyVal;
   int besti = -1;
   for (int t = lane; t < n; t += 64) {
-    int s = ts[t];
-    if (s < 0) continue;
     float cost = tc[t];
-    if (p.use_final && p.final_cost) cost = cost + p.final_cost[s];
+    if (!(cost < __builtin_inff())) continue;   // dropped by the frame cutoff
+    if (p.use_final && p.final_cost) cost = cost + p.final_cost[ts[t]];
     if (!(cost < __builtin_inff())) continue;
     uint64_t k = ((uint64_t)f2ord(cost) << 32) | (uint32_t)bp[base + t].x;
     if (k < bestk) { bestk = k; besti = t; }
@@ -736,7 +904,7 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
     if (ok < bestk) { bestk = ok; besti = oi; }
   }
   if (besti < 0) {
-    if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
+    if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
   // walk back: lane 0 writes the arcs newest-first into the output row
@@ -757,7 +925,7 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   na = __shfl(na, 0, 64);
   __threadfence_block();
   if (na > max_steps) {
-    if (lane == 0) { meta[0] = kStatusEpsDiverged; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
+    if (lane == 0) { meta[0] = kStatusEpsDiverged; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
   if (na > p.capacity) {
@@ -768,7 +936,7 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
       for (int step = 0; r >= 0 && step < na; ++step) {
         int2 rec = bp[r];
         if ((uint32_t)rec.x == kArcNone) break;
-        if (p.arcs[rec.x].olabel != 0) nw++;
+        if (p.olabel[rec.x] != 0) nw++;
         r = rec.y;
       }
       meta[0] = kStatusBuffer; meta[1] = na; meta[2] = nw; meta[3] = (int)__float_as_uint(ord2f((uint32_t)(bestk >> 32)));
@@ -789,7 +957,7 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   for (int j0 = 0; j0 < na; j0 += 64) {
     int j = j0 + lane;
     int w = 0, a = 0;
-    if (j < na) { a = oarcs[j]; w = p.arcs[a].olabel; }
+    if (j < na) { a = oarcs[j]; w = p.olabel[a]; }
     unsigned long long wm = __ballot(w != 0);
     if (w != 0) owords[nw_total + __popcll(wm & ((1ull << lane) - 1ull))] = w;
     nw_total += __popcll(wm);

@@ -16,9 +16,12 @@ from . import synth
 
 
 def default_hash_log2(w: synth.Workload) -> int:
-    """Table size: the LDS tables hold 2048 tokens per frame at 12, which the beam-limited
-    workloads here stay well below; bigger tables move to device memory."""
-    return 12
+    """Device-memory tables (used by the rare frames that outgrow LDS): 8192 tokens per frame."""
+    return 14
+
+
+# Back-pointer records reserved per frame and channel (the workloads here average 350-500 tokens a frame).
+DEFAULT_RECORDS_PER_FRAME = 1536
 
 
 @dataclass
@@ -41,7 +44,7 @@ class Session:
     """A decoder sized for a workload, bound to torch's current stream."""
 
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
-                 records_per_frame: int = 0, graph_handle=None, biased: bool = True):
+                 records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0):
         import torch
         self.torch = torch
         self.inp = inp
@@ -54,7 +57,8 @@ class Session:
         self.stream = torch.cuda.current_stream()
         self.dh = B.cbd_decoder_create(
             self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
-            hash_log2 if hash_log2 is not None else default_hash_log2(w), 0, records_per_frame, table_location,
+            hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
+            records_per_frame or DEFAULT_RECORDS_PER_FRAME, table_location, lds_token_cap,
             hip_stream=self.stream.cuda_stream)
         self.all = np.arange(w.channels, dtype=np.int32)
         self.capacity = 4 * w.frames + 64

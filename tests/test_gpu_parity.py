@@ -33,16 +33,22 @@ def tiny_inputs(torch, T=100, seed=(0,)):
     return w, g, L, ctxs, offs
 
 
-@pytest.mark.parametrize("table_location,block", [(1, "1024"), (2, "1024"), (1, "256"), (2, "512")])
-def test_tiny_frame_by_frame(torch_cuda, monkeypatch, table_location, block):
-    """Config Tiny: every frame's token table, then words / path / cost / arc counter."""
+@pytest.mark.parametrize("table_location,block,lds_cap", [(1, "1024", 0), (2, "1024", 0), (1, "256", 0), (2, "512", 0),
+                                                          (1, "1024", 192), (1, "512", 64)])
+def test_tiny_frame_by_frame(torch_cuda, monkeypatch, table_location, block, lds_cap):
+    """Config Tiny: every frame's token table, then words / path / cost / arc counter.  With a small
+    LDS capacity most frames outgrow the LDS tables and are redone in device memory, and decoding
+    moves back to LDS whenever the token list fits again."""
     torch = torch_cuda
     monkeypatch.setenv("CBD_BLOCK", block)
     w, g, L, ctxs, offs = tiny_inputs(torch)
     Lh = L.cpu().numpy()
-    dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location)
+    dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location,
+                        lds_token_cap=lds_cap)
     info = B.cbd_decoder_info(dec.dh)
     assert info["tables_in_lds"] == (table_location == 1) and info["block_threads"] == int(block)
+    if lds_cap:
+        assert info["lds_token_cap"] == lds_cap
     try:
         orc = GH.oracle_channels(g, 1, w.beam, w.max_active)[0]
         dec.set_contexts(ctxs, offs)
@@ -57,6 +63,12 @@ def test_tiny_frame_by_frame(torch_cuda, monkeypatch, table_location, block):
         st = dec.stats(0)
         assert st["emit_arcs"] == orc.emit_arcs and st["frames"] == w.frames
         assert st["tokens"] == orc.stat(1) and st["active_tokens"] == orc.stat(2) and st["max_tokens"] == orc.stat(3)
+        if table_location == 2:
+            assert st["slow_frames"] == w.frames
+        elif lds_cap:
+            assert 0 < st["slow_frames"] < w.frames   # both kinds of frames, and switches in both directions
+        else:
+            assert st["slow_frames"] == 0
     finally:
         dec.close()
 
@@ -88,14 +100,14 @@ def test_worked_example_on_gpu(torch_cuda):
 
 
 def run_batch(torch, g, L, ctxs, offs, beam, max_active, chunks, lookup_mode=0, table_location=0, hash_log2=12,
-              use_final=False, partial_check=True, swap=None):
+              use_final=False, partial_check=True, swap=None, lds_token_cap=0):
     """Decode all channels of L on the GPU and one by one on the checker; compare partial results
     after every chunk, final results, tables and counters.  swap = (frame, lists, offsets): replace
     all contexts before that frame (must be a chunk boundary)."""
     C, T, P = L.shape
     Lh = L.cpu().numpy()
     dec = GH.GpuDecoder(g, C, beam, max_active, max_frames=T, lookup_mode=lookup_mode, table_location=table_location,
-                        hash_log2=hash_log2, max_context_arcs=max(1, max(len(x) for x in ctxs),
+                        hash_log2=hash_log2, lds_token_cap=lds_token_cap, max_context_arcs=max(1, max(len(x) for x in ctxs),
                                                                   max((len(x) for x in swap[1]), default=1) if swap else 1))
     try:
         og = OracleGraph.from_graph(g)
@@ -139,13 +151,15 @@ def mid_inputs(torch, C=6, T=48, S=60_000, P=500, sigma=4.0, eps=0.10, finals=Fa
     return g, L, ctxs, offs
 
 
-@pytest.mark.parametrize("table_location", [1, 2])
-def test_multichannel_chunks_and_partials(torch_cuda, table_location):
+@pytest.mark.parametrize("table_location,lds_cap", [(1, 0), (2, 0), (1, 128)])
+def test_multichannel_chunks_and_partials(torch_cuda, table_location, lds_cap):
     """Several channels with their own contexts, ragged chunking, partial traceback per chunk."""
     g, L, ctxs, offs = mid_inputs(torch_cuda)
     s = run_batch(torch_cuda, g, L, ctxs, offs, beam=13.0, max_active=0, chunks=[1, 7, 16, 24],
-                  table_location=table_location)
+                  table_location=table_location, lds_token_cap=lds_cap)
     assert s["eps_arcs"] > 0 and s["improvements"] >= s["tokens"]
+    if lds_cap:
+        assert 0 < s["slow_frames"] < s["frames"]
 
 
 def test_histogram_pruning_engages(torch_cuda):
@@ -245,7 +259,7 @@ def test_error_states(torch_cuda):
     # table too small -> CAPACITY (sticky until reset), never silent truncation
     w, gt, Lt, ctxs, offs = tiny_inputs(torch, T=40)
     for loc in (1, 2):
-        dec = GH.GpuDecoder(gt, 1, w.beam, 0, hash_log2=6, table_location=loc)
+        dec = GH.GpuDecoder(gt, 1, w.beam, 0, hash_log2=7, table_location=loc, lds_token_cap=64)
         try:
             dec.reset()
             dec.advance(Lt, 0, 40)
