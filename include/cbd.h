@@ -203,6 +203,10 @@ int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *l
 
 int32_t cbd_synchronize(cbd_decoder *d);
 
+/* Runs the kernels' wave-level prefix sum and minimum on the current device against plain host loops.
+ * CBD_OK, or CBD_E_HIP with the mismatch in cbd_last_error(). */
+int32_t cbd_selftest(void);
+
 const char *cbd_strerror(int32_t status);
 /* Text of the last CBD_E_HIP / CBD_E_INVALID on this thread. */
 const char *cbd_last_error(void);

@@ -22,7 +22,7 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
     "cbd_set_context", "cbd_set_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_get_tokens",
-    "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_strerror", "cbd_last_error",
+    "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
 
 
@@ -91,6 +91,8 @@ def lib():
     L.cbd_decoder_info.argtypes = [vp, vp, vp, vp, vp]
     L.cbd_synchronize.restype = i32
     L.cbd_synchronize.argtypes = [vp]
+    L.cbd_selftest.restype = i32
+    L.cbd_selftest.argtypes = []
     L.cbd_strerror.restype = C.c_char_p
     L.cbd_strerror.argtypes = [i32]
     L.cbd_last_error.restype = C.c_char_p
@@ -247,6 +249,10 @@ def cbd_decoder_info(d) -> dict:
 
 def cbd_synchronize(d):
     _check(lib().cbd_synchronize(d), "cbd_synchronize")
+
+
+def cbd_selftest():
+    _check(lib().cbd_selftest(), "cbd_selftest")
 
 
 def cbd_strerror(status: int) -> str:

@@ -627,6 +627,45 @@ int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
   return CBD_OK;
 }
 
+int32_t cbd_selftest(void) {
+  // the decode kernel's wave-level prefix sum and minimum against plain host loops
+  int32_t *d_in = nullptr, *d_scan = nullptr;
+  uint32_t *d_min = nullptr;
+  HIPCHK(hipMalloc((void **)&d_in, 128 * sizeof(int32_t)));
+  HIPCHK(hipMalloc((void **)&d_scan, 64 * sizeof(int32_t)));
+  HIPCHK(hipMalloc((void **)&d_min, 64 * sizeof(uint32_t)));
+  int32_t rc = CBD_OK;
+  uint32_t seed = 12345u;
+  for (int trial = 0; trial < 8 && rc == CBD_OK; ++trial) {
+    int32_t in[128], scan[64];
+    uint32_t mn[64];
+    for (int i = 0; i < 128; ++i) {
+      seed = seed * 1664525u + 1013904223u;
+      in[i] = trial == 0 ? 1 : (trial == 1 ? i : (int32_t)(seed >> (i < 64 ? 20 : 0)));
+    }
+    if (trial == 2) for (int i = 64; i < 128; ++i) in[i] = (i == 64 + 63) ? 7 : 1000 + i;   // minimum in the last lane
+    if (trial == 3) for (int i = 64; i < 128; ++i) in[i] = (i == 64) ? 7 : 1000 + i;        // minimum in the first lane
+    hipError_t e = hipMemcpy(d_in, in, sizeof(in), hipMemcpyHostToDevice);
+    if (e == hipSuccess) {
+      hipLaunchKernelGGL(cbd::selftest_kernel, dim3(1), dim3(64), 0, nullptr, d_in, d_scan, d_min);
+      e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipMemcpy(scan, d_scan, sizeof(scan), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(mn, d_min, sizeof(mn), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) { rc = fail(CBD_E_HIP, std::string("selftest: ") + hipGetErrorString(e)); break; }
+    int32_t run = 0;
+    uint32_t want_min = 0xFFFFFFFFu;
+    for (int i = 64; i < 128; ++i) want_min = std::min(want_min, (uint32_t)in[i]);
+    for (int i = 0; i < 64; ++i) {
+      run += in[i];
+      if (scan[i] != run) { rc = fail(CBD_E_HIP, "selftest: wave prefix sum mismatch at lane " + std::to_string(i)); break; }
+      if (mn[i] != want_min) { rc = fail(CBD_E_HIP, "selftest: wave minimum mismatch at lane " + std::to_string(i)); break; }
+    }
+  }
+  (void)hipFree(d_in); (void)hipFree(d_scan); (void)hipFree(d_min);
+  return rc;
+}
+
 int32_t cbd_synchronize(cbd_decoder *d) {
   if (!d) return fail(CBD_E_INVALID, "synchronize: null decoder");
   HIPCHK(hipStreamSynchronize(d->stream));

@@ -128,7 +128,7 @@ struct Shared {
   uint32_t best_ord;   // minimum over all accepted candidates of the frame
   int32_t n_claim;     // states in the table = tokens of the frame
   int32_t log_n;
-  int32_t n_front;     // log entries of the last phase whose state has epsilon-input arcs
+  int32_t n_front[2];  // log entries of the last / the running phase whose state has epsilon-input arcs
   int32_t n_surv;      // tokens within the beam of best
   int32_t n_live;      // tokens that passed the frame cutoff
   int32_t fault;       // capacity overflow seen
@@ -141,7 +141,7 @@ struct Shared {
 };
 
 struct LdsLayout {
-  uint32_t sh, hist, bitmap, ctx, L, hval, hkey, hidx, tfirst, teps, tend, tcost, log, total;
+  uint32_t sh, hist, bitmap, owner, ctx, L, hval, hkey, hidx, tfirst, teps, tend, tcost, log, total;
 };
 
 __host__ __device__ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
@@ -151,7 +151,8 @@ __host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, 
   uint32_t o = 0;
   l.sh = o; o += align_up((uint32_t)sizeof(Shared), 16);
   l.hist = o; o += 256 * 4;
-  l.bitmap = o; o += 256 * 4;
+  l.bitmap = o; o += 512 * 4;
+  l.owner = o; o += 16 * 256;   // per-wave owner map of the first 256 arcs of a tile
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
   l.L = o; o += align_up((uint32_t)num_pdfs * 4, 16);
   l.hval = o; o += (uint32_t)slots * 8;
@@ -182,22 +183,50 @@ __device__ __forceinline__ float ord2f(uint32_t o) {
   return __uint_as_float(b);
 }
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    int t = __shfl_up(v, d, 64);
-    if (lane >= d) v += t;
-  }
-  return v;
+// Cross-lane steps on the DPP path (no LDS round trip).  Lanes that a step does not reach
+// (row/bank masked off, or whose source lies outside the 16-lane row) receive `identity`.
+template <int kCtrl, int kRowMask, int kBankMask>
+__device__ __forceinline__ int dpp_step(int identity, int v) {
+  return __builtin_amdgcn_update_dpp(identity, v, kCtrl, kRowMask, kBankMask, false);
+}
+constexpr int kRowShr1 = 0x111, kRowShr2 = 0x112, kRowShr3 = 0x113, kRowShr4 = 0x114, kRowShr8 = 0x118;
+constexpr int kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+
+// Inclusive prefix sum over the 64 lanes: three shifts inside groups of four, two
+// shifts inside the 16-lane row, then the row totals are carried across rows.
+__device__ __forceinline__ int wave_incl_scan(int v) {
+  int s = v;
+  s += dpp_step<kRowShr1, 0xf, 0xf>(0, v);
+  s += dpp_step<kRowShr2, 0xf, 0xf>(0, v);
+  s += dpp_step<kRowShr3, 0xf, 0xf>(0, v);
+  s += dpp_step<kRowShr4, 0xf, 0xe>(0, s);
+  s += dpp_step<kRowShr8, 0xf, 0xc>(0, s);
+  s += dpp_step<kRowBcast15, 0xa, 0xf>(0, s);
+  s += dpp_step<kRowBcast31, 0xc, 0xf>(0, s);
+  return s;
 }
 
+__device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+// Minimum over the 64 lanes (same ladder with min instead of add), returned in every lane.
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    uint32_t t = (uint32_t)__shfl_xor((int)v, d, 64);
-    v = t < v ? t : v;
-  }
-  return v;
+  const int id = -1;  // 0xFFFFFFFF
+  uint32_t s = v;
+  s = umin32(s, (uint32_t)dpp_step<kRowShr1, 0xf, 0xf>(id, (int)v));
+  s = umin32(s, (uint32_t)dpp_step<kRowShr2, 0xf, 0xf>(id, (int)v));
+  s = umin32(s, (uint32_t)dpp_step<kRowShr3, 0xf, 0xf>(id, (int)v));
+  s = umin32(s, (uint32_t)dpp_step<kRowShr4, 0xf, 0xe>(id, (int)s));
+  s = umin32(s, (uint32_t)dpp_step<kRowShr8, 0xf, 0xc>(id, (int)s));
+  s = umin32(s, (uint32_t)dpp_step<kRowBcast15, 0xa, 0xf>(id, (int)s));
+  s = umin32(s, (uint32_t)dpp_step<kRowBcast31, 0xc, 0xf>(id, (int)s));
+  return (uint32_t)__builtin_amdgcn_readlane((int)s, 63);
+}
+
+// Workgroup barrier.  A frame whose working set is in LDS only has to order LDS traffic;
+// outstanding HBM loads and stores (the next log-likelihood row, back-pointer records) keep flying.
+template <bool kLds> __device__ __forceinline__ void wg_barrier() {
+  if (kLds) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  else __syncthreads();
 }
 
 // Accessors for values that other waves change with atomics.
@@ -220,7 +249,9 @@ __device__ __forceinline__ bool sorted_contains(const int32_t *list, int n, int3
   return lo < n && list[lo] == a;
 }
 
-__device__ __forceinline__ uint32_t bitmap_bit(int32_t a) { return ((uint32_t)a * 2654435761u) >> 19; }  // 13 bits
+constexpr int kBloomWords = 512;  // 16K bits, two hash functions
+__device__ __forceinline__ uint32_t bloom_bit0(int32_t a) { return ((uint32_t)a * 2654435761u) >> 18; }
+__device__ __forceinline__ uint32_t bloom_bit1(int32_t a) { return ((uint32_t)a * 2246822519u + 0x9E3779B9u) >> 18; }
 
 struct Ctx {
   const int32_t *lds_list;
@@ -235,8 +266,9 @@ struct Ctx {
 __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
   if (cx.n == 0) return false;
   if (cx.use_bitmap) {
-    uint32_t b = bitmap_bit(a);
-    if (!((cx.bitmap[b >> 5] >> (b & 31)) & 1u)) return false;
+    uint32_t b0 = bloom_bit0(a), b1 = bloom_bit1(a);
+    uint32_t w0 = cx.bitmap[b0 >> 5], w1 = cx.bitmap[b1 >> 5];
+    if (!((w0 >> (b0 & 31)) & (w1 >> (b1 & 31)) & 1u)) return false;
   }
   if (cx.in_lds) return sorted_contains(cx.lds_list, cx.n, a);
   return sorted_contains(cx.g_list, cx.n, a);
@@ -279,19 +311,16 @@ __device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, int no
                                           const RowInfo &row, uint32_t &h_out) {
   uint32_t h = __umulhi(state * 2654435761u, M.slots);
   for (uint32_t probe = 0; probe < M.slots; ++probe) {
-    uint32_t k = ldv<kLds>(&M.hkey[h]);
-    if (k == kEmptyKey) {
-      k = atomicCAS(&M.hkey[h], kEmptyKey, state);
+    // most candidates open a new state: try to take the slot straight away
+    uint32_t k = atomicCAS(&M.hkey[h], kEmptyKey, state);
+    if (k == kEmptyKey || k == state) {
+      uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
       if (k == kEmptyKey) {
         int idx = atomicAdd(&sh->n_claim, 1);
         if (idx >= M.tok_cap) { sh->fault = 1; idx = M.tok_cap - 1; }
         else { M.t_first[no + idx] = row.first; M.t_eps[no + idx] = row.eps; M.t_end[no + idx] = row.end; }
         stv<kLds>(&M.hidx[h], (typename Mem<kLds>::idx_t)idx);
-        k = state;
       }
-    }
-    if (k == state) {
-      uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
       h_out = h;
       return old > key;
     }
@@ -304,8 +333,8 @@ __device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, int no
 
 // Append the updates of this wave's lanes to the channel's change log.
 template <bool kLds>
-__device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, bool improved, uint32_t arc, uint32_t h,
-                                           uint32_t src, int lane) {
+__device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, int32_t *front, bool improved, uint32_t arc,
+                                           uint32_t h, uint32_t src, int lane) {
   unsigned long long mask = __ballot(improved);
   if (mask == 0) return;
   int leader = __ffsll((long long)mask) - 1;
@@ -314,9 +343,9 @@ __device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, bool 
   int base = 0;
   if (lane == leader) {
     base = atomicAdd(&sh->log_n, n);
-    if (nf) atomicAdd(&sh->n_front, nf);
+    if (nf) atomicAdd(front, nf);
   }
-  base = __shfl(base, leader, 64);
+  base = __builtin_amdgcn_readlane(base, leader);
   if (improved) {
     int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
     if (pos < M.log_cap) {
@@ -330,19 +359,24 @@ __device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, bool 
 }
 
 // The wave's arc list: lane i contributes `deg` arcs starting at `first`.
-struct ArcList { int pos, rel, total; };
+struct ArcList { int pos, rel, total; uint8_t *owner; };
+constexpr int kOwnerMap = 256;   // list positions covered by the per-wave owner map
 
-__device__ __forceinline__ ArcList make_arc_list(int first, int deg, int lane) {
+__device__ __forceinline__ ArcList make_arc_list(int first, int deg, int lane, uint8_t *owner_map) {
   ArcList L;
-  int incl = wave_incl_scan(deg, lane);
+  int incl = wave_incl_scan(deg);
   L.pos = incl - deg;
   L.rel = first - L.pos;   // arc index = rel(owner) + position in the list
-  L.total = __shfl(incl, 63, 64);
+  L.total = __builtin_amdgcn_readlane(incl, 63);
+  L.owner = owner_map;
+  // every contributing lane signs the positions it owns (rows are short: a few stores)
+  for (int k = 0; k < deg && L.pos + k < kOwnerMap; ++k) owner_map[L.pos + k] = (uint8_t)lane;
   return L;
 }
 
-// owner of list position jj = last lane whose first position is <= jj
-__device__ __forceinline__ int arc_owner(const ArcList &L, int jj) {
+// owner of list position jj: from the map, or (long lists) the last lane whose first position is <= jj
+__device__ __forceinline__ int arc_owner(const ArcList &L, int jj, int j0) {
+  if (j0 + 64 <= kOwnerMap) return L.owner[jj < kOwnerMap ? jj : 0];   // j0 is uniform
   int owner = 0;
 #pragma unroll
   for (int step = 32; step >= 1; step >>= 1) {
@@ -355,8 +389,9 @@ __device__ __forceinline__ int arc_owner(const ArcList &L, int jj) {
 
 // Cutoff test, recombination and logging of one candidate per lane (called by whole waves).
 template <bool kLds, bool kEmit>
-__device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no, bool act,
-                                       float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed, int lane) {
+__device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front, int no,
+                                       bool act, float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed,
+                                       int lane) {
   bool pass = false;
   if (act) {
     float mref = kEmit ? ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) : m_fixed;
@@ -379,19 +414,19 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
     uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
     improved = table_min<kLds>(M, sh, no, (uint32_t)rec.dst, key, row, h);
   }
-  log_append<kLds>(M, sh, improved, (uint32_t)a, h, src, lane);
+  log_append<kLds>(M, sh, front, improved, (uint32_t)a, h, src, lane);
 }
 
 // Expand positions [j_begin, total) of the wave's arc list, one lane per arc, committing
 // each candidate at once (closure rounds, and the rare emit overflow beyond the register batch).
 template <bool kLds, bool kEmit>
-__device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
-                                              const float *Lrow, int no, const ArcList &AL, int j_begin, float cost,
-                                              uint32_t src_tag, float m_fixed, int lane) {
+__device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
+                                              const Ctx &cx, const float *Lrow, int no, const ArcList &AL, int j_begin,
+                                              float cost, uint32_t src_tag, float m_fixed, int lane) {
   for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
     int jj = j0 + lane;
     bool act = jj < AL.total;
-    int owner = arc_owner(AL, jj);
+    int owner = arc_owner(AL, jj, j0);
     int a = __shfl(AL.rel, owner, 64) + jj;
     float c_own = __shfl(cost, owner, 64);
     uint32_t s_own = (uint32_t)__shfl((int)src_tag, owner, 64);
@@ -408,7 +443,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
       if (lane == 0) atomicMin(&sh->m_ord, wmin);
     }
-    commit<kLds, kEmit>(p, M, sh, no, act, cand, a, rec, s_own, m_fixed, lane);
+    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, lane);
   }
 }
 
@@ -418,23 +453,24 @@ constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimu
 // Nothing that outlives the frame is written before the capacity checks have passed.
 template <bool kLds, int kBlock>
 __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
-                                         const float *Lrow, uint32_t *hist, int f, int cur, int2 *bp,
-                                         int32_t *g_tok_state, bool last_frame) {
+                                         const float *Lrow, uint32_t *hist, uint8_t *owner_maps, int f, int cur,
+                                         int2 *bp, int32_t *g_tok_state, bool last_frame) {
   constexpr int NW = kBlock / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int co = cur * M.tok_cap, no = (cur ^ 1) * M.tok_cap;   // token buffer read / built
   const bool hist_on = p.max_active > 0 && p.beam > 0.0f && p.beam < __builtin_inff();
   const float inv = 256.0f / p.beam;
   typedef LogT<kLds> LogE;
+  uint8_t *owner_map = owner_maps + wave * kOwnerMap;
 
   if (tid == 0) {
     sh->m_ord = f < 0 ? f2ord(0.0f) : 0xFFFFFFFFu;
-    sh->n_claim = 0; sh->log_n = 0; sh->n_front = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
+    sh->n_claim = 0; sh->log_n = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
     sh->fault = 0; sh->diverged = 0;
     sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
   }
   for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
-  __syncthreads();
+  wg_barrier<kLds>();
 
   if (f < 0) {
     // reset: one start token at cost 0
@@ -446,7 +482,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       RowInfo row; row.first = o.x; row.eps = o.y; row.end = o2.x;
       if (lane == 0) improved = table_min<kLds>(M, sh, no, (uint32_t)p.start_state, key, row, h);
       uint32_t src = LogE::kSrcNone | ((row.end > row.eps) ? LogE::kSrcHasEps : 0u);
-      log_append<kLds>(M, sh, improved, kArcNone, h, src, lane);
+      log_append<kLds>(M, sh, &sh->n_front[0], improved, kArcNone, h, src, lane);
     }
   } else {
     // ---- emit: prune (step 1), expand emitting arcs (step 2), in batches of one tile per wave
@@ -472,7 +508,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         if (alive) { first = M.t_first[co + i]; deg = M.t_eps[co + i] - first; }
       }
       unsigned long long am = __ballot(alive);
-      ArcList AL = make_arc_list(first, deg, lane);
+      ArcList AL = make_arc_list(first, deg, lane, owner_map);
       if (lane == 0 && am) { atomicAdd(&sh->c_active, (uint32_t)__popcll(am)); atomicAdd(&sh->c_emit, (uint32_t)AL.total); }
       // phase A: fetch up to kEmitSlots arcs per lane, keep the candidates in registers
       float cand[kEmitSlots];
@@ -487,7 +523,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         cand[r] = 0.0f; arc[r] = 0; srct[r] = 0;
         rec[r].dst = 0; rec[r].weight = 0.0f; rec[r].row = 0; rec[r].meta = 0;
         if (r * 64 < AL.total) {   // uniform
-          int owner = arc_owner(AL, jj);
+          int owner = arc_owner(AL, jj, r * 64);
           arc[r] = __shfl(AL.rel, owner, 64) + jj;
           float c_own = __shfl(cost, owner, 64);
           srct[r] = (uint32_t)(tile0 + owner);
@@ -503,35 +539,34 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       }
       uint32_t wmin = wave_min_u32(lmin);
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
-      __syncthreads();   // the batch minimum is known: few doomed candidates reach the table
+      wg_barrier<kLds>();   // the batch minimum is known: few doomed candidates reach the table
       // phase B: cutoff, recombination
 #pragma unroll
       for (int r = 0; r < kEmitSlots; ++r) {
         if (r * 64 < AL.total) {
           bool act = r * 64 + lane < AL.total;
-          commit<kLds, true>(p, M, sh, no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, lane);
+          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, lane);
         }
       }
       if (AL.total > kEmitSlots * 64)
-        expand_direct<kLds, true>(p, M, sh, cx, Lrow, no, AL, kEmitSlots * 64, cost, (uint32_t)(tile0 + lane), 0.0f,
-                                  lane);
+        expand_direct<kLds, true>(p, M, sh, &sh->n_front[0], cx, Lrow, no, AL, kEmitSlots * 64, cost,
+                                  (uint32_t)(tile0 + lane), 0.0f, lane);
     }
   }
-  __syncthreads();
+  wg_barrier<kLds>();
 
   // ---- step 3: the emission minimum fixes the frame's cutoff
   const float m = ord2f(sh->m_ord);
   if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh->log_n; }
-  __syncthreads();
+  wg_barrier<kLds>();
   if (sh->fault) return kFrameOverflow;
   if (sh->n_claim == 0) return kFrameNoTokens;
 
-  // ---- step 4: epsilon closure, one round per barrier pair
-  while (sh->n_front > 0) {
+  // ---- step 4: epsilon closure; round r reads the entries logged in round r-1 and counts the
+  // entries it logs for round r+1 in the other counter
+  for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
     const int fb = sh->fr_begin, fe = sh->fr_end;
-    __syncthreads();
-    if (tid == 0) sh->n_front = 0;
-    __syncthreads();
+    int32_t *front = &sh->n_front[(r + 1) & 1];
     for (int tile = wave; fb + tile * 64 < fe; tile += NW) {
       int j = fb + tile * 64 + lane;
       float cost = 0.0f;
@@ -551,17 +586,18 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
           }
         }
       }
-      ArcList AL = make_arc_list(first, deg, lane);
+      ArcList AL = make_arc_list(first, deg, lane, owner_map);
       if (AL.total == 0) continue;
       if (lane == 0) atomicAdd(&sh->c_eps, (uint32_t)AL.total);
-      expand_direct<kLds, false>(p, M, sh, cx, Lrow, no, AL, 0, cost, src_tag, m, lane);
+      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, src_tag, m, lane);
     }
-    __syncthreads();
+    wg_barrier<kLds>();
     if (tid == 0) {
       sh->fr_begin = fe; sh->fr_end = sh->log_n; sh->rounds++;
-      if (sh->n_front > 0 && sh->rounds >= p.max_eps_iters) sh->diverged = 1;
+      sh->n_front[r & 1] = 0;
+      if (*front > 0 && sh->rounds >= p.max_eps_iters) sh->diverged = 1;
     }
-    __syncthreads();
+    wg_barrier<kLds>();
     if (sh->diverged || sh->fault) break;
   }
   if (sh->fault) return kFrameOverflow;
@@ -605,7 +641,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     if (my_surv) atomicAdd(&sh->n_surv, my_surv);
     if (my_live) atomicAdd(&sh->n_live, my_live);
   }
-  __syncthreads();
+  wg_barrier<kLds>();
 
   // ---- close the frame
   if (wave == 0) {
@@ -615,7 +651,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       int loc[4], sum = 0;
 #pragma unroll
       for (int k = 0; k < 4; ++k) { loc[k] = (int)hist[lane * 4 + k]; sum += loc[k]; }
-      int incl = wave_incl_scan(sum, lane);
+      int incl = wave_incl_scan(sum);
       int run = incl - sum;
       int myB = -1;
 #pragma unroll
@@ -641,7 +677,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       sh->a_impr += sh->log_n; sh->a_rounds += sh->rounds;
     }
   }
-  __syncthreads();
+  wg_barrier<kLds>();
   return kFrameOk;
 }
 
@@ -656,6 +692,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   Shared *sh = (Shared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
+  uint8_t *owner_maps = (uint8_t *)(smem + lay.owner);
   int32_t *ctx_lds = (int32_t *)(smem + lay.ctx);
   float *Lrow = (float *)(smem + lay.L);
 
@@ -707,11 +744,12 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   cx.use_bitmap = p.lookup_mode == 1;
   if (cx.in_lds) for (int i = tid; i < cx.n; i += kBlock) ctx_lds[i] = cx.g_list[i];
   if (cx.use_bitmap) {
-    for (int i = tid; i < 256; i += kBlock) bitmap[i] = 0;
+    for (int i = tid; i < kBloomWords; i += kBlock) bitmap[i] = 0;
     __syncthreads();
     for (int i = tid; i < cx.n; i += kBlock) {
-      uint32_t b = bitmap_bit(cx.g_list[i]);
-      atomicOr(&bitmap[b >> 5], 1u << (b & 31));
+      uint32_t b0 = bloom_bit0(cx.g_list[i]), b1 = bloom_bit1(cx.g_list[i]);
+      atomicOr(&bitmap[b0 >> 5], 1u << (b0 & 31));
+      atomicOr(&bitmap[b1 >> 5], 1u << (b1 & 31));
     }
   }
   // tokens enter through device-memory buffer 0; LDS takes them over when they fit
@@ -741,7 +779,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     const bool last = f == p.n_frames - 1;
     bool slow = !fast;
     if (fast) {
-      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, hist, f, cur, bp, g_tok_state, last);
+      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, hist, owner_maps, f, cur, bp, g_tok_state, last);
       if (outcome == kFrameOverflow) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the tokens over
         const int lo = cur * p.lds_tok_cap;
@@ -754,7 +792,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         fast = false; cur = 0; slow = true;
       }
     }
-    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, hist, f, cur, bp, g_tok_state, last);
+    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, hist, owner_maps, f, cur, bp, g_tok_state, last);
     if (outcome != kFrameOk) break;
     cur ^= 1;
     if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {
@@ -820,6 +858,15 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
     cs->slow_frames += sh->a_slow;
   }
+}
+
+// ---- self-test of the cross-lane primitives ------------------------------------
+
+// One wave: prefix sums of in[0..63] and the minimum of in[64..127] (as unsigned).
+__global__ __launch_bounds__(64) void selftest_kernel(const int32_t *in, int32_t *out_scan, uint32_t *out_min) {
+  int lane = threadIdx.x;
+  out_scan[lane] = wave_incl_scan(in[lane]);
+  out_min[lane] = wave_min_u32((uint32_t)in[64 + lane]);
 }
 
 // ---- contexts ---------------------------------------------------------------

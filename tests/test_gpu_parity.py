@@ -25,6 +25,11 @@ def torch_cuda():
     return torch
 
 
+def test_wave_primitives_selftest(torch_cuda):
+    """The DPP prefix sum / minimum the kernels rely on, against host loops."""
+    B.cbd_selftest()
+
+
 def tiny_inputs(torch, T=100, seed=(0,)):
     w = synth.WORKLOADS["tiny"]
     g = synth.graph_for(w)
