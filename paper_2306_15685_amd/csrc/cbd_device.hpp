@@ -126,8 +126,7 @@ struct AdvanceParams {
 struct Shared {
   uint32_t m_ord;      // running minimum of emitting candidates (orderable bits)
   uint32_t best_ord;   // minimum over all accepted candidates of the frame
-  int32_t n_claim;     // states in the table = tokens of the frame
-  int32_t log_n;
+  unsigned long long log_claim;  // low 32 bits: change-log entries; high 32 bits: states in the table (= tokens)
   int32_t n_front[2];  // log entries of the last / the running phase whose state has epsilon-input arcs
   int32_t n_surv;      // tokens within the beam of best
   int32_t n_live;      // tokens that passed the frame cutoff
@@ -139,6 +138,9 @@ struct Shared {
   int32_t a_maxtok, a_slow;   // counters of this call
   long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
+
+__device__ __forceinline__ int sh_log_n(const Shared *sh) { return (int)(uint32_t)sh->log_claim; }
+__device__ __forceinline__ int sh_n_claim(const Shared *sh) { return (int)(uint32_t)(sh->log_claim >> 32); }
 
 struct LdsLayout {
   uint32_t sh, hist, bitmap, owner, ctx, L, hval, hkey, hidx, tfirst, teps, tend, tcost, log, total;
@@ -303,24 +305,19 @@ __device__ __forceinline__ RowInfo row_of(const AdvanceParams &p, const ArcRec &
 }
 
 // Recombination: E[state] = min key.  Returns true if this call lowered the
-// state's value (old > key); h receives the slot.  The lane that creates the
-// state's entry also files the state's row under the entry's token index
-// (no = offset of the token buffer being built).
+// state's value (old > key); h receives the slot, claimed tells whether this
+// lane created the state's entry.
 template <bool kLds>
-__device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, int no, uint32_t state, uint64_t key,
-                                          const RowInfo &row, uint32_t &h_out) {
+__device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, uint32_t state, uint64_t key, uint32_t &h_out,
+                                          bool &claimed) {
   uint32_t h = __umulhi(state * 2654435761u, M.slots);
+  claimed = false;
   for (uint32_t probe = 0; probe < M.slots; ++probe) {
     // most candidates open a new state: try to take the slot straight away
     uint32_t k = atomicCAS(&M.hkey[h], kEmptyKey, state);
     if (k == kEmptyKey || k == state) {
       uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
-      if (k == kEmptyKey) {
-        int idx = atomicAdd(&sh->n_claim, 1);
-        if (idx >= M.tok_cap) { sh->fault = 1; idx = M.tok_cap - 1; }
-        else { M.t_first[no + idx] = row.first; M.t_eps[no + idx] = row.eps; M.t_end[no + idx] = row.end; }
-        stv<kLds>(&M.hidx[h], (typename Mem<kLds>::idx_t)idx);
-      }
+      claimed = k == kEmptyKey;
       h_out = h;
       return old > key;
     }
@@ -331,23 +328,39 @@ __device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, int no
   return false;
 }
 
-// Append the updates of this wave's lanes to the channel's change log.
+// Book the updates of this wave's lanes: one atomic on the packed counter yields the
+// change-log positions and, for lanes that created a state, the token indices; those
+// lanes file the state's row under their index (no = offset of the token buffer being built).
 template <bool kLds>
-__device__ __forceinline__ void log_append(const Mem<kLds> &M, Shared *sh, int32_t *front, bool improved, uint32_t arc,
-                                           uint32_t h, uint32_t src, int lane) {
-  unsigned long long mask = __ballot(improved);
-  if (mask == 0) return;
-  int leader = __ffsll((long long)mask) - 1;
-  int n = __popcll(mask);
+__device__ __forceinline__ void record(const Mem<kLds> &M, Shared *sh, int32_t *front, int no, bool improved,
+                                       bool claimed, uint32_t arc, uint32_t h, uint32_t src, const RowInfo &row,
+                                       int lane) {
+  unsigned long long imask = __ballot(improved);
+  unsigned long long cmask = __ballot(claimed);
+  // (a lane can create a state's entry and still lose the minimum to a lane of another wave
+  // that reached the value first: it must get its token index all the same)
+  if ((imask | cmask) == 0) return;
+  int leader = __ffsll((long long)(imask | cmask)) - 1;
   int nf = __popcll(__ballot(improved && (src & LogT<kLds>::kSrcHasEps)));
-  int base = 0;
+  unsigned long long base = 0;
   if (lane == leader) {
-    base = atomicAdd(&sh->log_n, n);
+    base = atomicAdd(&sh->log_claim, (unsigned long long)__popcll(imask) | ((unsigned long long)__popcll(cmask) << 32));
     if (nf) atomicAdd(front, nf);
   }
-  base = __builtin_amdgcn_readlane(base, leader);
+  int base_log = __builtin_amdgcn_readlane((int)(uint32_t)base, leader);
+  int base_tok = __builtin_amdgcn_readlane((int)(uint32_t)(base >> 32), leader);
+  unsigned long long below = (1ull << lane) - 1ull;
+  if (claimed) {
+    int idx = base_tok + __popcll(cmask & below);
+    if (idx < M.tok_cap) {
+      M.t_first[no + idx] = row.first; M.t_eps[no + idx] = row.eps; M.t_end[no + idx] = row.end;
+      stv<kLds>(&M.hidx[h], (typename Mem<kLds>::idx_t)idx);
+    } else {
+      sh->fault = 1;
+    }
+  }
   if (improved) {
-    int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+    int pos = base_log + __popcll(imask & below);
     if (pos < M.log_cap) {
       LogT<kLds> e;
       e.arc = arc; e.h = (decltype(e.h))h; e.src = (decltype(e.src))src;
@@ -388,33 +401,36 @@ __device__ __forceinline__ int arc_owner(const ArcList &L, int jj, int j0) {
 }
 
 // Cutoff test, recombination and logging of one candidate per lane (called by whole waves).
+// n_cand counts the candidates that passed the cutoff (same value in every lane).
 template <bool kLds, bool kEmit>
 __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front, int no,
                                        bool act, float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed,
-                                       int lane) {
+                                       uint32_t &n_cand, int lane) {
   bool pass = false;
+  const int fault = __hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   if (act) {
     float mref = kEmit ? ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) : m_fixed;
     pass = !(cand - mref > p.beam);
   }
   unsigned long long pmask = __ballot(pass);
   if (pmask == 0) return;
+  n_cand += (uint32_t)__popcll(pmask);
   uint32_t co = pass ? f2ord(cand) : 0xFFFFFFFFu;
   if (!kEmit) {
     uint32_t wmin = wave_min_u32(co);
     if (lane == 0) atomicMin(&sh->best_ord, wmin);
   }
-  if (lane == 0) atomicAdd(&sh->c_cand, (uint32_t)__popcll(pmask));
-  bool improved = false;
+  bool improved = false, claimed = false;
   uint32_t h = 0;
   uint32_t src = src_tag;
-  if (pass && !__hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) {
-    RowInfo row = row_of(p, rec);
+  RowInfo row; row.first = row.eps = row.end = 0;
+  if (pass && !fault) {
+    row = row_of(p, rec);
     if (row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;
     uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
-    improved = table_min<kLds>(M, sh, no, (uint32_t)rec.dst, key, row, h);
+    improved = table_min<kLds>(M, sh, (uint32_t)rec.dst, key, h, claimed);
   }
-  log_append<kLds>(M, sh, front, improved, (uint32_t)a, h, src, lane);
+  record<kLds>(M, sh, front, no, improved, claimed, (uint32_t)a, h, src, row, lane);
 }
 
 // Expand positions [j_begin, total) of the wave's arc list, one lane per arc, committing
@@ -422,7 +438,7 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
 template <bool kLds, bool kEmit>
 __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
                                               const Ctx &cx, const float *Lrow, int no, const ArcList &AL, int j_begin,
-                                              float cost, uint32_t src_tag, float m_fixed, int lane) {
+                                              float cost, uint32_t src_tag, float m_fixed, uint32_t &n_cand, int lane) {
   for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
     int jj = j0 + lane;
     bool act = jj < AL.total;
@@ -443,7 +459,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
       if (lane == 0) atomicMin(&sh->m_ord, wmin);
     }
-    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, lane);
+    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane);
   }
 }
 
@@ -465,24 +481,25 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 
   if (tid == 0) {
     sh->m_ord = f < 0 ? f2ord(0.0f) : 0xFFFFFFFFu;
-    sh->n_claim = 0; sh->log_n = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
+    sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
     sh->fault = 0; sh->diverged = 0;
     sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
   }
   for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
   wg_barrier<kLds>();
 
+  uint32_t n_active = 0, n_emit = 0, n_eps = 0, n_cand = 0;   // this wave's share of the frame's counters
   if (f < 0) {
     // reset: one start token at cost 0
     if (wave == 0) {
       uint32_t h = 0;
       uint64_t key = ((uint64_t)f2ord(0.0f) << 32) | kArcNone;
-      bool improved = false;
+      bool improved = false, claimed = false;
       int2 o = p.off2[p.start_state], o2 = p.off2[p.start_state + 1];
       RowInfo row; row.first = o.x; row.eps = o.y; row.end = o2.x;
-      if (lane == 0) improved = table_min<kLds>(M, sh, no, (uint32_t)p.start_state, key, row, h);
+      if (lane == 0) improved = table_min<kLds>(M, sh, (uint32_t)p.start_state, key, h, claimed);
       uint32_t src = LogE::kSrcNone | ((row.end > row.eps) ? LogE::kSrcHasEps : 0u);
-      log_append<kLds>(M, sh, &sh->n_front[0], improved, kArcNone, h, src, lane);
+      record<kLds>(M, sh, &sh->n_front[0], no, improved, claimed, kArcNone, h, src, row, lane);
     }
   } else {
     // ---- emit: prune (step 1), expand emitting arcs (step 2), in batches of one tile per wave
@@ -491,12 +508,16 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     const int cut = sh->cut_bin;
     const int n_batches = (n_tok + kBlock - 1) / kBlock;
     for (int b = 0; b < n_batches; ++b) {
-      const int tile0 = (b * NW + wave) * 64;
+      // a batch holds up to kBlock tokens, shared evenly by the waves: with few tokens every
+      // wave still gets some, and each lane ends up with about one arc
+      const int nb = min(kBlock, n_tok - b * kBlock);
+      const int tpw = (nb + NW - 1) / NW;
+      const int tile0 = b * kBlock + wave * tpw;
       int i = tile0 + lane;
       bool alive = false;
       float cost = 0.0f;
       int first = 0, deg = 0;
-      if (i < n_tok) {
+      if (lane < tpw && i < b * kBlock + nb) {
         cost = M.t_cost[i];
         float r = cost - best;
         alive = !(r > p.beam) && cost < __builtin_inff();
@@ -509,7 +530,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       }
       unsigned long long am = __ballot(alive);
       ArcList AL = make_arc_list(first, deg, lane, owner_map);
-      if (lane == 0 && am) { atomicAdd(&sh->c_active, (uint32_t)__popcll(am)); atomicAdd(&sh->c_emit, (uint32_t)AL.total); }
+      n_active += (uint32_t)__popcll(am); n_emit += (uint32_t)AL.total;
       // phase A: fetch up to kEmitSlots arcs per lane, keep the candidates in registers
       float cand[kEmitSlots];
       int arc[kEmitSlots];
@@ -545,30 +566,34 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       for (int r = 0; r < kEmitSlots; ++r) {
         if (r * 64 < AL.total) {
           bool act = r * 64 + lane < AL.total;
-          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, lane);
+          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane);
         }
       }
       if (AL.total > kEmitSlots * 64)
         expand_direct<kLds, true>(p, M, sh, &sh->n_front[0], cx, Lrow, no, AL, kEmitSlots * 64, cost,
-                                  (uint32_t)(tile0 + lane), 0.0f, lane);
+                                  (uint32_t)(tile0 + lane), 0.0f, n_cand, lane);
     }
   }
   wg_barrier<kLds>();
 
   // ---- step 3: the emission minimum fixes the frame's cutoff
   const float m = ord2f(sh->m_ord);
-  if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh->log_n; }
+  if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh_log_n(sh); }
   wg_barrier<kLds>();
   if (sh->fault) return kFrameOverflow;
-  if (sh->n_claim == 0) return kFrameNoTokens;
+  if (sh_n_claim(sh) == 0) return kFrameNoTokens;
 
   // ---- step 4: epsilon closure; round r reads the entries logged in round r-1 and counts the
   // entries it logs for round r+1 in the other counter
   for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
     const int fb = sh->fr_begin, fe = sh->fr_end;
     int32_t *front = &sh->n_front[(r + 1) & 1];
-    for (int tile = wave; fb + tile * 64 < fe; tile += NW) {
-      int j = fb + tile * 64 + lane;
+    for (int base = fb; base < fe; base += kBlock) {
+      // the round's entries are shared evenly by the waves
+      const int nb = min(kBlock, fe - base);
+      const int tpw = (nb + NW - 1) / NW;
+      int j = lane < tpw ? base + wave * tpw + lane : fe;
+      if (j >= base + nb) j = fe;
       float cost = 0.0f;
       int first = 0, deg = 0;
       uint32_t src_tag = 0;
@@ -588,12 +613,12 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       }
       ArcList AL = make_arc_list(first, deg, lane, owner_map);
       if (AL.total == 0) continue;
-      if (lane == 0) atomicAdd(&sh->c_eps, (uint32_t)AL.total);
-      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, src_tag, m, lane);
+      n_eps += (uint32_t)AL.total;
+      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, src_tag, m, n_cand, lane);
     }
     wg_barrier<kLds>();
     if (tid == 0) {
-      sh->fr_begin = fe; sh->fr_end = sh->log_n; sh->rounds++;
+      sh->fr_begin = fe; sh->fr_end = sh_log_n(sh); sh->rounds++;
       sh->n_front[r & 1] = 0;
       if (*front > 0 && sh->rounds >= p.max_eps_iters) sh->diverged = 1;
     }
@@ -602,44 +627,56 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   }
   if (sh->fault) return kFrameOverflow;
   if (sh->diverged) return kFrameDiverged;
-  if (sh->n_rec + sh->n_claim > p.bp_cap) return kFrameRecordsFull;
+  if (sh->n_rec + sh_n_claim(sh) > p.bp_cap) return kFrameRecordsFull;
 
   // ---- step 5 and bookkeeping: every state's winning update writes the token
   {
     const float best = ord2f(sh->best_ord);
-    const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh->log_n;
-    int my_surv = 0, my_live = 0;
-    for (int j = tid; j < log_n; j += kBlock) {
+    const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh_log_n(sh);
+    int w_surv = 0, w_live = 0;   // per wave, counted with ballots (same-address LDS atomics from many lanes crawl)
+    for (int j0 = wave * 64; j0 < log_n; j0 += kBlock) {
+      const int j = j0 + lane;
+      bool live = false, surv = false;
+      if (j < log_n) {
       LogE e = M.log[j];
       uint64_t curv = ldv<kLds>(&M.hval[e.h]);
-      if ((uint32_t)curv != e.arc || curv == kEmptyVal) continue;
       // an arc can appear twice for a slot (its source improved in a later round): one of them takes the slot
-      if (atomicCAS((unsigned long long *)&M.hval[e.h], (unsigned long long)curv, (unsigned long long)kEmptyVal) != curv)
-        continue;
-      int idx = (int)ldv<kLds>(&M.hidx[e.h]);
-      float cost = ord2f((uint32_t)(curv >> 32));
-      bool dead = cost - m > p.beam;
-      uint32_t sf = e.src & LogE::kSrcMask;
-      int prev = sf == LogE::kSrcNone ? -1 : ((e.src & LogE::kSrcEps) ? base_cur + (int)sf : base_prev + (int)sf);
-      M.t_cost[idx] = dead ? __builtin_inff() : cost;
-      bp[base_cur + idx] = make_int2((int)e.arc, prev);
-      if (last_frame) g_tok_state[idx] = (int)ldv<kLds>(&M.hkey[e.h]);
-      if (!dead) {
-        my_live++;
-        float r = cost - best;
-        if (!(r > p.beam)) {
-          my_surv++;
-          if (hist_on) {
-            int bin = (int)floorf(r * inv);
-            bin = bin > 255 ? 255 : bin;
-            atomicAdd(&hist[bin], 1u);
+      if ((uint32_t)curv == e.arc && curv != kEmptyVal &&
+          atomicCAS((unsigned long long *)&M.hval[e.h], (unsigned long long)curv, (unsigned long long)kEmptyVal) == curv) {
+        int idx = (int)ldv<kLds>(&M.hidx[e.h]);
+        float cost = ord2f((uint32_t)(curv >> 32));
+        bool dead = cost - m > p.beam;
+        uint32_t sf = e.src & LogE::kSrcMask;
+        int prev = sf == LogE::kSrcNone ? -1 : ((e.src & LogE::kSrcEps) ? base_cur + (int)sf : base_prev + (int)sf);
+        M.t_cost[idx] = dead ? __builtin_inff() : cost;
+        bp[base_cur + idx] = make_int2((int)e.arc, prev);
+        if (last_frame) g_tok_state[idx] = (int)ldv<kLds>(&M.hkey[e.h]);
+        if (!dead) {
+          live = true;
+          float r = cost - best;
+          if (!(r > p.beam)) {
+            surv = true;
+            if (hist_on) {
+              int bin = (int)floorf(r * inv);
+              bin = bin > 255 ? 255 : bin;
+              atomicAdd(&hist[bin], 1u);
+            }
           }
         }
+        stv<kLds>(&M.hkey[e.h], kEmptyKey);
       }
-      stv<kLds>(&M.hkey[e.h], kEmptyKey);
+      }
+      w_live += __popcll(__ballot(live));
+      w_surv += __popcll(__ballot(surv));
     }
-    if (my_surv) atomicAdd(&sh->n_surv, my_surv);
-    if (my_live) atomicAdd(&sh->n_live, my_live);
+    if (lane == 0) {
+      if (w_surv) atomicAdd(&sh->n_surv, w_surv);
+      if (w_live) atomicAdd(&sh->n_live, w_live);
+      if (n_active) atomicAdd(&sh->c_active, n_active);
+      if (n_emit) atomicAdd(&sh->c_emit, n_emit);
+      if (n_eps) atomicAdd(&sh->c_eps, n_eps);
+      if (n_cand) atomicAdd(&sh->c_cand, n_cand);
+    }
   }
   wg_barrier<kLds>();
 
@@ -663,9 +700,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     }
     if (lane == 0) {
       sh->cut_bin = cut;
-      sh->n_tok = sh->n_claim;
+      sh->n_tok = sh_n_claim(sh);
       sh->frame_base = sh->n_rec;
-      sh->n_rec += sh->n_claim;
+      sh->n_rec += sh_n_claim(sh);
       sh->best = ord2f(sh->best_ord);
       if (f >= 0) {  // the table made at reset is not a decoded frame
         sh->a_frames++;
@@ -674,7 +711,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         if (!kLds) sh->a_slow++;
       }
       sh->a_active += sh->c_active; sh->a_emit += sh->c_emit; sh->a_eps += sh->c_eps; sh->a_cand += sh->c_cand;
-      sh->a_impr += sh->log_n; sh->a_rounds += sh->rounds;
+      sh->a_impr += sh_log_n(sh); sh->a_rounds += sh->rounds;
     }
   }
   wg_barrier<kLds>();

@@ -299,6 +299,32 @@ def test_error_states(torch_cuda):
         dec.close()
 
 
+@pytest.mark.parametrize("table_location,block", [(1, "1024"), (2, "1024"), (1, "256")])
+def test_repeated_decodes_match_checker(torch_cuda, monkeypatch, table_location, block):
+    """The same utterance many times over, one frame per call: counters and the final table must
+    match the checker every time (lanes of different waves race for the same states; a lane can
+    create a state's entry and still lose the minimum to another wave)."""
+    torch = torch_cuda
+    monkeypatch.setenv("CBD_BLOCK", block)
+    w, g, L, ctxs, offs = tiny_inputs(torch)
+    Lh = L.cpu().numpy()
+    orc = GH.oracle_channels(g, 1, w.beam, w.max_active)[0]
+    orc.set_context(ctxs[0], offs[0]); orc.reset(); orc.advance(Lh[0])
+    want = orc.tokens()
+    dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location)
+    try:
+        dec.set_contexts(ctxs, offs)
+        for rep in range(60):
+            dec.reset()
+            for t in range(w.frames):
+                dec.advance(L, t, t + 1)
+            st = dec.stats(0)
+            assert st["tokens"] == orc.stat(1) and st["emit_arcs"] == orc.emit_arcs, f"repeat {rep}"
+            GH.assert_tables_equal(dec.tokens(0), want, f"repeat {rep}")
+    finally:
+        dec.close()
+
+
 def test_determinism_repeat(torch_cuda):
     """Two runs give identical tables (thread order must not matter)."""
     torch = torch_cuda
