@@ -10,8 +10,10 @@
 //            batch's candidates wait in registers until the batch minimum is
 //            known, then pass the cutoff and are recombined by a 64-bit atomic
 //            min on (orderable cost << 32 | arc) in an open-addressing table;
-//   closure  rounds over the change log: states whose value changed and that
-//            have epsilon-input arcs are expanded again until nothing changes;
+//   closure  states whose value changed and that have epsilon-input arcs are
+//            expanded again until nothing changes: every wave follows the chains
+//            it starts without barriers (the children of a pass stay in its
+//            registers); only oversized passes go back through the change log;
 //   compact  the change log names each state's winning update exactly once;
 //            the winner writes the token, its back-pointer record and the
 //            pruning histogram, and frees its table slot.
@@ -51,7 +53,10 @@ struct __attribute__((aligned(16))) ArcRec {
 };
 constexpr uint32_t kDegEscape = 255;
 
-// Change-log entry: slot h took a value through arc `arc` leaving token `src`.
+// Change-log entry: slot h took a value through arc `arc`.  `src` names where the arc
+// started: a token index of the previous frame (emitting arc), or, with kSrcEps, the
+// table slot of the source state in this frame (epsilon-input arc).  kSrcHasEps marks an
+// entry whose state has epsilon-input arcs that nobody has expanded for this value yet.
 // LDS form: 8 bytes; device-memory form: wide indices.
 template <bool kLds> struct LogT;
 template <> struct LogT<true> {
@@ -405,7 +410,9 @@ __device__ __forceinline__ int arc_owner(const ArcList &L, int jj, int j0) {
 template <bool kLds, bool kEmit>
 __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front, int no,
                                        bool act, float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed,
-                                       uint32_t &n_cand, int lane) {
+                                       uint32_t &n_cand, int lane, bool flag_children, bool &improved, uint32_t &h,
+                                       RowInfo &row) {
+  improved = false; h = 0; row.first = row.eps = row.end = 0;
   bool pass = false;
   const int fault = __hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   if (act) {
@@ -420,13 +427,11 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
     uint32_t wmin = wave_min_u32(co);
     if (lane == 0) atomicMin(&sh->best_ord, wmin);
   }
-  bool improved = false, claimed = false;
-  uint32_t h = 0;
+  bool claimed = false;
   uint32_t src = src_tag;
-  RowInfo row; row.first = row.eps = row.end = 0;
   if (pass && !fault) {
     row = row_of(p, rec);
-    if (row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;
+    if (flag_children && row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;
     uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
     improved = table_min<kLds>(M, sh, (uint32_t)rec.dst, key, h, claimed);
   }
@@ -459,7 +464,55 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
       if (lane == 0) atomicMin(&sh->m_ord, wmin);
     }
-    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane);
+    bool imp; uint32_t hh; RowInfo rr;
+    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane, true, imp, hh, rr);
+  }
+}
+
+// Epsilon closure from this wave's pending states: lane i holds a state whose value changed
+// (its epsilon row [first, first+deg), its cost, its table slot).  While a level has at most 64
+// arcs, each lane takes one arc and, if it lowered a state that has epsilon arcs of its own,
+// keeps that state for the next level: no barrier, no change-log round trip.  A bigger level is
+// expanded in bulk and its children are left flagged in the change log for the next round.
+template <bool kLds>
+__device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
+                                      const Ctx &cx, const float *Lrow, int no, uint8_t *owner_map, int first, int deg,
+                                      float cost, uint32_t slot, float m, uint32_t &n_eps, uint32_t &n_cand,
+                                      int &levels, int lane) {
+  typedef LogT<kLds> LogE;
+  while (true) {
+    ArcList AL = make_arc_list(first, deg, lane, owner_map);
+    if (AL.total == 0) return;
+    n_eps += (uint32_t)AL.total;
+    if (++levels > p.max_eps_iters) {
+      if (lane == 0) sh->diverged = 1;
+      return;
+    }
+    uint32_t tag = slot | LogE::kSrcEps;
+    if (AL.total > 64) {
+      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, tag, m, n_cand, lane);
+      return;
+    }
+    bool act = lane < AL.total;
+    int owner = arc_owner(AL, lane, 0);
+    int a = __shfl(AL.rel, owner, 64) + lane;
+    float c_own = __shfl(cost, owner, 64);
+    uint32_t s_own = (uint32_t)__shfl((int)tag, owner, 64);
+    float cand = 0.0f;
+    ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
+    if (act) {
+      rec = p.arcs[a];
+      float w = rec.weight;
+      if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
+      cand = c_own + w;
+    }
+    bool improved; uint32_t h; RowInfo row;
+    commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, s_own, m, n_cand, lane, false, improved, h, row);
+    bool go = improved && row.end > row.eps;
+    first = go ? row.eps : 0;
+    deg = go ? row.end - row.eps : 0;
+    cost = cand;
+    slot = h;
   }
 }
 
@@ -566,7 +619,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       for (int r = 0; r < kEmitSlots; ++r) {
         if (r * 64 < AL.total) {
           bool act = r * 64 + lane < AL.total;
-          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane);
+          bool imp; uint32_t hh; RowInfo rr;
+          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane,
+                             true, imp, hh, rr);
         }
       }
       if (AL.total > kEmitSlots * 64)
@@ -585,6 +640,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 
   // ---- step 4: epsilon closure; round r reads the entries logged in round r-1 and counts the
   // entries it logs for round r+1 in the other counter
+  int levels = 0;   // passes this wave has made (bounds the closure depth)
   for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
     const int fb = sh->fr_begin, fe = sh->fr_end;
     int32_t *front = &sh->n_front[(r + 1) & 1];
@@ -596,7 +652,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       if (j >= base + nb) j = fe;
       float cost = 0.0f;
       int first = 0, deg = 0;
-      uint32_t src_tag = 0;
+      uint32_t slot = 0;
       if (j < fe) {
         LogE e = M.log[j];
         if (e.src & LogE::kSrcHasEps) {
@@ -607,20 +663,17 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
             uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
             first = M.t_eps[no + idx];
             deg = M.t_end[no + idx] - first;
-            src_tag = idx | LogE::kSrcEps;
+            slot = e.h;
           }
         }
       }
-      ArcList AL = make_arc_list(first, deg, lane, owner_map);
-      if (AL.total == 0) continue;
-      n_eps += (uint32_t)AL.total;
-      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, src_tag, m, n_cand, lane);
+      chase<kLds>(p, M, sh, front, cx, Lrow, no, owner_map, first, deg, cost, slot, m, n_eps, n_cand, levels, lane);
     }
     wg_barrier<kLds>();
     if (tid == 0) {
-      sh->fr_begin = fe; sh->fr_end = sh_log_n(sh); sh->rounds++;
+      sh->fr_begin = fe; sh->fr_end = sh_log_n(sh);
       sh->n_front[r & 1] = 0;
-      if (*front > 0 && sh->rounds >= p.max_eps_iters) sh->diverged = 1;
+      if (*front > 0 && r + 1 >= p.max_eps_iters) sh->diverged = 1;
     }
     wg_barrier<kLds>();
     if (sh->diverged || sh->fault) break;
@@ -647,7 +700,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         float cost = ord2f((uint32_t)(curv >> 32));
         bool dead = cost - m > p.beam;
         uint32_t sf = e.src & LogE::kSrcMask;
-        int prev = sf == LogE::kSrcNone ? -1 : ((e.src & LogE::kSrcEps) ? base_cur + (int)sf : base_prev + (int)sf);
+        int prev = -1;
+        if (e.src & LogE::kSrcEps) prev = base_cur + (int)ldv<kLds>(&M.hidx[sf]);   // source state's token, via its slot
+        else if (sf != LogE::kSrcNone) prev = base_prev + (int)sf;
         M.t_cost[idx] = dead ? __builtin_inff() : cost;
         bp[base_cur + idx] = make_int2((int)e.arc, prev);
         if (last_frame) g_tok_state[idx] = (int)ldv<kLds>(&M.hkey[e.h]);
@@ -676,6 +731,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       if (n_emit) atomicAdd(&sh->c_emit, n_emit);
       if (n_eps) atomicAdd(&sh->c_eps, n_eps);
       if (n_cand) atomicAdd(&sh->c_cand, n_cand);
+      if (levels) atomicMax(&sh->rounds, levels);
     }
   }
   wg_barrier<kLds>();
