@@ -198,23 +198,39 @@ def cbd_best_path(d, channel, use_final=False, capacity=4096) -> Tuple[int, np.n
         return rc, words[:nw.value].copy(), arcs[:na.value].copy(), float(cost.value)
 
 
-def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True):
-    """-> (status[n], words list, arcs list or None, cost[n])."""
+class BestPathBuffers:
+    """Host arrays a caller can reuse across cbd_best_paths calls."""
+
+    def __init__(self, n: int, capacity: int, want_arcs: bool = True):
+        self.n, self.capacity = n, capacity
+        self.words = np.zeros((n, capacity), np.int32)
+        self.arcs = np.zeros((n, capacity), np.int32) if want_arcs else None
+        self.n_words = np.zeros(n, np.int32)
+        self.n_arcs = np.zeros(n, np.int32)
+        self.cost = np.zeros(n, np.float32)
+        self.status = np.zeros(n, np.int32)
+
+
+def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, buffers: Optional[BestPathBuffers] = None,
+                   as_lists=True):
+    """-> (status[n], words, arcs or None, cost[n], n_arcs[n], n_words[n]).
+
+    With as_lists the words / arcs come back as one array per channel; otherwise as the
+    [n, capacity] matrices of `buffers` (rows valid up to n_words / n_arcs)."""
     ch = _i32(channels)
     n = int(ch.size)
-    words = np.zeros((n, capacity), np.int32)
-    arcs = np.zeros((n, capacity), np.int32) if want_arcs else None
-    nw = np.zeros(n, np.int32)
-    na = np.zeros(n, np.int32)
-    cost = np.zeros(n, np.float32)
-    st = np.zeros(n, np.int32)
-    _check(lib().cbd_best_paths(d, _p(ch), n, int(bool(use_final)), _p(words), _p(arcs), int(capacity), _p(nw),
-                                _p(na), _p(cost), _p(st)), "cbd_best_paths")
-    wl = [words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    b = buffers if buffers is not None else BestPathBuffers(n, capacity, want_arcs)
+    assert b.n >= n and b.capacity == capacity
+    _check(lib().cbd_best_paths(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
+                                int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths")
+    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
+    if not as_lists:
+        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw
+    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
     al = None
     if want_arcs:
-        al = [arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    return st, wl, al, cost, na, nw
+        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    return st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()
 
 
 def cbd_get_tokens(d, channel):

@@ -121,6 +121,7 @@ struct cbd_decoder {
   uint64_t *d_hval = nullptr;
   uint32_t *d_hidx = nullptr;
   int32_t *d_out_arcs = nullptr, *d_out_words = nullptr, *d_out_meta = nullptr;
+  int32_t *h_out_arcs = nullptr, *h_out_words = nullptr, *h_out_meta = nullptr;  // pinned
   int32_t out_capacity = 0, out_rows = 0;
   StageRing ids;   // channel lists
   StageRing ctxs;  // context uploads
@@ -411,6 +412,9 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
                   d->d_log, d->d_ctx, d->d_hkey, d->d_hval, d->d_hidx, d->d_out_arcs, d->d_out_words, d->d_out_meta};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
+  if (d->h_out_arcs) (void)hipHostFree(d->h_out_arcs);
+  if (d->h_out_words) (void)hipHostFree(d->h_out_words);
+  if (d->h_out_meta) (void)hipHostFree(d->h_out_meta);
   d->ids.destroy();
   d->ctxs.destroy();
   delete d;
@@ -526,39 +530,63 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   int32_t rc = stage_channels(d, channels, n, &dev, &slot);
   if (rc != CBD_OK) return rc;
   if (d->out_capacity < capacity || d->out_rows < n) {
+    const int32_t rows = std::max(n, d->out_rows), cap = std::max(capacity, d->out_capacity);
     HIPCHK(hipStreamSynchronize(d->stream));
     if (d->d_out_arcs) (void)hipFree(d->d_out_arcs);
     if (d->d_out_words) (void)hipFree(d->d_out_words);
     if (d->d_out_meta) (void)hipFree(d->d_out_meta);
+    if (d->h_out_arcs) (void)hipHostFree(d->h_out_arcs);
+    if (d->h_out_words) (void)hipHostFree(d->h_out_words);
+    if (d->h_out_meta) (void)hipHostFree(d->h_out_meta);
     d->d_out_arcs = d->d_out_words = d->d_out_meta = nullptr;
-    int32_t rows = std::max(n, d->out_rows), cap = std::max(capacity, d->out_capacity);
+    d->h_out_arcs = d->h_out_words = d->h_out_meta = nullptr;
+    d->out_rows = d->out_capacity = 0;
     HIPCHK(dmalloc(&d->d_out_arcs, (size_t)rows * cap, nullptr));
     HIPCHK(dmalloc(&d->d_out_words, (size_t)rows * cap, nullptr));
     HIPCHK(dmalloc(&d->d_out_meta, (size_t)rows * 4, nullptr));
+    HIPCHK(hipHostMalloc((void **)&d->h_out_arcs, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
+    HIPCHK(hipHostMalloc((void **)&d->h_out_words, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
+    HIPCHK(hipHostMalloc((void **)&d->h_out_meta, sizeof(int32_t) * (size_t)rows * 4, hipHostMallocDefault));
     d->out_rows = rows; d->out_capacity = cap;
   }
   cbd::BestParams bp{};
   bp.chan = d->d_chan; bp.chan_ids = dev; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost; bp.bp = d->d_bp;
   bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
   bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
+  bp.row_pitch = d->out_capacity;
   bp.out_arcs = d->d_out_arcs; bp.out_words = d->d_out_words; bp.out_meta = d->d_out_meta;
   hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(d->ids.release(slot, d->stream));
-  std::vector<int32_t> meta((size_t)n * 4);
-  HIPCHK(hipMemcpyAsync(meta.data(), d->d_out_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, d->stream));
-  HIPCHK(hipMemcpyAsync(words, d->d_out_words, sizeof(int32_t) * (size_t)n * capacity, hipMemcpyDeviceToHost,
-                        d->stream));
-  if (arcs)
-    HIPCHK(hipMemcpyAsync(arcs, d->d_out_arcs, sizeof(int32_t) * (size_t)n * capacity, hipMemcpyDeviceToHost,
-                          d->stream));
+  // results come back through pinned staging: the small header first, then only as many
+  // columns of the word / arc rows as the longest path needs
+  int32_t *meta = d->h_out_meta;
+  HIPCHK(hipMemcpyAsync(meta, d->d_out_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, d->stream));
   HIPCHK(hipStreamSynchronize(d->stream));
+  int32_t max_na = 0, max_nw = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (meta[(size_t)i * 4] != CBD_OK) continue;
+    max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
+    max_nw = std::max(max_nw, meta[(size_t)i * 4 + 2]);
+  }
+  const size_t pitch = sizeof(int32_t) * (size_t)d->out_capacity;
+  if (max_nw > 0)
+    HIPCHK(hipMemcpy2DAsync(d->h_out_words, pitch, d->d_out_words, pitch, sizeof(int32_t) * (size_t)max_nw, (size_t)n,
+                            hipMemcpyDeviceToHost, d->stream));
+  if (arcs && max_na > 0)
+    HIPCHK(hipMemcpy2DAsync(d->h_out_arcs, pitch, d->d_out_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
+                            hipMemcpyDeviceToHost, d->stream));
+  if (max_nw > 0 || (arcs && max_na > 0)) HIPCHK(hipStreamSynchronize(d->stream));
   for (int32_t i = 0; i < n; ++i) {
     status[i] = meta[(size_t)i * 4 + 0];
     n_arcs[i] = meta[(size_t)i * 4 + 1];
     n_words[i] = meta[(size_t)i * 4 + 2];
     uint32_t bits = (uint32_t)meta[(size_t)i * 4 + 3];
     memcpy(&cost[i], &bits, 4);
+    if (status[i] != CBD_OK) continue;
+    memcpy(words + (size_t)i * capacity, d->h_out_words + (size_t)i * d->out_capacity, sizeof(int32_t) * (size_t)n_words[i]);
+    if (arcs)
+      memcpy(arcs + (size_t)i * capacity, d->h_out_arcs + (size_t)i * d->out_capacity, sizeof(int32_t) * (size_t)n_arcs[i]);
   }
   return CBD_OK;
 }

@@ -1003,8 +1003,9 @@ struct BestParams {
   const int32_t *int2pub;   // library arc order -> caller's numbering
   const float *final_cost;  // or null
   int32_t tok_cap, bp_cap, use_final, capacity;
-  int32_t *out_arcs;        // [n][capacity]
-  int32_t *out_words;       // [n][capacity]
+  int32_t row_pitch;        // entries between consecutive output rows (>= capacity)
+  int32_t *out_arcs;        // [n][row_pitch]
+  int32_t *out_words;       // [n][row_pitch]
   int32_t *out_meta;        // [n][4]: status, n_arcs, n_words, cost bits
 };
 
@@ -1016,8 +1017,8 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   const int c = p.chan_ids[i];
   const ChanState *cs = p.chan + c;
   int32_t *meta = p.out_meta + (size_t)i * 4;
-  int32_t *oarcs = p.out_arcs + (size_t)i * p.capacity;
-  int32_t *owords = p.out_words + (size_t)i * p.capacity;
+  int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
+  int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
   const int inf_bits = (int)__float_as_uint(__builtin_inff());
   if (cs->status != kStatusOk) {
     if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }

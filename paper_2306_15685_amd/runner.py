@@ -62,6 +62,7 @@ class Session:
             hip_stream=self.stream.cuda_stream)
         self.all = np.arange(w.channels, dtype=np.int32)
         self.capacity = 4 * w.frames + 64
+        self.buffers = B.BestPathBuffers(w.channels, self.capacity, want_arcs=True)
         self.advance_events: List = []
         self.time_kernels = False
         self.on_partial: Optional[Callable] = None  # called with (segment, frames_done, best_paths result)
@@ -109,10 +110,12 @@ class Session:
                 self._advance(L, t, n)
                 t += n
                 if w.partial_every_chunk and t < w.frames:
-                    r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
+                    r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
+                                         buffers=self.buffers, as_lists=keep_results)
                     if keep_results:
                         self.partials.append((s, t, r))
-            r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results)
+            r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results,
+                                 buffers=self.buffers, as_lists=keep_results)
             if keep_results:
                 finals.append(r)
             if collect_stats:

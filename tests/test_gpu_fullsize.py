@@ -1,0 +1,118 @@
+"""Full-size parity: the five benchmark workloads in the launch configuration bench.py times
+(runner.Session.step), checked against the CPU checker on sampled channels (every partial and
+final result, counters) and, on many more channels, by properties that need no checker:
+the returned arc path is connected from the start state, consumes exactly the decoded frames,
+re-accumulating its cost in fp32 in path order gives the returned cost bit for bit, and the
+words are the path's output labels."""
+import numpy as np
+import pytest
+
+from paper_2306_15685_amd import synth, runner
+from paper_2306_15685_amd import binding as B
+
+import gpu_harness as GH
+import helpers as H
+from oracle import OracleGraph, OracleChannel
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    torch.cuda.set_device(0)
+    return torch
+
+
+@pytest.fixture(scope="module")
+def big_graph():
+    """The 10M-state graph shared by the large, dynamic and stress workloads (same seed stream)."""
+    w = synth.WORKLOADS["large"]
+    g = synth.make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob, seed_stream=(w.config_id,),
+                         mean_degree=w.mean_degree, word_frac=w.word_frac)
+    return g, OracleGraph.from_graph(g)
+
+
+def check_workload(torch, w, g, og, sample, prop_channels, graph_handle=None):
+    inp = runner.make_inputs(w, g)
+    sess = runner.Session(inp, graph_handle=graph_handle)
+    try:
+        finals = sess.step(keep_results=True, collect_stats=False)
+        partials = sess.partials
+        n_seg = w.segments
+        assert len(finals) == n_seg
+        # --- sampled channels against the checker: every chunk's partial result, the final one, counters
+        for c in sample:
+            ch = OracleChannel(og, w.beam, w.max_active)
+            for s in range(n_seg):
+                lists, offs = inp.contexts[s]
+                ch.set_context(lists[c], offs[c])
+                ch.reset()
+                Lh = inp.loglikes[s][c].cpu().numpy()
+                t = 0
+                while t < w.frames:
+                    n = min(w.chunk, w.frames - t)
+                    ch.advance(Lh[t:t + n])
+                    t += n
+                    if w.partial_every_chunk and t < w.frames:
+                        st, wl, al, cost, na, nw = next(r for (ss, tt, r) in partials if ss == s and tt == t)
+                        GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(False),
+                                             f"{w.name} seg {s} ch {c} partial t={t}")
+                st, wl, al, cost, na, nw = finals[s]
+                GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(True),
+                                     f"{w.name} seg {s} ch {c} final")
+            stc = sess.stats(c)   # counters of the last segment
+            assert stc["emit_arcs"] == ch.emit_arcs and stc["tokens"] == ch.stat(1), f"{w.name} ch {c} counters"
+            assert stc["active_tokens"] == ch.stat(2) and stc["max_tokens"] == ch.stat(3)
+        # --- properties on many channels
+        for s in range(n_seg if n_seg <= 2 else 2):
+            lists, offs = inp.contexts[s]
+            st, wl, al, cost, na, nw = finals[s]
+            assert (st == 0).all(), f"{w.name}: channel in error state {st[st != 0][:4]}"
+            for c in prop_channels:
+                Lh = inp.loglikes[s][c].cpu().numpy()
+                ctx = set(lists[c].tolist())
+                c2, frames, words2, end = H.rescore_path(g, al[c], Lh, lambda t: ctx, lambda t: float(offs[c]))
+                assert frames == w.frames, f"{w.name} ch {c}: path consumes {frames} frames"
+                assert np.float32(cost[c]) == c2, f"{w.name} ch {c}: cost {cost[c]} vs re-scored {c2}"
+                assert wl[c].tolist() == words2, f"{w.name} ch {c}: words are not the path's labels"
+        total = sess.stats(-1)
+        return total
+    finally:
+        sess.close()
+
+
+def test_medium_all_channels(torch_cuda):
+    w = synth.WORKLOADS["medium"]
+    g = synth.graph_for(w)
+    og = OracleGraph.from_graph(g)
+    check_workload(torch_cuda, w, g, og, sample=range(w.channels), prop_channels=range(w.channels))
+
+
+@pytest.mark.timeout(900)
+def test_large_online(torch_cuda, big_graph):
+    g, og = big_graph
+    w = synth.WORKLOADS["large"]
+    rng = np.random.default_rng(1)
+    sample = [0, w.channels - 1] + rng.choice(w.channels, 6, replace=False).tolist()
+    total = check_workload(torch_cuda, w, g, og, sample=sample, prop_channels=range(0, w.channels, 4))
+    assert total["slow_frames"] < total["frames"] // 100   # LDS tables carry the workload, the fallback is rare
+
+
+@pytest.mark.timeout(900)
+def test_dynamic_context_switching(torch_cuda, big_graph):
+    """512 channels, 20 utterances each with a fresh context per channel (fewer channels are
+    sampled for the checker because each costs 20 utterances)."""
+    g, og = big_graph
+    w = synth.WORKLOADS["dynamic"]
+    check_workload(torch_cuda, w, g, og, sample=[0, 257, w.channels - 1], prop_channels=range(0, w.channels, 16))
+
+
+@pytest.mark.timeout(900)
+def test_throughput_stress(torch_cuda, big_graph):
+    g, og = big_graph
+    w = synth.WORKLOADS["stress"]
+    rng = np.random.default_rng(2)
+    sample = [0, w.channels - 1] + rng.choice(w.channels, 4, replace=False).tolist()
+    check_workload(torch_cuda, w, g, og, sample=sample, prop_channels=range(0, w.channels, 64))
