@@ -80,6 +80,8 @@ def main():
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-channels", type=int, default=32)
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device copy of BYTES, ten times (scale for the profiler's HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build decodes on one GPU only; channels are independent, so more GPUs would each "
@@ -91,6 +93,15 @@ def main():
     from paper_2306_15685_amd import binding as B
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = args.calibrate_copy // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n * 4, "copies": 10}))
+        return
     w = synth.WORKLOADS[args.workload]
     if args.channels:
         w = synth.scaled(w, channels=args.channels)
