@@ -518,12 +518,34 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
 
 constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimum settles
 
+// Per-frame scalars and the pruning histogram, set by one wave; a barrier must follow before use.
+// start: the frame is the start of an utterance (its cutoff reference is the start token's cost 0).
+__device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool start, int lane) {
+#pragma unroll
+  for (int k = 0; k < 4; ++k) hist[lane * 4 + k] = 0;
+  if (lane == 0) {
+    sh->m_ord = start ? f2ord(0.0f) : 0xFFFFFFFFu;
+    sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
+    sh->fault = 0; sh->diverged = 0;
+    sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
+  }
+}
+
 // One frame (f >= 0) or the start of an utterance (f < 0).  Uniform control flow; returns a kFrame* code.
 // Nothing that outlives the frame is written before the capacity checks have passed.
 template <bool kLds, int kBlock>
 __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
-                                         const float *Lrow, uint32_t *hist, uint8_t *owner_maps, int f, int cur,
-                                         int2 *bp, int32_t *g_tok_state, bool last_frame) {
+                                         float *Lrow, const float *Lnext, uint32_t *hist, uint8_t *owner_maps, int f,
+                                         int cur, int2 *bp, int32_t *g_tok_state, bool last_frame) {
+  // Lnext: the next frame's log-likelihood row in HBM (null: none).  It starts its way now, waits in
+  // registers during the frame and is parked in Lrow right before the frame's last barrier.
+  constexpr int kPre = kBlock >= 1024 ? 6 : 8;
+  float pre[kPre];
+#pragma unroll
+  for (int k = 0; k < kPre; ++k) {
+    int i = threadIdx.x + k * kBlock;
+    pre[k] = (Lnext && i < p.num_pdfs) ? Lnext[i] : 0.0f;
+  }
   constexpr int NW = kBlock / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int co = cur * M.tok_cap, no = (cur ^ 1) * M.tok_cap;   // token buffer read / built
@@ -531,15 +553,6 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   const float inv = 256.0f / p.beam;
   typedef LogT<kLds> LogE;
   uint8_t *owner_map = owner_maps + wave * kOwnerMap;
-
-  if (tid == 0) {
-    sh->m_ord = f < 0 ? f2ord(0.0f) : 0xFFFFFFFFu;
-    sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
-    sh->fault = 0; sh->diverged = 0;
-    sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
-  }
-  for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
-  wg_barrier<kLds>();
 
   uint32_t n_active = 0, n_emit = 0, n_eps = 0, n_cand = 0;   // this wave's share of the frame's counters
   if (f < 0) {
@@ -769,6 +782,15 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       sh->a_active += sh->c_active; sh->a_emit += sh->c_emit; sh->a_eps += sh->c_eps; sh->a_cand += sh->c_cand;
       sh->a_impr += sh_log_n(sh); sh->a_rounds += sh->rounds;
     }
+    frame_init(sh, hist, false, lane);   // for the next frame
+  }
+  if (Lnext) {
+#pragma unroll
+    for (int k = 0; k < kPre; ++k) {
+      int i = tid + k * kBlock;
+      if (i < p.num_pdfs) Lrow[i] = pre[k];
+    }
+    for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lrow[i] = Lnext[i];
   }
   wg_barrier<kLds>();
   return kFrameOk;
@@ -777,7 +799,6 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 template <int kBlock>
 __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int kPre = kBlock >= 1024 ? 6 : 8;  // log-likelihood values a thread holds while the next row is in flight
   const int tid = threadIdx.x;
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
@@ -859,20 +880,14 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   __syncthreads();
 
   int outcome = kFrameOk;
+  if (tid < 64) frame_init(sh, hist, p.do_reset != 0, tid);
+  __syncthreads();
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
-    // next frame's row starts its way from HBM now and waits in registers
-    float pre[kPre];
-    const bool have_next = f + 1 < p.n_frames && f >= 0;
-    const float *Lnext = Lbase + (long long)(f + 1) * p.num_pdfs;
-#pragma unroll
-    for (int k = 0; k < kPre; ++k) {
-      int i = tid + k * kBlock;
-      pre[k] = (have_next && i < p.num_pdfs) ? Lnext[i] : 0.0f;
-    }
+    const float *Lnext = (f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
     const bool last = f == p.n_frames - 1;
     bool slow = !fast;
     if (fast) {
-      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, hist, owner_maps, f, cur, bp, g_tok_state, last);
+      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
       if (outcome == kFrameOverflow) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the tokens over
         const int lo = cur * p.lds_tok_cap;
@@ -882,31 +897,24 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
           MG.t_eps[i] = ML.t_eps[lo + i]; MG.t_end[i] = ML.t_end[lo + i];
         }
         __syncthreads();
+        if (tid < 64) frame_init(sh, hist, f < 0, tid);
+        __syncthreads();
         fast = false; cur = 0; slow = true;
       }
     }
-    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, hist, owner_maps, f, cur, bp, g_tok_state, last);
+    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
     if (outcome != kFrameOk) break;
     cur ^= 1;
     if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {
-      // the token list fits LDS again
+      // the token list fits LDS again (the next frame's first barrier orders these LDS writes)
       const int go = cur * p.g_tok_cap;
       for (int i = tid; i < sh->n_tok; i += kBlock) {
         ML.t_cost[i] = MG.t_cost[i]; ML.t_first[i] = MG.t_first[go + i];
         ML.t_eps[i] = MG.t_eps[go + i]; ML.t_end[i] = MG.t_end[go + i];
       }
       fast = true; cur = 0;
+      __syncthreads();
     }
-    // park the prefetched row in LDS for the next frame
-    if (have_next) {
-#pragma unroll
-      for (int k = 0; k < kPre; ++k) {
-        int i = tid + k * kBlock;
-        if (i < p.num_pdfs) Lrow[i] = pre[k];
-      }
-      for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lrow[i] = Lnext[i];
-    }
-    __syncthreads();
   }
 
   // ---- leave: a frame that produced nothing, overflowed or diverged parks the channel
