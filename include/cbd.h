@@ -100,6 +100,7 @@ typedef struct cbd_config {
   int32_t table_location;     /* 0 or 1 = LDS tables, frames that outgrow them are redone in device memory;
                                  2 = device-memory tables only */
   int32_t lds_token_cap;      /* tokens per frame the LDS tables hold; 0 = as many as fit beside the row */
+  int32_t max_pool_contexts;  /* pre-loaded contexts the decoder can hold besides one per channel (Sec. 4.3) */
 } cbd_config;
 
 /*
@@ -134,6 +135,20 @@ int32_t cbd_set_context(cbd_decoder *d, int32_t channel, const int32_t *arc_idx,
  */
 int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const int32_t *arc_idx,
                          const int32_t *list_offsets, const float *offsets);
+
+/*
+ * Pre-loaded contexts (Sec. 4.3: contexts anticipated in advance are loaded before decoding and the
+ * decoder switches among them).  cbd_contexts_create uploads n_contexts lists (same layout and rules as
+ * cbd_set_contexts) into the decoder's pool and returns their ids in context_ids (HOST [n_contexts]);
+ * CBD_E_CAPACITY if the pool (max_pool_contexts) has too few free entries.  cbd_use_contexts switches
+ * channels[i] to context_ids[i] (-1 = back to the channel's own list from cbd_set_context) without any
+ * upload; many channels may share one context.  It takes effect like cbd_set_context.  A destroyed id may
+ * be reused by a later create; channels still bound to it keep decoding with whatever the slot holds.
+ */
+int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *arc_idx, const int32_t *list_offsets,
+                            const float *offsets, int32_t *context_ids);
+int32_t cbd_context_destroy(cbd_decoder *d, int32_t context_id);
+int32_t cbd_use_contexts(cbd_decoder *d, const int32_t *channels, const int32_t *context_ids, int32_t n);
 
 /*
  * Decodes n_frames frames on the listed channels (Sec. 2.2, Sec. 3.2: a chunk

@@ -21,7 +21,7 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
-    "cbd_set_context", "cbd_set_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_get_tokens",
+    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_get_tokens",
     "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
 
@@ -37,7 +37,8 @@ class cbd_config(C.Structure):
     _fields_ = [("num_channels", C.c_int32), ("beam", C.c_float), ("max_active", C.c_int32),
                 ("max_frames", C.c_int32), ("max_context_arcs", C.c_int32), ("lookup_mode", C.c_int32),
                 ("hash_capacity_log2", C.c_int32), ("max_eps_iters", C.c_int32),
-                ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32)]
+                ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32),
+                ("max_pool_contexts", C.c_int32)]
 
 
 class cbd_stats(C.Structure):
@@ -77,6 +78,12 @@ def lib():
     L.cbd_set_context.argtypes = [vp, i32, vp, i32, f32]
     L.cbd_set_contexts.restype = i32
     L.cbd_set_contexts.argtypes = [vp, vp, i32, vp, vp, vp]
+    L.cbd_contexts_create.restype = i32
+    L.cbd_contexts_create.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.cbd_context_destroy.restype = i32
+    L.cbd_context_destroy.argtypes = [vp, i32]
+    L.cbd_use_contexts.restype = i32
+    L.cbd_use_contexts.argtypes = [vp, vp, vp, i32]
     L.cbd_advance.restype = i32
     L.cbd_advance.argtypes = [vp, vp, i32, vp, i64, i32]
     L.cbd_best_path.restype = i32
@@ -142,10 +149,10 @@ def cbd_graph_free(g):
 
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,
                        hash_capacity_log2=14, max_eps_iters=0, records_per_frame=0, table_location=0,
-                       lds_token_cap=0, hip_stream=0):
+                       lds_token_cap=0, max_pool_contexts=0, hip_stream=0):
     cfg = cbd_config(int(num_channels), float(beam), int(max_active), int(max_frames), int(max_context_arcs),
                      int(lookup_mode), int(hash_capacity_log2), int(max_eps_iters), int(records_per_frame),
-                     int(table_location), int(lds_token_cap))
+                     int(table_location), int(lds_token_cap), int(max_pool_contexts))
     h = C.c_void_p()
     _check(lib().cbd_decoder_create(g, C.byref(cfg), C.c_void_p(int(hip_stream)), C.byref(h)), "cbd_decoder_create")
     return h
@@ -165,14 +172,41 @@ def cbd_set_context(d, channel, arc_idx, offset):
     _check(lib().cbd_set_context(d, int(channel), _p(a), int(a.size), float(offset)), "cbd_set_context")
 
 
-def cbd_set_contexts(d, channels, lists: Sequence[np.ndarray], offsets):
-    ch = _i32(channels)
-    lo = np.zeros(ch.size + 1, dtype=np.int32)
+def pack_lists(lists: Sequence[np.ndarray]):
+    """Concatenates arc-index lists -> (arc_idx int32, list_offsets int32 [n+1])."""
+    lo = np.zeros(len(lists) + 1, dtype=np.int32)
     if len(lists):
         np.cumsum([len(x) for x in lists], out=lo[1:])
     cat = _i32(np.concatenate([_i32(x) for x in lists])) if len(lists) and lo[-1] > 0 else np.zeros(1, np.int32)
+    return cat, lo
+
+
+def cbd_set_contexts(d, channels, lists, offsets, packed=None):
+    """lists: one arc-index array per channel, or pass packed=(arc_idx, list_offsets) from pack_lists."""
+    ch = _i32(channels)
+    cat, lo = packed if packed is not None else pack_lists(lists)
     off = np.ascontiguousarray(offsets, dtype=np.float32)
     _check(lib().cbd_set_contexts(d, _p(ch), int(ch.size), _p(cat), _p(lo), _p(off)), "cbd_set_contexts")
+
+
+def cbd_contexts_create(d, lists, offsets, packed=None) -> np.ndarray:
+    """Uploads the lists into the decoder's context pool -> context ids."""
+    cat, lo = packed if packed is not None else pack_lists(lists)
+    off = np.ascontiguousarray(offsets, dtype=np.float32)
+    ids = np.zeros(off.size, dtype=np.int32)
+    _check(lib().cbd_contexts_create(d, int(off.size), _p(cat), _p(lo), _p(off), _p(ids)), "cbd_contexts_create")
+    return ids
+
+
+def cbd_context_destroy(d, context_id):
+    _check(lib().cbd_context_destroy(d, int(context_id)), "cbd_context_destroy")
+
+
+def cbd_use_contexts(d, channels, context_ids):
+    ch = _i32(channels)
+    ids = _i32(context_ids)
+    assert ch.size == ids.size
+    _check(lib().cbd_use_contexts(d, _p(ch), _p(ids), int(ch.size)), "cbd_use_contexts")
 
 
 def cbd_advance(d, channels, loglikes_ptr: int, channel_stride: int, n_frames: int):

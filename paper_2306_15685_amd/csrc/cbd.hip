@@ -116,7 +116,11 @@ struct cbd_decoder {
   int32_t *d_tok_first = nullptr, *d_tok_eps = nullptr, *d_tok_end = nullptr;
   int2 *d_bp = nullptr;
   cbd::LogT<false> *d_log = nullptr;
-  int32_t *d_ctx = nullptr;
+  int32_t *d_ctx = nullptr;      // [C + pool][max_ctx]
+  int32_t *d_ctx_n = nullptr;    // [C + pool]
+  float *d_ctx_off = nullptr;
+  int32_t pool = 0;              // pre-loaded contexts the store has room for
+  std::vector<uint8_t> pool_used;
   uint32_t *d_hkey = nullptr;
   uint64_t *d_hval = nullptr;
   uint32_t *d_hidx = nullptr;
@@ -166,7 +170,7 @@ AdvanceParams base_params(const cbd_decoder *d) {
   p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap;
   p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost;
   p.tok_first = d->d_tok_first; p.tok_eps = d->d_tok_eps; p.tok_end = d->d_tok_end;
-  p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx;
+  p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx; p.ctx_n = d->d_ctx_n; p.ctx_off = d->d_ctx_off;
   p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_hidx = d->d_hidx;
   return p;
 }
@@ -308,6 +312,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     return fail(CBD_E_INVALID, "decoder: hash_capacity_log2 must be in [6, 24]");
   if (cfg->table_location < 0 || cfg->table_location > 2) return fail(CBD_E_INVALID, "decoder: table_location");
   if (cfg->lds_token_cap < 0) return fail(CBD_E_INVALID, "decoder: lds_token_cap");
+  if (cfg->max_pool_contexts < 0) return fail(CBD_E_INVALID, "decoder: max_pool_contexts");
   cbd_decoder *d = new (std::nothrow) cbd_decoder();
   if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
   d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
@@ -383,7 +388,13 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   DCHK(dmalloc(&d->d_tok_end, C * 2 * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_bp, C * (size_t)d->bp_cap, &d->bytes));
   DCHK(dmalloc(&d->d_log, C * (size_t)d->g_log_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_ctx, C * (size_t)d->max_ctx, &d->bytes));
+  d->pool = cfg->max_pool_contexts;
+  d->pool_used.assign((size_t)d->pool, 0);
+  DCHK(dmalloc(&d->d_ctx, (C + d->pool) * (size_t)d->max_ctx, &d->bytes));
+  DCHK(dmalloc(&d->d_ctx_n, C + d->pool, &d->bytes));
+  DCHK(dmalloc(&d->d_ctx_off, C + d->pool, &d->bytes));
+  DCHK(hipMemsetAsync(d->d_ctx_n, 0, sizeof(int32_t) * (C + d->pool), d->stream));
+  DCHK(hipMemsetAsync(d->d_ctx_off, 0, sizeof(float) * (C + d->pool), d->stream));
   DCHK(dmalloc(&d->d_hkey, C * (size_t)d->g_slots, &d->bytes));
   DCHK(dmalloc(&d->d_hval, C * (size_t)d->g_slots, &d->bytes));
   DCHK(dmalloc(&d->d_hidx, C * (size_t)d->g_slots, &d->bytes));
@@ -398,7 +409,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   DCHK(hipGetLastError());
   DCHK(d->ids.init(sizeof(int32_t) * C));
   // context staging: [channels n][list offsets n+1][offsets n][lists ...]
-  DCHK(d->ctxs.init(sizeof(int32_t) * (C * 3 + 1 + C * (size_t)d->max_ctx)));
+  DCHK(d->ctxs.init(sizeof(int32_t) * (C * 4 + 1 + C * (size_t)d->max_ctx)));
   DCHK(hipStreamSynchronize(d->stream));
 #undef DCHK
   *out = d;
@@ -409,7 +420,7 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_first, d->d_tok_eps, d->d_tok_end, d->d_bp,
-                  d->d_log, d->d_ctx, d->d_hkey, d->d_hval, d->d_hidx, d->d_out_arcs, d->d_out_words, d->d_out_meta};
+                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_out_arcs, d->d_out_words, d->d_out_meta};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->h_out_arcs) (void)hipHostFree(d->h_out_arcs);
@@ -444,52 +455,147 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
   return CBD_OK;
 }
 
+namespace {
+
+// Checks n lists (list i = arc_idx[list_offsets[i] .. list_offsets[i+1])) and turns them into sorted,
+// de-duplicated lists in the library's arc order.  Nothing is enqueued here.
+int32_t prepare_lists(const cbd_decoder *d, int32_t n, const int32_t *arc_idx, const int32_t *list_offsets,
+                      const float *offsets, std::vector<int32_t> &packed, std::vector<int32_t> &new_off,
+                      const char *who) {
+  const std::string w(who);
+  if (list_offsets[0] != 0) return fail(CBD_E_INVALID, w + ": list_offsets[0] != 0");
+  for (int32_t i = 0; i < n; ++i) {
+    if (list_offsets[i + 1] < list_offsets[i]) return fail(CBD_E_INVALID, w + ": list_offsets not monotone");
+    if (!std::isfinite(offsets[i])) return fail(CBD_E_INVALID, w + ": non-finite offset");
+  }
+  const int32_t total = list_offsets[n];
+  if (total > 0 && !arc_idx) return fail(CBD_E_INVALID, w + ": null list");
+  for (int32_t k = 0; k < total; ++k)
+    if (arc_idx[k] < 0 || arc_idx[k] >= d->g->A) return fail(CBD_E_INVALID, w + ": arc index out of range");
+  // the list is a set: sort + de-duplicate, in place in the packed array
+  packed.resize((size_t)total);
+  new_off.assign((size_t)n + 1, 0);
+  const int32_t *p2i = d->g->pub2int.data();
+  int32_t out = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t b = out;
+    for (int32_t k = list_offsets[i]; k < list_offsets[i + 1]; ++k) packed[(size_t)out++] = p2i[arc_idx[k]];
+    std::sort(packed.begin() + b, packed.begin() + out);
+    out = (int32_t)(std::unique(packed.begin() + b, packed.begin() + out) - packed.begin());
+    if (out - b > d->cfg.max_context_arcs) return fail(CBD_E_INVALID, w + ": more than max_context_arcs distinct arcs");
+    new_off[(size_t)i + 1] = out;
+  }
+  packed.resize((size_t)out);
+  return CBD_OK;
+}
+
+// Uploads prepared lists into the given store slots (at most C per staging buffer, so in pieces);
+// bind != null also switches channel bind[i] to slots[i].
+int32_t upload_lists(cbd_decoder *d, int32_t n, const int32_t *slots, const int32_t *bind, const float *offsets,
+                     const std::vector<int32_t> &packed, const std::vector<int32_t> &off) {
+  for (int32_t i0 = 0; i0 < n; i0 += d->C) {
+    const int32_t m = std::min(d->C, n - i0);
+    int slot = 0;
+    HIPCHK(d->ctxs.acquire(&slot));
+    int32_t *h = (int32_t *)d->ctxs.host[slot];
+    const size_t mm = (size_t)m;
+    const int32_t base = off[(size_t)i0], cnt = off[(size_t)i0 + mm] - base;
+    memcpy(h, slots + i0, sizeof(int32_t) * mm);
+    if (bind) memcpy(h + mm, bind + i0, sizeof(int32_t) * mm);
+    for (size_t k = 0; k <= mm; ++k) h[2 * mm + k] = off[(size_t)i0 + k] - base;
+    memcpy(h + 3 * mm + 1, offsets + i0, sizeof(float) * mm);
+    if (cnt > 0) memcpy(h + 4 * mm + 1, packed.data() + base, sizeof(int32_t) * (size_t)cnt);
+    HIPCHK(d->ctxs.upload(slot, sizeof(int32_t) * (4 * mm + 1 + (size_t)cnt), d->stream));
+    const int32_t *dv = (const int32_t *)d->ctxs.dev[slot];
+    hipLaunchKernelGGL(cbd::scatter_contexts_kernel, dim3((unsigned)m), dim3(256), 0, d->stream, dv,
+                       bind ? dv + mm : (const int32_t *)nullptr, dv + 2 * mm, (const float *)(dv + 3 * mm + 1),
+                       dv + 4 * mm + 1, d->d_ctx, d->max_ctx, d->d_ctx_n, d->d_ctx_off, d->d_chan);
+    HIPCHK(hipGetLastError());
+    HIPCHK(d->ctxs.release(slot, d->stream));
+  }
+  return CBD_OK;
+}
+
+int32_t check_channel_list(cbd_decoder *d, const int32_t *channels, int32_t n, const char *who) {
+  const std::string w(who);
+  if (!channels || n <= 0 || n > d->C) return fail(CBD_E_INVALID, w + ": bad channel count");
+  d->h_tmp.assign((size_t)d->C, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t c = channels[i];
+    if (c < 0 || c >= d->C) return fail(CBD_E_INVALID, w + ": channel out of range");
+    if (d->h_tmp[c]) return fail(CBD_E_INVALID, w + ": duplicate channel");
+    d->h_tmp[c] = 1;
+  }
+  return CBD_OK;
+}
+
+}  // namespace
+
 int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const int32_t *arc_idx,
                          const int32_t *list_offsets, const float *offsets) {
   if (!d || !channels || !list_offsets || !offsets) return fail(CBD_E_INVALID, "set_contexts: null argument");
-  if (n_channels <= 0 || n_channels > d->C) return fail(CBD_E_INVALID, "set_contexts: bad channel count");
-  if (list_offsets[0] != 0) return fail(CBD_E_INVALID, "set_contexts: list_offsets[0] != 0");
   // validate everything before anything changes
-  d->h_tmp.assign((size_t)d->C, 0);
-  for (int32_t i = 0; i < n_channels; ++i) {
-    int32_t c = channels[i];
-    if (c < 0 || c >= d->C) return fail(CBD_E_INVALID, "set_contexts: channel out of range");
-    if (d->h_tmp[c]) return fail(CBD_E_INVALID, "set_contexts: duplicate channel");
-    d->h_tmp[c] = 1;
-    if (list_offsets[i + 1] < list_offsets[i]) return fail(CBD_E_INVALID, "set_contexts: list_offsets not monotone");
-    if (!std::isfinite(offsets[i])) return fail(CBD_E_INVALID, "set_contexts: non-finite offset");
+  int32_t rc = check_channel_list(d, channels, n_channels, "set_contexts");
+  if (rc != CBD_OK) return rc;
+  std::vector<int32_t> packed, off;
+  rc = prepare_lists(d, n_channels, arc_idx, list_offsets, offsets, packed, off, "set_contexts");
+  if (rc != CBD_OK) return rc;
+  // a channel's own context lives in store slot `channel`
+  return upload_lists(d, n_channels, channels, channels, offsets, packed, off);
+}
+
+int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *arc_idx, const int32_t *list_offsets,
+                            const float *offsets, int32_t *context_ids) {
+  if (!d || !list_offsets || !offsets || !context_ids) return fail(CBD_E_INVALID, "contexts_create: null argument");
+  if (n_contexts <= 0) return fail(CBD_E_INVALID, "contexts_create: bad count");
+  int32_t free_ids = 0;
+  for (uint8_t u : d->pool_used) free_ids += !u;
+  if (n_contexts > free_ids) return fail(CBD_E_CAPACITY, "contexts_create: context pool full");
+  std::vector<int32_t> packed, off;
+  int32_t rc = prepare_lists(d, n_contexts, arc_idx, list_offsets, offsets, packed, off, "contexts_create");
+  if (rc != CBD_OK) return rc;
+  std::vector<int32_t> slots((size_t)n_contexts);
+  int32_t next = 0;
+  for (int32_t i = 0; i < n_contexts; ++i) {
+    while (d->pool_used[(size_t)next]) ++next;
+    d->pool_used[(size_t)next] = 1;
+    context_ids[i] = next;
+    slots[(size_t)i] = d->C + next;
   }
-  const int32_t total = list_offsets[n_channels];
-  if (total > 0 && !arc_idx) return fail(CBD_E_INVALID, "set_contexts: null list");
-  for (int32_t k = 0; k < total; ++k)
-    if (arc_idx[k] < 0 || arc_idx[k] >= d->g->A) return fail(CBD_E_INVALID, "set_contexts: arc index out of range");
-  // sort + de-duplicate in the library's arc order (the list is a set)
-  std::vector<int32_t> packed;
-  packed.reserve((size_t)total);
-  std::vector<int32_t> new_off((size_t)n_channels + 1, 0);
-  std::vector<int32_t> one;
-  for (int32_t i = 0; i < n_channels; ++i) {
-    one.clear();
-    for (int32_t k = list_offsets[i]; k < list_offsets[i + 1]; ++k) one.push_back(d->g->pub2int[arc_idx[k]]);
-    std::sort(one.begin(), one.end());
-    one.erase(std::unique(one.begin(), one.end()), one.end());
-    if ((int32_t)one.size() > d->cfg.max_context_arcs)
-      return fail(CBD_E_INVALID, "set_contexts: more than max_context_arcs distinct arcs");
-    packed.insert(packed.end(), one.begin(), one.end());
-    new_off[i + 1] = (int32_t)packed.size();
+  rc = upload_lists(d, n_contexts, slots.data(), nullptr, offsets, packed, off);
+  if (rc != CBD_OK)
+    for (int32_t i = 0; i < n_contexts; ++i) d->pool_used[(size_t)context_ids[i]] = 0;
+  return rc;
+}
+
+int32_t cbd_context_destroy(cbd_decoder *d, int32_t context_id) {
+  if (!d) return fail(CBD_E_INVALID, "context_destroy: null decoder");
+  if (context_id < 0 || context_id >= d->pool || !d->pool_used[(size_t)context_id])
+    return fail(CBD_E_INVALID, "context_destroy: no such context");
+  d->pool_used[(size_t)context_id] = 0;
+  return CBD_OK;
+}
+
+int32_t cbd_use_contexts(cbd_decoder *d, const int32_t *channels, const int32_t *context_ids, int32_t n) {
+  if (!d || !context_ids) return fail(CBD_E_INVALID, "use_contexts: null argument");
+  int32_t rc = check_channel_list(d, channels, n, "use_contexts");
+  if (rc != CBD_OK) return rc;
+  for (int32_t i = 0; i < n; ++i) {
+    int32_t id = context_ids[i];
+    if (id != -1 && (id < 0 || id >= d->pool || !d->pool_used[(size_t)id]))
+      return fail(CBD_E_INVALID, "use_contexts: no such context");
   }
   int slot = 0;
   HIPCHK(d->ctxs.acquire(&slot));
   int32_t *h = (int32_t *)d->ctxs.host[slot];
-  const size_t n = (size_t)n_channels;
-  memcpy(h, channels, sizeof(int32_t) * n);
-  memcpy(h + n, new_off.data(), sizeof(int32_t) * (n + 1));
-  memcpy(h + 2 * n + 1, offsets, sizeof(float) * n);
-  if (!packed.empty()) memcpy(h + 3 * n + 1, packed.data(), sizeof(int32_t) * packed.size());
-  HIPCHK(d->ctxs.upload(slot, sizeof(int32_t) * (3 * n + 1 + packed.size()), d->stream));
+  for (int32_t i = 0; i < n; ++i) {
+    h[i] = channels[i];
+    h[(size_t)n + i] = context_ids[i] < 0 ? channels[i] : d->C + context_ids[i];   // -1: the channel's own list
+  }
+  HIPCHK(d->ctxs.upload(slot, sizeof(int32_t) * 2 * (size_t)n, d->stream));
   const int32_t *dv = (const int32_t *)d->ctxs.dev[slot];
-  hipLaunchKernelGGL(cbd::scatter_contexts_kernel, dim3((unsigned)n_channels), dim3(256), 0, d->stream, dv, dv + n,
-                     (const float *)(dv + 2 * n + 1), dv + 3 * n + 1, d->d_ctx, d->max_ctx, d->d_chan);
+  hipLaunchKernelGGL(cbd::bind_contexts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, d->stream, dv, dv + n,
+                     n, d->d_chan);
   HIPCHK(hipGetLastError());
   HIPCHK(d->ctxs.release(slot, d->stream));
   return CBD_OK;

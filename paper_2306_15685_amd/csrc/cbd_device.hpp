@@ -81,8 +81,8 @@ struct __attribute__((aligned(128))) ChanState {
   int32_t status;       // sticky
   float best;           // minimum cost of the current table
   int32_t cut_bin;      // histogram cut for the next prune; 255 = none
-  int32_t ctx_n;
-  float ctx_offset;
+  int32_t ctx_slot;     // which stored context the channel decodes with
+  int32_t pad0;
   long long frames, active_tokens, emit_arcs, eps_arcs, candidates, improvements, tokens, eps_rounds;
   int32_t max_tokens;
   int32_t slow_frames;  // frames decoded with the device-memory tables
@@ -121,7 +121,9 @@ struct AdvanceParams {
   int32_t *tok_end;
   int2 *bp;                // [C][bp_cap] (arc, predecessor record or -1)
   LogT<false> *g_log;      // [C][g_log_cap]
-  const int32_t *ctx;      // [C][max_ctx] sorted, library arc order
+  const int32_t *ctx;      // [C + pool][max_ctx] stored contexts: sorted, library arc order
+  const int32_t *ctx_n;    // [C + pool] entries of each stored context
+  const float *ctx_off;    // [C + pool] its offset
   uint32_t *g_hkey;        // [C][g_slots]
   uint64_t *g_hval;
   uint32_t *g_hidx;
@@ -851,8 +853,9 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
 
   // context of this call (Sec. 4.3: whichever list is current is the one used)
   Ctx cx;
-  cx.n = cs->ctx_n; cx.offset = cs->ctx_offset;
-  cx.g_list = p.ctx + (size_t)c * p.max_ctx;
+  const int cslot = cs->ctx_slot;
+  cx.n = p.ctx_n[cslot]; cx.offset = p.ctx_off[cslot];
+  cx.g_list = p.ctx + (size_t)cslot * p.max_ctx;
   cx.lds_list = ctx_lds; cx.bitmap = bitmap;
   cx.in_lds = cx.n <= p.ctx_lds_cap;
   cx.use_bitmap = p.lookup_mode == 1;
@@ -972,14 +975,25 @@ __global__ __launch_bounds__(64) void selftest_kernel(const int32_t *in, int32_t
 
 // ---- contexts ---------------------------------------------------------------
 
-// One workgroup per listed channel copies its sorted list into the channel's row.
-__global__ void scatter_contexts_kernel(const int32_t *chan_ids, const int32_t *list_off, const float *offsets,
-                                        const int32_t *lists, int32_t *ctx, int max_ctx, ChanState *chan) {
+// One workgroup per uploaded list copies it into its slot of the context store; with `bind`,
+// channel bind[i] is switched to that slot as well.
+__global__ void scatter_contexts_kernel(const int32_t *slots, const int32_t *bind, const int32_t *list_off,
+                                        const float *offsets, const int32_t *lists, int32_t *ctx, int max_ctx,
+                                        int32_t *ctx_n, float *ctx_off, ChanState *chan) {
   int i = blockIdx.x;
-  int c = chan_ids[i];
+  int slot = slots[i];
   int b = list_off[i], n = list_off[i + 1] - b;
-  for (int k = threadIdx.x; k < n; k += blockDim.x) ctx[(size_t)c * max_ctx + k] = lists[b + k];
-  if (threadIdx.x == 0) { chan[c].ctx_n = n; chan[c].ctx_offset = offsets[i]; }
+  for (int k = threadIdx.x; k < n; k += blockDim.x) ctx[(size_t)slot * max_ctx + k] = lists[b + k];
+  if (threadIdx.x == 0) {
+    ctx_n[slot] = n; ctx_off[slot] = offsets[i];
+    if (bind) chan[bind[i]].ctx_slot = slot;
+  }
+}
+
+// Sec. 4.3: switching a channel to a context that is already on the device is one store.
+__global__ void bind_contexts_kernel(const int32_t *chan_ids, const int32_t *slots, int n, ChanState *chan) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) chan[chan_ids[i]].ctx_slot = slots[i];
 }
 
 __global__ void init_tables_kernel(uint32_t *hkey, uint64_t *hval, size_t n) {
@@ -995,6 +1009,7 @@ __global__ void init_chan_kernel(ChanState *chan, int n) {
     for (size_t k = 0; k < sizeof(ChanState); ++k) b[k] = 0;
     z.status = kStatusNoTokens;  // until reset
     z.cut_bin = 255;
+    z.ctx_slot = i;              // the channel's own (empty) context
     chan[i] = z;
   }
 }

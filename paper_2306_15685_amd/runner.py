@@ -44,7 +44,10 @@ class Session:
     """A decoder sized for a workload, bound to torch's current stream."""
 
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
-                 records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0):
+                 records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
+                 context_mode: str = "upload"):
+        """context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
+        segments' lists once with cbd_contexts_create and switches by id (Sec. 4.3)."""
         import torch
         self.torch = torch
         self.inp = inp
@@ -59,7 +62,15 @@ class Session:
             self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
             records_per_frame or DEFAULT_RECORDS_PER_FRAME, table_location, lds_token_cap,
+            w.channels * w.segments if context_mode == "pool" else 0,
             hip_stream=self.stream.cuda_stream)
+        self.context_mode = context_mode
+        # contexts packed once: per segment (arc_idx, list_offsets)
+        self.packed = [B.pack_lists(lists) for lists, _ in inp.contexts]
+        self.pool_ids = None
+        if context_mode == "pool":
+            self.pool_ids = [B.cbd_contexts_create(self.dh, None, offs, packed=self.packed[s])
+                             for s, (_, offs) in enumerate(inp.contexts)]
         self.all = np.arange(w.channels, dtype=np.int32)
         self.capacity = 4 * w.frames + 64
         self.buffers = B.BestPathBuffers(w.channels, self.capacity, want_arcs=True)
@@ -97,8 +108,10 @@ class Session:
         self.step_stats = None
         for s in range(w.segments):
             lists, offs = self.inp.contexts[s]
-            if self.biased:
-                B.cbd_set_contexts(self.dh, self.all, lists, offs)
+            if self.biased and self.context_mode == "pool":
+                B.cbd_use_contexts(self.dh, self.all, self.pool_ids[s])
+            elif self.biased:
+                B.cbd_set_contexts(self.dh, self.all, None, offs, packed=self.packed[s])
             elif s == 0:
                 B.cbd_set_contexts(self.dh, self.all, [np.zeros(0, np.int32)] * w.channels,
                                    np.zeros(w.channels, np.float32))

@@ -197,6 +197,55 @@ def test_context_swap_mid_utterance_and_finals(torch_cuda):
               swap=(20, ctx2, off2))
 
 
+def test_preloaded_context_pool(torch_cuda):
+    """Sec. 4.3: contexts loaded in advance, channels switch among them by id (also shared by several
+    channels, also in mid-utterance), and can go back to their own uploaded list."""
+    torch = torch_cuda
+    g, L, ctxs, offs = mid_inputs(torch, C=4, T=36, seed=17)
+    Lh = L.cpu().numpy()
+    w2 = synth.scaled(synth.WORKLOADS["dynamic"], channels=3, ctx_min=20, ctx_max=400, config_id=78)
+    pool_lists, pool_offs = synth.make_contexts(w2, g, segment=2)
+    dec = GH.GpuDecoder(g, 4, 12.0, 0, max_frames=36, max_context_arcs=512, max_pool_contexts=3)
+    try:
+        ids = B.cbd_contexts_create(dec.dh, pool_lists, pool_offs)
+        assert sorted(ids.tolist()) == [0, 1, 2]
+        with pytest.raises(B.CbdError) as ei:   # pool is full
+            B.cbd_contexts_create(dec.dh, pool_lists[:1], pool_offs[:1])
+        assert ei.value.status == B.CBD_E_CAPACITY
+        dec.set_contexts(ctxs, offs)            # the channels' own lists
+        orcs = GH.oracle_channels(g, 4, 12.0, 0)
+        # channels 0 and 1 share pool context 1, channel 2 uses pool context 0, channel 3 keeps its own list
+        plan = {0: 1, 1: 1, 2: 0}
+        B.cbd_use_contexts(dec.dh, np.array([0, 1, 2], np.int32), np.array([ids[1], ids[1], ids[0]], np.int32))
+        for c in range(4):
+            if c in plan:
+                orcs[c].set_context(pool_lists[plan[c]], pool_offs[plan[c]])
+            else:
+                orcs[c].set_context(ctxs[c], offs[c])
+            orcs[c].reset()
+        dec.reset()
+        dec.advance(L, 0, 18)
+        for c in range(4):
+            orcs[c].advance(Lh[c, :18])
+        # mid-utterance: channel 0 goes back to its own list, channel 3 switches to pool context 2
+        B.cbd_use_contexts(dec.dh, np.array([0, 3], np.int32), np.array([-1, ids[2]], np.int32))
+        orcs[0].set_context(ctxs[0], offs[0])
+        orcs[3].set_context(pool_lists[2], pool_offs[2])
+        dec.advance(L, 18, 36)
+        for c in range(4):
+            orcs[c].advance(Lh[c, 18:])
+            GH.assert_tables_equal(dec.tokens(c), orcs[c].tokens(), f"pool ch={c}")
+            GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"pool ch={c}")
+        with pytest.raises(B.CbdError):
+            B.cbd_use_contexts(dec.dh, np.array([0], np.int32), np.array([7], np.int32))
+        B.cbd_context_destroy(dec.dh, int(ids[0]))
+        with pytest.raises(B.CbdError):
+            B.cbd_use_contexts(dec.dh, np.array([1], np.int32), np.array([ids[0]], np.int32))
+        assert B.cbd_contexts_create(dec.dh, pool_lists[:1], pool_offs[:1]).tolist() == [int(ids[0])]
+    finally:
+        dec.close()
+
+
 def test_channel_subset_and_reuse_after_reset(torch_cuda):
     """A subset of channels advances while the others wait; a channel reset for a second utterance
     gives the same result as a fresh decoder."""
