@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--table-location", type=int, default=0)
     ap.add_argument("--lds-token-cap", type=int, default=0)
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
+    ap.add_argument("--sync-partials", action="store_true",
+                    help="partial results with the blocking call instead of begin/finish requests")
     ap.add_argument("--context-mode", default="upload", choices=["upload", "pool"],
                     help="upload every segment's lists, or pre-load all of them and switch by id")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -113,7 +115,8 @@ def main():
     log(f"inputs: graph {inp.g.num_states} states {inp.g.num_arcs} arcs, {w.channels} channels x "
         f"{w.segments} x {w.frames} frames x {w.num_pdfs} pdfs in {time.perf_counter() - t0:.1f} s")
     sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
-                          biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode)
+                          biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
+                          async_partials=not args.sync_partials)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -156,7 +159,7 @@ def main():
         "config": {"workload": w.name, "channels": w.channels, "segments": w.segments, "frames": w.frames,
                    "chunk": w.chunk, "states": inp.g.num_states, "arcs": inp.g.num_arcs, "pdfs": w.num_pdfs,
                    "beam": w.beam, "max_active": w.max_active, "biased": not args.unbiased,
-                   "context_mode": args.context_mode,
+                   "context_mode": args.context_mode, "async_partials": not args.sync_partials,
                    "lookup_mode": w.lookup_mode, "lds_token_cap": info["lds_token_cap"],
                    "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"]},
         "arcs_per_s": arcs / (wall / args.steps),

@@ -185,6 +185,20 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
                        int32_t *status);
 
 /*
+ * The same in two steps, so that intermediate results leave the GPU without interrupting the
+ * decoding (Sec. 2.2).  cbd_best_paths_begin notes the best tokens on the decoder's stream and
+ * enqueues the path walks and the copy on a stream of the library's own; it returns at once with a
+ * ticket.  Calls enqueued afterwards (cbd_advance, context changes) do not disturb the request;
+ * cbd_reset_channels waits on the device for outstanding walks.  cbd_best_paths_finish waits for the
+ * request and fills the caller's arrays exactly like cbd_best_paths (same capacity as at begin; arcs
+ * only if want_arcs was set).  At most four requests may be in flight (CBD_E_CAPACITY).
+ */
+int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
+                             int32_t want_arcs, int32_t *ticket);
+int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status);
+
+/*
  * The channel's current token table (any order): state, cost, arc (caller's
  * numbering, -1 for the start token).  For tests and inspection.  Synchronises.
  * *n receives the table size; at most `capacity` entries are written.

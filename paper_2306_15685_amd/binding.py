@@ -21,7 +21,7 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
-    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_get_tokens",
+    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_get_tokens",
     "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
 
@@ -90,6 +90,10 @@ def lib():
     L.cbd_best_path.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp]
     L.cbd_best_paths.restype = i32
     L.cbd_best_paths.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+    L.cbd_best_paths_begin.restype = i32
+    L.cbd_best_paths_begin.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+    L.cbd_best_paths_finish.restype = i32
+    L.cbd_best_paths_finish.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     L.cbd_get_tokens.restype = i32
     L.cbd_get_tokens.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.cbd_get_stats.restype = i32
@@ -257,6 +261,32 @@ def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, 
     assert b.n >= n and b.capacity == capacity
     _check(lib().cbd_best_paths(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
                                 int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths")
+    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
+    if not as_lists:
+        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw
+    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    al = None
+    if want_arcs:
+        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    return st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()
+
+
+def cbd_best_paths_begin(d, channels, use_final=False, capacity=4096, want_arcs=True) -> int:
+    """Enqueues the request; returns a ticket for cbd_best_paths_finish."""
+    ch = _i32(channels)
+    t = C.c_int32(0)
+    _check(lib().cbd_best_paths_begin(d, _p(ch), int(ch.size), int(bool(use_final)), int(capacity), int(bool(want_arcs)),
+                                      C.byref(t)), "cbd_best_paths_begin")
+    return (t.value, int(ch.size), int(capacity), bool(want_arcs))
+
+
+def cbd_best_paths_finish(d, ticket, buffers: Optional[BestPathBuffers] = None, as_lists=True):
+    """Waits for the request; same return value as cbd_best_paths."""
+    t, n, capacity, want_arcs = ticket
+    b = buffers if buffers is not None else BestPathBuffers(n, capacity, want_arcs)
+    assert b.n >= n and b.capacity == capacity
+    _check(lib().cbd_best_paths_finish(d, t, _p(b.words), _p(b.arcs) if want_arcs else None, int(capacity),
+                                       _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths_finish")
     st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
     if not as_lists:
         return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw

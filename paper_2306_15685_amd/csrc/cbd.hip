@@ -3,6 +3,8 @@
 #include "../../include/cbd.h"
 
 #include <algorithm>
+#include <atomic>
+#include <thread>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -124,9 +126,18 @@ struct cbd_decoder {
   uint32_t *d_hkey = nullptr;
   uint64_t *d_hval = nullptr;
   uint32_t *d_hidx = nullptr;
-  int32_t *d_out_arcs = nullptr, *d_out_words = nullptr, *d_out_meta = nullptr;
-  int32_t *h_out_arcs = nullptr, *h_out_words = nullptr, *h_out_meta = nullptr;  // pinned
-  int32_t out_capacity = 0, out_rows = 0;
+  // best-path results: slot 0 serves the synchronous calls, the others asynchronous requests
+  static constexpr int kOutSlots = 5;
+  struct OutSlot {
+    int32_t *d_arcs = nullptr, *d_words = nullptr, *d_meta = nullptr, *d_snap = nullptr;
+    int32_t *h_arcs = nullptr, *h_words = nullptr, *h_meta = nullptr;   // pinned
+    int32_t rows = 0, capacity = 0;
+    int32_t n = 0, req_capacity = 0;
+    bool want_arcs = false, pending = false;
+    hipEvent_t done = nullptr;
+  } out[kOutSlots];
+  hipStream_t side = nullptr;      // walks and copies of asynchronous requests
+  hipEvent_t snap_ev = nullptr;
   StageRing ids;   // channel lists
   StageRing ctxs;  // context uploads
   std::vector<int32_t> h_tmp;
@@ -173,6 +184,82 @@ AdvanceParams base_params(const cbd_decoder *d) {
   p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx; p.ctx_n = d->d_ctx_n; p.ctx_off = d->d_ctx_off;
   p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_hidx = d->d_hidx;
   return p;
+}
+
+void free_out_slot(cbd_decoder::OutSlot &o) {
+  if (o.d_arcs) (void)hipFree(o.d_arcs);
+  if (o.d_words) (void)hipFree(o.d_words);
+  if (o.d_meta) (void)hipFree(o.d_meta);
+  if (o.d_snap) (void)hipFree(o.d_snap);
+  if (o.h_arcs) (void)hipHostFree(o.h_arcs);
+  if (o.h_words) (void)hipHostFree(o.h_words);
+  if (o.h_meta) (void)hipHostFree(o.h_meta);
+  o.d_arcs = o.d_words = o.d_meta = o.d_snap = o.h_arcs = o.h_words = o.h_meta = nullptr;
+  o.rows = o.capacity = 0;
+}
+
+// Makes the slot's buffers hold at least n rows of `capacity` entries (the slot must be idle).
+int32_t size_out_slot(cbd_decoder *d, cbd_decoder::OutSlot &o, int32_t n, int32_t capacity) {
+  if (o.capacity >= capacity && o.rows >= n) return CBD_OK;
+  const int32_t rows = std::max(n, o.rows), cap = std::max(capacity, o.capacity);
+  HIPCHK(hipStreamSynchronize(d->stream));
+  free_out_slot(o);
+  HIPCHK(dmalloc(&o.d_arcs, (size_t)rows * cap, nullptr));
+  HIPCHK(dmalloc(&o.d_words, (size_t)rows * cap, nullptr));
+  HIPCHK(dmalloc(&o.d_meta, (size_t)rows * 4, nullptr));
+  HIPCHK(dmalloc(&o.d_snap, (size_t)rows * cbd::kSnapInts, nullptr));
+  HIPCHK(hipHostMalloc((void **)&o.h_arcs, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
+  HIPCHK(hipHostMalloc((void **)&o.h_words, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
+  HIPCHK(hipHostMalloc((void **)&o.h_meta, sizeof(int32_t) * (size_t)rows * 4, hipHostMallocDefault));
+  o.rows = rows; o.capacity = cap;
+  return CBD_OK;
+}
+
+cbd::BestParams best_params(const cbd_decoder *d, const cbd_decoder::OutSlot &o, const int32_t *chan_ids,
+                            int32_t use_final, int32_t capacity) {
+  cbd::BestParams bp{};
+  bp.chan = d->d_chan; bp.chan_ids = chan_ids; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost;
+  bp.bp = d->d_bp; bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
+  bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
+  bp.row_pitch = o.capacity;
+  bp.out_arcs = o.d_arcs; bp.out_words = o.d_words; bp.out_meta = o.d_meta; bp.snap = o.d_snap;
+  return bp;
+}
+
+// Copies the header, then only as many columns of the word / arc rows as the longest path needs,
+// through pinned staging on stream `st`, waits, and hands the rows to the caller.
+int32_t fetch_results(cbd_decoder *d, cbd_decoder::OutSlot &o, hipStream_t st, int32_t n, int32_t capacity,
+                      int32_t *words, int32_t *arcs, int32_t *n_words, int32_t *n_arcs, float *cost,
+                      int32_t *status) {
+  int32_t *meta = o.h_meta;
+  HIPCHK(hipMemcpyAsync(meta, o.d_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, st));
+  HIPCHK(hipStreamSynchronize(st));
+  int32_t max_na = 0, max_nw = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (meta[(size_t)i * 4] != CBD_OK) continue;
+    max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
+    max_nw = std::max(max_nw, meta[(size_t)i * 4 + 2]);
+  }
+  const size_t pitch = sizeof(int32_t) * (size_t)o.capacity;
+  if (max_nw > 0)
+    HIPCHK(hipMemcpy2DAsync(o.h_words, pitch, o.d_words, pitch, sizeof(int32_t) * (size_t)max_nw, (size_t)n,
+                            hipMemcpyDeviceToHost, st));
+  if (arcs && max_na > 0)
+    HIPCHK(hipMemcpy2DAsync(o.h_arcs, pitch, o.d_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
+                            hipMemcpyDeviceToHost, st));
+  if (max_nw > 0 || (arcs && max_na > 0)) HIPCHK(hipStreamSynchronize(st));
+  for (int32_t i = 0; i < n; ++i) {
+    status[i] = meta[(size_t)i * 4 + 0];
+    n_arcs[i] = meta[(size_t)i * 4 + 1];
+    n_words[i] = meta[(size_t)i * 4 + 2];
+    uint32_t bits = (uint32_t)meta[(size_t)i * 4 + 3];
+    memcpy(&cost[i], &bits, 4);
+    if (status[i] != CBD_OK) continue;
+    memcpy(words + (size_t)i * capacity, o.h_words + (size_t)i * o.capacity, sizeof(int32_t) * (size_t)n_words[i]);
+    if (arcs)
+      memcpy(arcs + (size_t)i * capacity, o.h_arcs + (size_t)i * o.capacity, sizeof(int32_t) * (size_t)n_arcs[i]);
+  }
+  return CBD_OK;
 }
 
 // Validates a channel list and uploads it; *dev receives the device copy.
@@ -420,12 +507,16 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_first, d->d_tok_eps, d->d_tok_end, d->d_bp,
-                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_out_arcs, d->d_out_words, d->d_out_meta};
+                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
-  if (d->h_out_arcs) (void)hipHostFree(d->h_out_arcs);
-  if (d->h_out_words) (void)hipHostFree(d->h_out_words);
-  if (d->h_out_meta) (void)hipHostFree(d->h_out_meta);
+  if (d->side) (void)hipStreamSynchronize(d->side);
+  for (auto &o : d->out) {
+    free_out_slot(o);
+    if (o.done) (void)hipEventDestroy(o.done);
+  }
+  if (d->side) (void)hipStreamDestroy(d->side);
+  if (d->snap_ev) (void)hipEventDestroy(d->snap_ev);
   d->ids.destroy();
   d->ctxs.destroy();
   delete d;
@@ -448,6 +539,9 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n, &dev, &slot);
   if (rc != CBD_OK) return rc;
+  // a new utterance reuses the back-pointer buffer from its start: let outstanding walks finish first
+  for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
+    if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = nullptr; p.channel_stride = 0; p.n_frames = 0; p.do_reset = 1;
   HIPCHK(launch_advance(d, p, n));
@@ -470,19 +564,43 @@ int32_t prepare_lists(const cbd_decoder *d, int32_t n, const int32_t *arc_idx, c
   }
   const int32_t total = list_offsets[n];
   if (total > 0 && !arc_idx) return fail(CBD_E_INVALID, w + ": null list");
-  for (int32_t k = 0; k < total; ++k)
-    if (arc_idx[k] < 0 || arc_idx[k] >= d->g->A) return fail(CBD_E_INVALID, w + ": arc index out of range");
-  // the list is a set: sort + de-duplicate, in place in the packed array
+  // the list is a set: translate to the library's arc order, sort, de-duplicate.  Lists are independent,
+  // so large uploads are split over a few host threads (each list is handled in place in `packed`).
   packed.resize((size_t)total);
   new_off.assign((size_t)n + 1, 0);
+  std::vector<int32_t> count((size_t)n, 0);
   const int32_t *p2i = d->g->pub2int.data();
+  const int32_t num_arcs = d->g->A;
+  std::atomic<int> bad{0};
+  auto work = [&](int32_t i0, int32_t i1) {
+    for (int32_t i = i0; i < i1; ++i) {
+      const int32_t b = list_offsets[i], e = list_offsets[i + 1];
+      for (int32_t k = b; k < e; ++k) {
+        int32_t a = arc_idx[k];
+        if (a < 0 || a >= num_arcs) { bad.store(1); return; }
+        packed[(size_t)k] = p2i[a];
+      }
+      std::sort(packed.begin() + b, packed.begin() + e);
+      count[(size_t)i] = (int32_t)(std::unique(packed.begin() + b, packed.begin() + e) - (packed.begin() + b));
+    }
+  };
+  const int n_threads = total >= 32768 ? std::min<int>(8, std::max(1u, std::thread::hardware_concurrency())) : 1;
+  if (n_threads <= 1) {
+    work(0, n);
+  } else {
+    std::vector<std::thread> pool;
+    for (int t = 0; t < n_threads; ++t)
+      pool.emplace_back(work, (int32_t)((int64_t)n * t / n_threads), (int32_t)((int64_t)n * (t + 1) / n_threads));
+    for (auto &th : pool) th.join();
+  }
+  if (bad.load()) return fail(CBD_E_INVALID, w + ": arc index out of range");
   int32_t out = 0;
   for (int32_t i = 0; i < n; ++i) {
-    const int32_t b = out;
-    for (int32_t k = list_offsets[i]; k < list_offsets[i + 1]; ++k) packed[(size_t)out++] = p2i[arc_idx[k]];
-    std::sort(packed.begin() + b, packed.begin() + out);
-    out = (int32_t)(std::unique(packed.begin() + b, packed.begin() + out) - packed.begin());
-    if (out - b > d->cfg.max_context_arcs) return fail(CBD_E_INVALID, w + ": more than max_context_arcs distinct arcs");
+    if (count[(size_t)i] > d->cfg.max_context_arcs)
+      return fail(CBD_E_INVALID, w + ": more than max_context_arcs distinct arcs");
+    const int32_t b = list_offsets[i];
+    if (out != b) std::copy(packed.begin() + b, packed.begin() + b + count[(size_t)i], packed.begin() + out);
+    out += count[(size_t)i];
     new_off[(size_t)i + 1] = out;
   }
   packed.resize((size_t)out);
@@ -635,66 +753,62 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n, &dev, &slot);
   if (rc != CBD_OK) return rc;
-  if (d->out_capacity < capacity || d->out_rows < n) {
-    const int32_t rows = std::max(n, d->out_rows), cap = std::max(capacity, d->out_capacity);
-    HIPCHK(hipStreamSynchronize(d->stream));
-    if (d->d_out_arcs) (void)hipFree(d->d_out_arcs);
-    if (d->d_out_words) (void)hipFree(d->d_out_words);
-    if (d->d_out_meta) (void)hipFree(d->d_out_meta);
-    if (d->h_out_arcs) (void)hipHostFree(d->h_out_arcs);
-    if (d->h_out_words) (void)hipHostFree(d->h_out_words);
-    if (d->h_out_meta) (void)hipHostFree(d->h_out_meta);
-    d->d_out_arcs = d->d_out_words = d->d_out_meta = nullptr;
-    d->h_out_arcs = d->h_out_words = d->h_out_meta = nullptr;
-    d->out_rows = d->out_capacity = 0;
-    HIPCHK(dmalloc(&d->d_out_arcs, (size_t)rows * cap, nullptr));
-    HIPCHK(dmalloc(&d->d_out_words, (size_t)rows * cap, nullptr));
-    HIPCHK(dmalloc(&d->d_out_meta, (size_t)rows * 4, nullptr));
-    HIPCHK(hipHostMalloc((void **)&d->h_out_arcs, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
-    HIPCHK(hipHostMalloc((void **)&d->h_out_words, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
-    HIPCHK(hipHostMalloc((void **)&d->h_out_meta, sizeof(int32_t) * (size_t)rows * 4, hipHostMallocDefault));
-    d->out_rows = rows; d->out_capacity = cap;
-  }
-  cbd::BestParams bp{};
-  bp.chan = d->d_chan; bp.chan_ids = dev; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost; bp.bp = d->d_bp;
-  bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
-  bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
-  bp.row_pitch = d->out_capacity;
-  bp.out_arcs = d->d_out_arcs; bp.out_words = d->d_out_words; bp.out_meta = d->d_out_meta;
+  cbd_decoder::OutSlot &o = d->out[0];
+  rc = size_out_slot(d, o, n, capacity);
+  if (rc != CBD_OK) return rc;
+  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
   hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(d->ids.release(slot, d->stream));
-  // results come back through pinned staging: the small header first, then only as many
-  // columns of the word / arc rows as the longest path needs
-  int32_t *meta = d->h_out_meta;
-  HIPCHK(hipMemcpyAsync(meta, d->d_out_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, d->stream));
-  HIPCHK(hipStreamSynchronize(d->stream));
-  int32_t max_na = 0, max_nw = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    if (meta[(size_t)i * 4] != CBD_OK) continue;
-    max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
-    max_nw = std::max(max_nw, meta[(size_t)i * 4 + 2]);
-  }
-  const size_t pitch = sizeof(int32_t) * (size_t)d->out_capacity;
-  if (max_nw > 0)
-    HIPCHK(hipMemcpy2DAsync(d->h_out_words, pitch, d->d_out_words, pitch, sizeof(int32_t) * (size_t)max_nw, (size_t)n,
-                            hipMemcpyDeviceToHost, d->stream));
-  if (arcs && max_na > 0)
-    HIPCHK(hipMemcpy2DAsync(d->h_out_arcs, pitch, d->d_out_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
-                            hipMemcpyDeviceToHost, d->stream));
-  if (max_nw > 0 || (arcs && max_na > 0)) HIPCHK(hipStreamSynchronize(d->stream));
-  for (int32_t i = 0; i < n; ++i) {
-    status[i] = meta[(size_t)i * 4 + 0];
-    n_arcs[i] = meta[(size_t)i * 4 + 1];
-    n_words[i] = meta[(size_t)i * 4 + 2];
-    uint32_t bits = (uint32_t)meta[(size_t)i * 4 + 3];
-    memcpy(&cost[i], &bits, 4);
-    if (status[i] != CBD_OK) continue;
-    memcpy(words + (size_t)i * capacity, d->h_out_words + (size_t)i * d->out_capacity, sizeof(int32_t) * (size_t)n_words[i]);
-    if (arcs)
-      memcpy(arcs + (size_t)i * capacity, d->h_out_arcs + (size_t)i * d->out_capacity, sizeof(int32_t) * (size_t)n_arcs[i]);
-  }
+  return fetch_results(d, o, d->stream, n, capacity, words, arcs, n_words, n_arcs, cost, status);
+}
+
+int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
+                             int32_t want_arcs, int32_t *ticket) {
+  if (!d || !ticket) return fail(CBD_E_INVALID, "best_paths_begin: null argument");
+  if (capacity < 1) return fail(CBD_E_INVALID, "best_paths_begin: capacity < 1");
+  int t = -1;
+  for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
+    if (!d->out[k].pending) { t = k; break; }
+  if (t < 0) return fail(CBD_E_CAPACITY, "best_paths_begin: too many requests in flight (finish one first)");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  cbd_decoder::OutSlot &o = d->out[t];
+  rc = size_out_slot(d, o, n, capacity);
+  if (rc != CBD_OK) return rc;
+  if (!d->side) HIPCHK(hipStreamCreateWithFlags(&d->side, hipStreamNonBlocking));
+  if (!d->snap_ev) HIPCHK(hipEventCreateWithFlags(&d->snap_ev, hipEventDisableTiming));
+  if (!o.done) HIPCHK(hipEventCreateWithFlags(&o.done, hipEventDisableTiming));
+  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
+  // decode stream: pick the best tokens now, before a later call changes the channels
+  hipLaunchKernelGGL(cbd::best_snapshot_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
+  HIPCHK(hipGetLastError());
+  HIPCHK(d->ids.release(slot, d->stream));
+  HIPCHK(hipEventRecord(d->snap_ev, d->stream));
+  // side stream: the walk reads only records that are already final, so it runs beside later decoding
+  HIPCHK(hipStreamWaitEvent(d->side, d->snap_ev, 0));
+  hipLaunchKernelGGL(cbd::best_walk_kernel, dim3((unsigned)n), dim3(64), 0, d->side, bp);
+  HIPCHK(hipGetLastError());
+  HIPCHK(hipEventRecord(o.done, d->side));
+  o.pending = true; o.n = n; o.req_capacity = capacity; o.want_arcs = want_arcs != 0;
+  *ticket = t;
   return CBD_OK;
+}
+
+int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status) {
+  if (!d || !words || !n_words || !n_arcs || !cost || !status)
+    return fail(CBD_E_INVALID, "best_paths_finish: null argument");
+  if (ticket < 1 || ticket >= cbd_decoder::kOutSlots || !d->out[ticket].pending)
+    return fail(CBD_E_INVALID, "best_paths_finish: no such request");
+  cbd_decoder::OutSlot &o = d->out[ticket];
+  if (capacity != o.req_capacity) return fail(CBD_E_INVALID, "best_paths_finish: capacity differs from the request");
+  if (arcs && !o.want_arcs) return fail(CBD_E_INVALID, "best_paths_finish: arcs were not requested");
+  int32_t rc = fetch_results(d, o, d->side, o.n, capacity, words, arcs, n_words, n_arcs, cost, status);
+  o.pending = false;
+  return rc;
 }
 
 int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_t *words, int32_t *arcs,

@@ -1030,23 +1030,13 @@ struct BestParams {
   int32_t *out_arcs;        // [n][row_pitch]
   int32_t *out_words;       // [n][row_pitch]
   int32_t *out_meta;        // [n][4]: status, n_arcs, n_words, cost bits
+  int32_t *snap;            // [n][kSnapInts] snapshot taken on the decode stream (two-stage form only)
 };
+constexpr int kSnapInts = 8;   // status, best record, cost bits, records in use, channel
 
-// One wave per channel: best token (Sec. 1: the current best token sequence is
-// read directly, no lattice), then the back-pointer walk, then olabels in time order.
-__global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
-  const int lane = threadIdx.x;
-  const int i = blockIdx.x;
-  const int c = p.chan_ids[i];
-  const ChanState *cs = p.chan + c;
-  int32_t *meta = p.out_meta + (size_t)i * 4;
-  int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
-  int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
-  const int inf_bits = (int)__float_as_uint(__builtin_inff());
-  if (cs->status != kStatusOk) {
-    if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
-    return;
-  }
+// Best token of a channel's current table (Sec. 1: the current best token sequence is read
+// directly, no lattice).  One wave.  Returns the record index or -1; key receives (cost, arc).
+__device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanState *cs, uint64_t &key, int lane) {
   const int n = cs->n_tok, base = cs->frame_base;
   const int32_t *ts = p.tok_state + (size_t)c * p.tok_cap;
   const float *tc = p.tok_cost + (size_t)c * p.tok_cap;
@@ -1067,23 +1057,32 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
     int oi = __shfl_xor(besti, d, 64);
     if (ok < bestk) { bestk = ok; besti = oi; }
   }
-  if (besti < 0) {
-    if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
-    return;
-  }
-  // walk back: lane 0 writes the arcs newest-first into the output row
-  // (a path can never be longer than the records in use; the bound also ends
-  // the walk on a predecessor cycle, which zero-weight epsilon cycles can form)
-  const int max_steps = cs->n_rec;
+  key = bestk;
+  return besti < 0 ? -1 : base + besti;
+}
+
+// Back-pointer walk from record `rec` and labels in time order.  One wave.  Only records below
+// n_rec are touched (they never change once written), so this may run beside later decoding.
+__device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int rec, int n_rec, uint32_t cost_ord,
+                                          int lane) {
+  int32_t *meta = p.out_meta + (size_t)i * 4;
+  int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
+  int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
+  const int2 *bp = p.bp + (size_t)c * p.bp_cap;
+  const int inf_bits = (int)__float_as_uint(__builtin_inff());
+  // lane 0 writes the arcs newest-first into the output row.  A path can never be longer than the
+  // records in use; the bound also ends the walk on a predecessor cycle, which zero-weight epsilon
+  // cycles can form.
+  const int max_steps = n_rec;
   int na = 0;
   if (lane == 0) {
-    int r = base + besti;
+    int r = rec;
     while (r >= 0 && na <= max_steps) {
-      int2 rec = bp[r];
-      if ((uint32_t)rec.x == kArcNone) break;
-      if (na < p.capacity) oarcs[na] = rec.x;
+      int2 e = bp[r];
+      if ((uint32_t)e.x == kArcNone) break;
+      if (na < p.capacity) oarcs[na] = e.x;
       na++;
-      r = rec.y;
+      r = e.y;
     }
   }
   na = __shfl(na, 0, 64);
@@ -1096,14 +1095,14 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
     // count the words too so the caller learns both sizes
     int nw = 0;
     if (lane == 0) {
-      int r = base + besti;
+      int r = rec;
       for (int step = 0; r >= 0 && step < na; ++step) {
-        int2 rec = bp[r];
-        if ((uint32_t)rec.x == kArcNone) break;
-        if (p.olabel[rec.x] != 0) nw++;
-        r = rec.y;
+        int2 e = bp[r];
+        if ((uint32_t)e.x == kArcNone) break;
+        if (p.olabel[e.x] != 0) nw++;
+        r = e.y;
       }
-      meta[0] = kStatusBuffer; meta[1] = na; meta[2] = nw; meta[3] = (int)__float_as_uint(ord2f((uint32_t)(bestk >> 32)));
+      meta[0] = kStatusBuffer; meta[1] = na; meta[2] = nw; meta[3] = (int)__float_as_uint(ord2f(cost_ord));
     }
     return;
   }
@@ -1129,8 +1128,58 @@ __global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
   }
   if (lane == 0) {
     meta[0] = kStatusOk; meta[1] = na; meta[2] = nw_total;
-    meta[3] = (int)__float_as_uint(ord2f((uint32_t)(bestk >> 32)));
+    meta[3] = (int)__float_as_uint(ord2f(cost_ord));
   }
+}
+
+// One wave per channel: best token, then its path.
+__global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
+  const int lane = threadIdx.x, i = blockIdx.x;
+  const int c = p.chan_ids[i];
+  const ChanState *cs = p.chan + c;
+  int32_t *meta = p.out_meta + (size_t)i * 4;
+  const int inf_bits = (int)__float_as_uint(__builtin_inff());
+  if (cs->status != kStatusOk) {
+    if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
+    return;
+  }
+  uint64_t key;
+  int rec = find_best(p, c, cs, key, lane);
+  if (rec < 0) {
+    if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
+    return;
+  }
+  walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane);
+}
+
+// Two-stage form for results delivered beside later decoding.  Stage 1 (decode stream): pick the
+// best token and note everything the walk needs, before the next call changes the channel.
+__global__ __launch_bounds__(64) void best_snapshot_kernel(BestParams p) {
+  const int lane = threadIdx.x, i = blockIdx.x;
+  const int c = p.chan_ids[i];
+  const ChanState *cs = p.chan + c;
+  int32_t *snap = p.snap + (size_t)i * kSnapInts;
+  int status = cs->status, rec = -1;
+  uint64_t key = kEmptyVal;
+  if (status == kStatusOk) {
+    rec = find_best(p, c, cs, key, lane);
+    if (rec < 0) status = kStatusNoTokens;
+  }
+  if (lane == 0) {
+    snap[0] = status; snap[1] = rec; snap[2] = (int)(uint32_t)(key >> 32); snap[3] = cs->n_rec; snap[4] = c;
+  }
+}
+
+// Stage 2 (side stream): the walk, from the snapshot only.
+__global__ __launch_bounds__(64) void best_walk_kernel(BestParams p) {
+  const int lane = threadIdx.x, i = blockIdx.x;
+  const int32_t *snap = p.snap + (size_t)i * kSnapInts;
+  int32_t *meta = p.out_meta + (size_t)i * 4;
+  if (snap[0] != kStatusOk) {
+    if (lane == 0) { meta[0] = snap[0]; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
+    return;
+  }
+  walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane);
 }
 
 }  // namespace cbd

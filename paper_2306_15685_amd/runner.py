@@ -45,7 +45,7 @@ class Session:
 
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
-                 context_mode: str = "upload"):
+                 context_mode: str = "upload", async_partials: bool = True):
         """context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
         segments' lists once with cbd_contexts_create and switches by id (Sec. 4.3)."""
         import torch
@@ -65,6 +65,7 @@ class Session:
             w.channels * w.segments if context_mode == "pool" else 0,
             hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode
+        self.async_partials = async_partials   # partial results through cbd_best_paths_begin / _finish
         # contexts packed once: per segment (arc_idx, list_offsets)
         self.packed = [B.pack_lists(lists) for lists, _ in inp.contexts]
         self.pool_ids = None
@@ -118,15 +119,29 @@ class Session:
             B.cbd_reset_channels(self.dh, self.all)
             L = self.inp.loglikes[s]
             t = 0
+            pending = None   # (ticket, frames done) of the partial request still in flight
             while t < w.frames:
                 n = min(w.chunk, w.frames - t)
                 self._advance(L, t, n)
                 t += n
                 if w.partial_every_chunk and t < w.frames:
-                    r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
-                                         buffers=self.buffers, as_lists=keep_results)
-                    if keep_results:
-                        self.partials.append((s, t, r))
+                    if self.async_partials:
+                        # one request in flight: the walk and copy of chunk k overlap the decoding of chunk k+1
+                        tk = B.cbd_best_paths_begin(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
+                        if pending is not None:
+                            r = B.cbd_best_paths_finish(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
+                            if keep_results:
+                                self.partials.append((s, pending[1], r))
+                        pending = (tk, t)
+                    else:
+                        r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
+                                             buffers=self.buffers, as_lists=keep_results)
+                        if keep_results:
+                            self.partials.append((s, t, r))
+            if pending is not None:
+                r = B.cbd_best_paths_finish(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
+                if keep_results:
+                    self.partials.append((s, pending[1], r))
             r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results,
                                  buffers=self.buffers, as_lists=keep_results)
             if keep_results:

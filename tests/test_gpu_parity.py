@@ -246,6 +246,46 @@ def test_preloaded_context_pool(torch_cuda):
         dec.close()
 
 
+def test_asynchronous_partial_results(torch_cuda):
+    """Requests begun after a chunk and finished only after later chunks have been decoded (and a new
+    utterance started) still describe the moment of the request (Sec. 2.2: intermediate results leave
+    the GPU without interrupting the decoding)."""
+    torch = torch_cuda
+    g, L, ctxs, offs = mid_inputs(torch, C=5, T=40, seed=18)
+    Lh = L.cpu().numpy()
+    dec = GH.GpuDecoder(g, 5, 12.0, 0, max_frames=40)
+    try:
+        orcs = GH.oracle_channels(g, 5, 12.0, 0)
+        dec.set_contexts(ctxs, offs)
+        for c in range(5):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset()
+        dec.reset()
+        want, tickets = [], []
+        for k, (t0, t1) in enumerate([(0, 10), (10, 20), (20, 30), (30, 40)]):
+            dec.advance(L, t0, t1)
+            for c in range(5):
+                orcs[c].advance(Lh[c, t0:t1])
+            tickets.append(B.cbd_best_paths_begin(dec.dh, dec.all, False, capacity=200))
+            want.append([orcs[c].best_path(False) for c in range(5)])
+        with pytest.raises(B.CbdError) as ei:   # four requests are the limit
+            B.cbd_best_paths_begin(dec.dh, dec.all, False, capacity=200)
+        assert ei.value.status == B.CBD_E_CAPACITY
+        dec.reset()                              # new utterance while the requests are still out
+        dec.advance(L, 0, 5)
+        for k in (2, 0, 3, 1):                   # any order
+            st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, tickets[k])
+            for c in range(5):
+                GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), want[k][c], f"request {k} ch {c}")
+        with pytest.raises(B.CbdError):
+            B.cbd_best_paths_finish(dec.dh, tickets[0])   # already collected
+        # the decoder went on meanwhile
+        for c in range(5):
+            orcs[c].reset(); orcs[c].advance(Lh[c, :5])
+            GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"after requests ch {c}")
+    finally:
+        dec.close()
+
+
 def test_channel_subset_and_reuse_after_reset(torch_cuda):
     """A subset of channels advances while the others wait; a channel reset for a second utterance
     gives the same result as a fresh decoder."""
