@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--hash-log2", type=int, default=0)
     ap.add_argument("--table-location", type=int, default=0)
     ap.add_argument("--lds-token-cap", type=int, default=0)
+    ap.add_argument("--lookup-mode", type=int, default=-1, help="0 binary search, 1 Bloom filter + search; default: the workload's")
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
     ap.add_argument("--sync-partials", action="store_true",
                     help="partial results with the blocking call instead of begin/finish requests")
@@ -109,6 +110,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.channels:
         w = synth.scaled(w, channels=args.channels)
+    if args.lookup_mode >= 0:
+        w = synth.scaled(w, lookup_mode=args.lookup_mode)
     t0 = time.perf_counter()
     inp = runner.make_inputs(w)
     torch.cuda.synchronize()

@@ -86,6 +86,19 @@ typedef struct cbd_graph_desc {
 int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out);
 int32_t cbd_graph_free(cbd_graph *g);
 
+/*
+ * Which arcs to boost for a biasing list of word sequences (Algorithm 1; host only, no GPU work).
+ * words: HOST, the sequences' word ids back to back; sequence i is words[seq_offsets[i] ..
+ * seq_offsets[i+1]) (seq_offsets HOST [n_seq+1]).  For each sequence w_1..w_k: every arc that outputs
+ * w_1 (the sequence may start anywhere in the graph), and for t > 1 every arc that outputs w_t and
+ * leaves a state reached from a w_{t-1} arc of the sequence so far through arcs without output label.
+ * The union over the sequences is written to arcs (HOST [capacity]) sorted and without duplicates,
+ * ready for cbd_set_context; *n_arcs receives its size.  CBD_E_BUFFER if capacity is too small
+ * (*n_arcs = needed size).  Unknown words contribute nothing.  Not thread-safe per graph.
+ */
+int32_t cbd_context_from_words(cbd_graph *g, const int32_t *words, const int32_t *seq_offsets, int32_t n_seq,
+                               int32_t *arcs, int32_t capacity, int32_t *n_arcs);
+
 typedef struct cbd_config {
   int32_t num_channels;       /* >= 1 */
   float beam;                 /* >= 0; may be +inf */

@@ -5,3 +5,4 @@ package.  It shares nothing with the HIP library.
 """
 from .oracle import (OracleGraph, OracleChannel, build_oracle, prune,  # noqa: F401
                      ORC_OK, ORC_NO_TOKENS, ORC_EPS_DIVERGED)
+from .word_arcs import arcs_for_sequence, arcs_for_sequences  # noqa: F401

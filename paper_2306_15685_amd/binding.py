@@ -20,7 +20,7 @@ CBD_OK, CBD_E_INVALID, CBD_E_CAPACITY, CBD_E_EPS_DIVERGED = 0, -1, -2, -3
 CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
-    "cbd_graph_load", "cbd_graph_free", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
+    "cbd_graph_load", "cbd_graph_free", "cbd_context_from_words", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
     "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_get_tokens",
     "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
@@ -68,6 +68,8 @@ def lib():
     L.cbd_graph_load.argtypes = [C.POINTER(cbd_graph_desc), C.POINTER(vp)]
     L.cbd_graph_free.restype = i32
     L.cbd_graph_free.argtypes = [vp]
+    L.cbd_context_from_words.restype = i32
+    L.cbd_context_from_words.argtypes = [vp, vp, vp, i32, vp, i32, vp]
     L.cbd_decoder_create.restype = i32
     L.cbd_decoder_create.argtypes = [vp, C.POINTER(cbd_config), vp, C.POINTER(vp)]
     L.cbd_decoder_free.restype = i32
@@ -149,6 +151,21 @@ def cbd_graph_load(num_states, num_pdfs, start_state, row_offsets, dst, ilabel, 
 
 def cbd_graph_free(g):
     _check(lib().cbd_graph_free(g), "cbd_graph_free")
+
+
+def cbd_context_from_words(g, sequences) -> np.ndarray:
+    """Algorithm 1 for a list of word-id sequences -> sorted arc indices."""
+    words, offs = pack_lists([np.asarray(x, dtype=np.int32) for x in sequences])
+    cap = 1 << 14
+    while True:
+        arcs = np.zeros(cap, np.int32)
+        n = C.c_int32(0)
+        rc = lib().cbd_context_from_words(g, _p(words), _p(offs), int(len(sequences)), _p(arcs), cap, C.byref(n))
+        if rc == CBD_E_BUFFER:
+            cap = n.value
+            continue
+        _check(rc, "cbd_context_from_words")
+        return arcs[:n.value].copy()
 
 
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,

@@ -100,6 +100,13 @@ struct cbd_graph {
   int32_t *d_olabel = nullptr;
   float *d_final = nullptr;
   std::vector<int32_t> pub2int, int2pub;
+  // host copy in the caller's numbering, for building contexts from word sequences
+  std::vector<int32_t> h_row, h_dst, h_olabel;
+  std::vector<int32_t> word_arcs;   // arcs that carry a word, ordered by (word, arc); built on first use
+  std::vector<int32_t> word_first;  // [num_words + 2] start of each word's run in word_arcs
+  std::vector<int32_t> visit;       // [S] search stamps
+  int32_t visit_stamp = 0;
+  int32_t max_word = 0;
   size_t bytes = 0;
 };
 
@@ -320,6 +327,9 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   cbd_graph *g = new (std::nothrow) cbd_graph();
   if (!g) return fail(CBD_E_NOMEM, "graph: host allocation");
   g->S = S; g->A = A; g->P = P; g->start = desc->start_state;
+  g->h_row.assign(row, row + S + 1);
+  g->h_dst.assign(desc->dst, desc->dst + A);
+  g->h_olabel.assign(desc->olabel, desc->olabel + A);
   if (hipGetDevice(&g->device) != hipSuccess) { delete g; return fail(CBD_E_HIP, "hipGetDevice failed"); }
   // library order: per state, emitting arcs first, then epsilon-input arcs, each in the caller's order
   std::vector<int2> off2((size_t)S + 1);
@@ -374,6 +384,109 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   }
 #undef GCHK
   *out = g;
+  return CBD_OK;
+}
+
+namespace {
+
+// source state of an arc in the caller's numbering
+int32_t arc_source(const cbd_graph *g, int32_t a) {
+  return (int32_t)(std::upper_bound(g->h_row.begin(), g->h_row.end(), a) - g->h_row.begin()) - 1;
+}
+
+void build_word_index(cbd_graph *g) {
+  if (!g->word_first.empty()) return;
+  int32_t mw = 0;
+  for (int32_t w : g->h_olabel) mw = std::max(mw, w);
+  g->max_word = mw;
+  g->word_first.assign((size_t)mw + 2, 0);
+  for (int32_t w : g->h_olabel)
+    if (w > 0) g->word_first[(size_t)w + 1]++;
+  for (size_t w = 1; w < g->word_first.size(); ++w) g->word_first[w] += g->word_first[w - 1];
+  g->word_arcs.resize((size_t)g->word_first.back());
+  std::vector<int32_t> fill(g->word_first.begin(), g->word_first.end() - 1);
+  for (int32_t a = 0; a < g->A; ++a) {
+    int32_t w = g->h_olabel[(size_t)a];
+    if (w > 0) g->word_arcs[(size_t)fill[(size_t)w]++] = a;
+  }
+  g->visit.assign((size_t)g->S, 0);
+}
+
+bool state_outputs(const cbd_graph *g, int32_t s, int32_t w) {
+  for (int32_t a = g->h_row[(size_t)s]; a < g->h_row[(size_t)s + 1]; ++a)
+    if (g->h_olabel[(size_t)a] == w) return true;
+  return false;
+}
+
+// Algorithm 1 for one word sequence; arcs are appended to `out` (duplicates possible).
+void arcs_for_sequence(cbd_graph *g, const int32_t *words, int32_t k, std::vector<int32_t> &out) {
+  if (k <= 0) return;
+  auto run = [&](int32_t w, const int32_t **b, const int32_t **e) {
+    if (w <= 0 || w > g->max_word) { *b = *e = nullptr; return; }
+    *b = g->word_arcs.data() + g->word_first[(size_t)w];
+    *e = g->word_arcs.data() + g->word_first[(size_t)w + 1];
+  };
+  // states that output w_1: the sequence may start anywhere (Sec. 4.1)
+  std::vector<int32_t> reached, next, stack;
+  const int32_t *b, *e;
+  run(words[0], &b, &e);
+  for (const int32_t *p = b; p != e; ++p) reached.push_back(arc_source(g, *p));
+  std::sort(reached.begin(), reached.end());
+  reached.erase(std::unique(reached.begin(), reached.end()), reached.end());
+  for (int32_t t = 1; t < k; ++t) {
+    const int32_t w_prev = words[t - 1], w_next = words[t];
+    next.clear();
+    if (++g->visit_stamp == 0x7FFFFFFF) { std::fill(g->visit.begin(), g->visit.end(), 0); g->visit_stamp = 1; }
+    const int32_t stamp = g->visit_stamp;
+    for (int32_t s_p : reached) {
+      // leave s_p through an arc that outputs the previous word, then follow arcs without output
+      // label; states on the way that can output the next word are where the sequence continues
+      for (int32_t a = g->h_row[(size_t)s_p]; a < g->h_row[(size_t)s_p + 1]; ++a) {
+        if (g->h_olabel[(size_t)a] != w_prev) continue;
+        out.push_back(a);
+        stack.push_back(g->h_dst[(size_t)a]);
+      }
+      while (!stack.empty()) {
+        int32_t q = stack.back();
+        stack.pop_back();
+        if (g->visit[(size_t)q] == stamp) continue;   // shared by all s_p of this step: the result is a union
+        g->visit[(size_t)q] = stamp;
+        if (state_outputs(g, q, w_next)) next.push_back(q);
+        for (int32_t a = g->h_row[(size_t)q]; a < g->h_row[(size_t)q + 1]; ++a)
+          if (g->h_olabel[(size_t)a] == 0) stack.push_back(g->h_dst[(size_t)a]);
+      }
+    }
+    std::sort(next.begin(), next.end());
+    next.erase(std::unique(next.begin(), next.end()), next.end());
+    reached.swap(next);
+  }
+  const int32_t w_last = words[k - 1];
+  for (int32_t s : reached)
+    for (int32_t a = g->h_row[(size_t)s]; a < g->h_row[(size_t)s + 1]; ++a)
+      if (g->h_olabel[(size_t)a] == w_last) out.push_back(a);
+}
+
+}  // namespace
+
+int32_t cbd_context_from_words(cbd_graph *g, const int32_t *words, const int32_t *seq_offsets, int32_t n_seq,
+                               int32_t *arcs, int32_t capacity, int32_t *n_arcs) {
+  if (!g || !seq_offsets || !n_arcs) return fail(CBD_E_INVALID, "context_from_words: null argument");
+  if (n_seq < 0 || seq_offsets[0] != 0) return fail(CBD_E_INVALID, "context_from_words: bad sequence offsets");
+  for (int32_t i = 0; i < n_seq; ++i)
+    if (seq_offsets[i + 1] < seq_offsets[i]) return fail(CBD_E_INVALID, "context_from_words: offsets not monotone");
+  if (n_seq > 0 && seq_offsets[n_seq] > 0 && !words) return fail(CBD_E_INVALID, "context_from_words: null words");
+  build_word_index(g);
+  std::vector<int32_t> out;
+  for (int32_t i = 0; i < n_seq; ++i)
+    arcs_for_sequence(g, words + seq_offsets[i], seq_offsets[i + 1] - seq_offsets[i], out);
+  std::sort(out.begin(), out.end());
+  out.erase(std::unique(out.begin(), out.end()), out.end());
+  *n_arcs = (int32_t)out.size();
+  if ((int32_t)out.size() > capacity) return CBD_E_BUFFER;
+  if (!out.empty()) {
+    if (!arcs) return fail(CBD_E_INVALID, "context_from_words: null output");
+    memcpy(arcs, out.data(), sizeof(int32_t) * out.size());
+  }
   return CBD_OK;
 }
 

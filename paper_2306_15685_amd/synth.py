@@ -56,9 +56,9 @@ WORKLOADS: Dict[str, Workload] = {
     "medium": Workload("medium", 1_000_000, 3_000, 20_000, 0.10, 32, 333, 333, 13.0, 7_000, 4.0,
                        50, 50, -5.0, -5.0, config_id=1),
     "large": Workload("large", 10_000_000, 6_000, 200_000, 0.10, 256, 500, 50, 15.0, 10_000, 4.0,
-                      100, 500, -5.0, -5.0, partial_every_chunk=True, config_id=2),
+                      100, 500, -5.0, -5.0, partial_every_chunk=True, lookup_mode=1, config_id=2),
     "dynamic": Workload("dynamic", 10_000_000, 6_000, 200_000, 0.10, 512, 100, 100, 15.0, 10_000, 4.0,
-                        10, 1_000, -8.0, -2.0, segments=20, config_id=3),
+                        10, 1_000, -8.0, -2.0, segments=20, lookup_mode=1, config_id=3),
     "stress": Workload("stress", 10_000_000, 6_000, 200_000, 0.10, 2_048, 300, 50, 16.0, 20_000, 4.0,
                        1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4),
 }

@@ -286,6 +286,60 @@ def test_asynchronous_partial_results(torch_cuda):
         dec.close()
 
 
+def sample_word_sequences(g, n_seq, rng, max_len=4):
+    """Word sequences read off random walks, so that they exist in the graph."""
+    seqs = []
+    for _ in range(n_seq):
+        k = int(rng.integers(1, max_len + 1))
+        s, words = int(rng.integers(0, g.num_states)), []
+        for _ in range(400):
+            if len(words) == k or g.row_offsets[s] == g.row_offsets[s + 1]:
+                break
+            a = int(rng.integers(g.row_offsets[s], g.row_offsets[s + 1]))
+            if g.olabel[a]:
+                words.append(int(g.olabel[a]))
+            s = int(g.dst[a])
+        if words:
+            seqs.append(words)
+    return seqs
+
+
+def test_context_from_word_sequences(torch_cuda):
+    """Algorithm 1 in the library against the checker's plain version, then a decode biased with the
+    arcs it returns (unigrams, sequences, unknown words)."""
+    from oracle import arcs_for_sequences
+    torch = torch_cuda
+    g, L, _, _ = mid_inputs(torch, C=2, T=30, S=20_000, seed=19)
+    rng = np.random.default_rng(19)
+    gh = B.cbd_graph_load(g.num_states, g.num_pdfs, g.start_state, g.row_offsets, g.dst, g.ilabel, g.olabel,
+                          g.weight, g.final_cost)
+    try:
+        lists = []
+        for c in range(2):
+            seqs = sample_word_sequences(g, 25, rng) + [[int(rng.integers(1, 2000))], [999_999], []]
+            got = B.cbd_context_from_words(gh, seqs)
+            want = arcs_for_sequences(g, seqs)
+            assert np.array_equal(got, want), f"list {c}: {got.size} arcs vs {want.size}"
+            assert got.size > 25 and np.all(np.isin(g.olabel[got], np.concatenate([np.asarray(x) for x in seqs if x])))
+            lists.append(got)
+        offs = np.array([-2.0, -4.0], np.float32)   # the paper's discount factor, and a stronger one
+        dec = GH.GpuDecoder(g, 2, 12.0, 0, max_frames=30, max_context_arcs=max(len(x) for x in lists), graph_handle=gh)
+        try:
+            orcs = GH.oracle_channels(g, 2, 12.0, 0)
+            dec.set_contexts(lists, offs)
+            Lh = L.cpu().numpy()
+            for c in range(2):
+                orcs[c].set_context(lists[c], offs[c]); orcs[c].reset()
+            dec.reset(); dec.advance(L, 0, 30)
+            for c in range(2):
+                orcs[c].advance(Lh[c])
+                GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"word-sequence context ch {c}")
+        finally:
+            dec.close()
+    finally:
+        B.cbd_graph_free(gh)
+
+
 def test_channel_subset_and_reuse_after_reset(torch_cuda):
     """A subset of channels advances while the others wait; a channel reset for a second utterance
     gives the same result as a fresh decoder."""
