@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--hash-log2", type=int, default=0)
     ap.add_argument("--table-location", type=int, default=0)
     ap.add_argument("--lds-token-cap", type=int, default=0)
+    ap.add_argument("--workgroups-per-cu", type=int, default=0)
     ap.add_argument("--lookup-mode", type=int, default=-1, help="0 binary search, 1 Bloom filter + search; default: the workload's")
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
     ap.add_argument("--sync-partials", action="store_true",
@@ -119,7 +120,7 @@ def main():
         f"{w.segments} x {w.frames} frames x {w.num_pdfs} pdfs in {time.perf_counter() - t0:.1f} s")
     sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
                           biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
-                          async_partials=not args.sync_partials)
+                          async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 

@@ -118,6 +118,7 @@ struct cbd_decoder {
   int32_t lds_tok_cap = 0, lds_slots = 0, lds_log_cap = 0;  // LDS tables (0: unused)
   int32_t g_tok_cap = 0, g_slots = 0, g_log_cap = 0;        // device-memory tables
   int block = 1024;
+  int stage_rows = 1;
   uint32_t lds_bytes = 0;
   cbd::ChanState *d_chan = nullptr;
   int32_t *d_tok_state = nullptr;
@@ -185,7 +186,7 @@ AdvanceParams base_params(const cbd_decoder *d) {
   p.lookup_mode = d->cfg.lookup_mode;
   p.lds_tok_cap = d->lds_tok_cap; p.lds_slots = d->lds_slots; p.lds_log_cap = d->lds_log_cap;
   p.g_tok_cap = d->g_tok_cap; p.g_slots = d->g_slots; p.g_log_cap = d->g_log_cap;
-  p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap;
+  p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap; p.stage_rows = d->stage_rows;
   p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost;
   p.tok_first = d->d_tok_first; p.tok_eps = d->d_tok_eps; p.tok_end = d->d_tok_end;
   p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx; p.ctx_n = d->d_ctx_n; p.ctx_off = d->d_ctx_off;
@@ -513,6 +514,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->table_location < 0 || cfg->table_location > 2) return fail(CBD_E_INVALID, "decoder: table_location");
   if (cfg->lds_token_cap < 0) return fail(CBD_E_INVALID, "decoder: lds_token_cap");
   if (cfg->max_pool_contexts < 0) return fail(CBD_E_INVALID, "decoder: max_pool_contexts");
+  if (cfg->workgroups_per_cu < 0 || cfg->workgroups_per_cu > 4) return fail(CBD_E_INVALID, "decoder: workgroups_per_cu");
   cbd_decoder *d = new (std::nothrow) cbd_decoder();
   if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
   d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
@@ -541,36 +543,45 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
   DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
   {
-    cbd::LdsLayout none = cbd::make_layout(g->P, d->ctx_lds_cap, 0, 0, 0);
-    if ((int64_t)none.total > lds_limit) {
-      delete d;
-      return fail(CBD_E_INVALID, "decoder: log-likelihood row and context do not fit LDS");
-    }
-    // LDS tables: the largest token capacity (multiple of 64) that fits beside the row and the context
-    int cap = 0;
-    if (cfg->table_location != 2) {
+    // How many workgroups (channels) share a compute unit's LDS.  Two smaller workgroups can hide each
+    // other's dependent chains, but each gets half the table capacity (and the log-likelihood row moves to
+    // device memory / L2 when keeping it in LDS would leave too few tokens); with the workloads measured so
+    // far the extra frames redone in device memory cost more than the overlap gains, so the default is 1.
+    (void)n_cu;
+    int wgs = cfg->workgroups_per_cu;
+    if (wgs == 0) wgs = 1;
+    const int budget = lds_limit / wgs;
+    auto best_cap = [&](int pdfs_staged) {
+      if (cfg->table_location == 2) return 0;
       int want = cfg->lds_token_cap > 0 ? cfg->lds_token_cap : cbd::kLdsTokLimit;
       want = std::min(want, std::min<int>(d->g_tok_cap, cbd::kLdsTokLimit));
       for (int t = want / 64 * 64; t >= 64; t -= 64) {
-        cbd::LdsLayout l = cbd::make_layout(g->P, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t));
-        if ((int64_t)l.total <= lds_limit) { cap = t; break; }
+        cbd::LdsLayout l = cbd::make_layout(pdfs_staged, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t));
+        if ((int64_t)l.total <= budget) return t;
       }
-      if (cap == 0 && cfg->table_location == 1) {
-        delete d;
-        return fail(CBD_E_INVALID, "decoder: no room for token tables in LDS");
-      }
+      return 0;
+    };
+    int cap = best_cap(g->P);
+    d->stage_rows = 1;
+    const bool row_fits = (int64_t)cbd::make_layout(g->P, d->ctx_lds_cap, 0, 0, 0).total <= budget;
+    if (!row_fits || (wgs > 1 && cfg->table_location != 2 && cap < 1024 && cfg->lds_token_cap == 0)) {
+      d->stage_rows = 0;
+      cap = best_cap(0);
+    }
+    if ((int64_t)cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, 0, 0, 0).total > lds_limit) {
+      delete d;
+      return fail(CBD_E_INVALID, "decoder: context list does not fit LDS");
+    }
+    if (cap == 0 && cfg->table_location == 1) {
+      delete d;
+      return fail(CBD_E_INVALID, "decoder: no room for token tables in LDS");
     }
     d->lds_tok_cap = cap;
     d->lds_slots = cap ? cbd::lds_slots_for(cap) : 0;
     d->lds_log_cap = cap ? cbd::lds_log_for(cap) : 0;
-    d->lds_bytes = cbd::make_layout(g->P, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap).total;
-  }
-  // workgroup size: the more channels share a compute unit, the smaller the groups
-  {
-    int per_cu = (d->C + std::max(n_cu, 1) - 1) / std::max(n_cu, 1);
-    int by_lds = std::max(1, lds_limit / (int)std::max<uint32_t>(d->lds_bytes, 1));
-    int resident = std::min(per_cu, by_lds);
-    d->block = resident >= 4 ? 256 : (resident >= 2 ? 512 : 1024);
+    d->lds_bytes = cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap).total;
+    // workgroup size: the more channels share a compute unit, the smaller the groups
+    d->block = wgs >= 4 ? 256 : (wgs >= 2 ? 512 : 1024);
     const char *env = getenv("CBD_BLOCK");
     if (env) {
       int b = atoi(env);

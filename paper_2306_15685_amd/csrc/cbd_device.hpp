@@ -113,6 +113,7 @@ struct AdvanceParams {
   int32_t bp_cap;
   int32_t max_ctx;         // row length of ctx
   int32_t ctx_lds_cap;     // context entries that fit the LDS copy
+  int32_t stage_rows;      // 1: the frame's log-likelihood row is copied to LDS; 0: read from device memory
   // per channel, device memory
   int32_t *tok_state;      // [C][g_tok_cap] states of the current tokens (written on the last frame of a call)
   float *tok_cost;         // [C][g_tok_cap]
@@ -270,6 +271,15 @@ struct Ctx {
   bool in_lds;
   bool use_bitmap;
   float offset;
+};
+
+// The current frame's log-likelihood row: the LDS copy, or (when LDS is kept for more resident
+// workgroups instead) the row in device memory, which stays in L2 while the frame lasts.
+struct Rows {
+  const float *lds;
+  const float *glob;
+  bool staged;
+  __device__ __forceinline__ float at(uint32_t i) const { return staged ? lds[i] : glob[i]; }
 };
 
 __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
@@ -444,7 +454,7 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
 // each candidate at once (closure rounds, and the rare emit overflow beyond the register batch).
 template <bool kLds, bool kEmit>
 __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
-                                              const Ctx &cx, const float *Lrow, int no, const ArcList &AL, int j_begin,
+                                              const Ctx &cx, const Rows &Lrow, int no, const ArcList &AL, int j_begin,
                                               float cost, uint32_t src_tag, float m_fixed, uint32_t &n_cand, int lane) {
   for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
     int jj = j0 + lane;
@@ -459,7 +469,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       rec = p.arcs[a];
       float w = rec.weight;
       if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1: boosted weight = weight + discount
-      if (kEmit) cand = (c_own + w) - Lrow[(rec.meta & 0xFFFFu) - 1u];
+      if (kEmit) cand = (c_own + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u);
       else cand = c_own + w;
     }
     if (kEmit) {
@@ -478,7 +488,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
 // expanded in bulk and its children are left flagged in the change log for the next round.
 template <bool kLds>
 __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
-                                      const Ctx &cx, const float *Lrow, int no, uint8_t *owner_map, int first, int deg,
+                                      const Ctx &cx, const Rows &Lrow, int no, uint8_t *owner_map, int first, int deg,
                                       float cost, uint32_t slot, float m, uint32_t &n_eps, uint32_t &n_cand,
                                       int &levels, int lane) {
   typedef LogT<kLds> LogE;
@@ -537,10 +547,11 @@ __device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool star
 // Nothing that outlives the frame is written before the capacity checks have passed.
 template <bool kLds, int kBlock>
 __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, const Ctx &cx,
-                                         float *Lrow, const float *Lnext, uint32_t *hist, uint8_t *owner_maps, int f,
+                                         float *Lstage, const Rows &Lrow, const float *Lnext, uint32_t *hist,
+                                         uint8_t *owner_maps, int f,
                                          int cur, int2 *bp, int32_t *g_tok_state, bool last_frame) {
   // Lnext: the next frame's log-likelihood row in HBM (null: none).  It starts its way now, waits in
-  // registers during the frame and is parked in Lrow right before the frame's last barrier.
+  // registers during the frame and is parked in the LDS row Lstage right before the frame's last barrier.
   constexpr int kPre = kBlock >= 1024 ? 6 : 8;
   float pre[kPre];
 #pragma unroll
@@ -620,7 +631,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
             rec[r] = p.arcs[arc[r]];
             float w = rec[r].weight;
             if (ctx_contains(cx, arc[r])) w = w + cx.offset;   // Sec. 4.1
-            cand[r] = (c_own + w) - Lrow[(rec[r].meta & 0xFFFFu) - 1u];
+            cand[r] = (c_own + w) - Lrow.at((rec[r].meta & 0xFFFFu) - 1u);
             uint32_t o = f2ord(cand[r]);
             lmin = o < lmin ? o : lmin;
           }
@@ -790,9 +801,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 #pragma unroll
     for (int k = 0; k < kPre; ++k) {
       int i = tid + k * kBlock;
-      if (i < p.num_pdfs) Lrow[i] = pre[k];
+      if (i < p.num_pdfs) Lstage[i] = pre[k];
     }
-    for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lrow[i] = Lnext[i];
+    for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lstage[i] = Lnext[i];
   }
   wg_barrier<kLds>();
   return kFrameOk;
@@ -804,7 +815,8 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   const int tid = threadIdx.x;
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
-  const LdsLayout lay = make_layout(p.num_pdfs, p.ctx_lds_cap, p.lds_tok_cap, p.lds_slots, p.lds_log_cap);
+  const LdsLayout lay = make_layout(p.stage_rows ? p.num_pdfs : 0, p.ctx_lds_cap, p.lds_tok_cap, p.lds_slots,
+                                    p.lds_log_cap);
   Shared *sh = (Shared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
@@ -879,18 +891,20 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       ML.t_eps[i] = MG.t_eps[i]; ML.t_end[i] = MG.t_end[i];
     }
   }
-  if (p.n_frames > 0) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = Lbase[i];
+  if (p.n_frames > 0 && p.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = Lbase[i];
   __syncthreads();
 
   int outcome = kFrameOk;
   if (tid < 64) frame_init(sh, hist, p.do_reset != 0, tid);
   __syncthreads();
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
-    const float *Lnext = (f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
+    const float *Lnext = (p.stage_rows && f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
+    Rows rows;
+    rows.lds = Lrow; rows.glob = Lbase + (long long)(f < 0 ? 0 : f) * p.num_pdfs; rows.staged = p.stage_rows != 0;
     const bool last = f == p.n_frames - 1;
     bool slow = !fast;
     if (fast) {
-      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
       if (outcome == kFrameOverflow) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the tokens over
         const int lo = cur * p.lds_tok_cap;
@@ -905,7 +919,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         fast = false; cur = 0; slow = true;
       }
     }
-    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
     if (outcome != kFrameOk) break;
     cur ^= 1;
     if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {

@@ -45,7 +45,7 @@ class Session:
 
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
-                 context_mode: str = "upload", async_partials: bool = True):
+                 context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0):
         """context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
         segments' lists once with cbd_contexts_create and switches by id (Sec. 4.3)."""
         import torch
@@ -62,7 +62,7 @@ class Session:
             self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
             records_per_frame or DEFAULT_RECORDS_PER_FRAME, table_location, lds_token_cap,
-            w.channels * w.segments if context_mode == "pool" else 0,
+            w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu,
             hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode
         self.async_partials = async_partials   # partial results through cbd_best_paths_begin / _finish

@@ -105,14 +105,15 @@ def test_worked_example_on_gpu(torch_cuda):
 
 
 def run_batch(torch, g, L, ctxs, offs, beam, max_active, chunks, lookup_mode=0, table_location=0, hash_log2=12,
-              use_final=False, partial_check=True, swap=None, lds_token_cap=0):
+              use_final=False, partial_check=True, swap=None, lds_token_cap=0, workgroups_per_cu=0):
     """Decode all channels of L on the GPU and one by one on the checker; compare partial results
     after every chunk, final results, tables and counters.  swap = (frame, lists, offsets): replace
     all contexts before that frame (must be a chunk boundary)."""
     C, T, P = L.shape
     Lh = L.cpu().numpy()
     dec = GH.GpuDecoder(g, C, beam, max_active, max_frames=T, lookup_mode=lookup_mode, table_location=table_location,
-                        hash_log2=hash_log2, lds_token_cap=lds_token_cap, max_context_arcs=max(1, max(len(x) for x in ctxs),
+                        hash_log2=hash_log2, lds_token_cap=lds_token_cap, workgroups_per_cu=workgroups_per_cu,
+                        max_context_arcs=max(1, max(len(x) for x in ctxs),
                                                                   max((len(x) for x in swap[1]), default=1) if swap else 1))
     try:
         og = OracleGraph.from_graph(g)
@@ -143,7 +144,9 @@ def run_batch(torch, g, L, ctxs, offs, beam, max_active, chunks, lookup_mode=0, 
             s = dec.stats(c)
             assert s["emit_arcs"] == orcs[c].emit_arcs, f"ch={c} arcs expanded"
             assert s["tokens"] == orcs[c].stat(1) and s["active_tokens"] == orcs[c].stat(2)
-        return dec.stats(-1)
+        st = dec.stats(-1)
+        st["info"] = B.cbd_decoder_info(dec.dh)
+        return st
     finally:
         dec.close()
 
@@ -165,6 +168,19 @@ def test_multichannel_chunks_and_partials(torch_cuda, table_location, lds_cap):
     assert s["eps_arcs"] > 0 and s["improvements"] >= s["tokens"]
     if lds_cap:
         assert 0 < s["slow_frames"] < s["frames"]
+
+
+@pytest.mark.parametrize("wgs", [1, 2, 4])
+def test_shared_compute_units_and_unstaged_rows(torch_cuda, wgs):
+    """Several channels per compute unit: smaller workgroups, and with 6000 pdfs the log-likelihood
+    row is read from device memory instead of LDS when LDS is shared."""
+    g, L, ctxs, offs = mid_inputs(torch_cuda, C=5, T=32, P=6000, seed=20)
+    s = run_batch(torch_cuda, g, L, ctxs, offs, beam=13.0, max_active=0, chunks=[5, 27], workgroups_per_cu=wgs)
+    assert s["info"]["block_threads"] == {1: 1024, 2: 512, 4: 256}[wgs]
+    if wgs == 1:
+        assert s["info"]["lds_bytes"] > 100_000     # row staged, big tables
+    else:
+        assert s["info"]["lds_bytes"] <= 163_840 // wgs
 
 
 def test_histogram_pruning_engages(torch_cuda):
