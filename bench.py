@@ -72,7 +72,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "dynamic", "stress"])
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "dynamic", "stress", "e2e"])
     ap.add_argument("--channels", type=int, default=0, help="override the channel count (smaller trial runs)")
     ap.add_argument("--hash-log2", type=int, default=0)
     ap.add_argument("--table-location", type=int, default=0)

@@ -130,6 +130,9 @@ struct AdvanceParams {
   uint32_t *g_hidx;
 };
 
+constexpr int kBigRows = 32;      // slots for such rows per frame
+constexpr int kBigRowArcs = 512;  // a row with more arcs than this is shared out over all waves
+
 // Workgroup-shared scalars.
 struct Shared {
   uint32_t m_ord;      // running minimum of emitting candidates (orderable bits)
@@ -143,6 +146,10 @@ struct Shared {
   float best;
   uint32_t c_active, c_emit, c_eps, c_cand;
   int32_t diverged;
+  int32_t n_big;              // rows too long for one wave, expanded by the whole workgroup (emit)
+  int32_t big_first[kBigRows], big_deg[kBigRows];
+  float big_cost[kBigRows];
+  uint32_t big_src[kBigRows];
   int32_t a_maxtok, a_slow;   // counters of this call
   long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
@@ -538,7 +545,7 @@ __device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool star
   if (lane == 0) {
     sh->m_ord = start ? f2ord(0.0f) : 0xFFFFFFFFu;
     sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
-    sh->fault = 0; sh->diverged = 0;
+    sh->fault = 0; sh->diverged = 0; sh->n_big = 0;
     sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
   }
 }
@@ -586,6 +593,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     const float best = sh->best;
     const int cut = sh->cut_bin;
     const int n_batches = (n_tok + kBlock - 1) / kBlock;
+    int big_arcs = 0;
     for (int b = 0; b < n_batches; ++b) {
       // a batch holds up to kBlock tokens, shared evenly by the waves: with few tokens every
       // wave still gets some, and each lane ends up with about one arc
@@ -607,9 +615,23 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         }
         if (alive) { first = M.t_first[co + i]; deg = M.t_eps[co + i] - first; }
       }
+      if (deg > kBigRowArcs) {
+        // a hub-like row: one wave would walk it alone, so park it for the whole workgroup
+        int slot = atomicAdd(&sh->n_big, 1);
+        if (slot < kBigRows) {
+          sh->big_first[slot] = first; sh->big_deg[slot] = deg; sh->big_cost[slot] = cost; sh->big_src[slot] = (uint32_t)i;
+          big_arcs += deg;
+          deg = 0;
+        }
+      }
       unsigned long long am = __ballot(alive);
       ArcList AL = make_arc_list(first, deg, lane, owner_map);
       n_active += (uint32_t)__popcll(am); n_emit += (uint32_t)AL.total;
+      {
+        int wb = wave_incl_scan(big_arcs);
+        n_emit += (uint32_t)__builtin_amdgcn_readlane(wb, 63);
+        big_arcs = 0;
+      }
       // phase A: fetch up to kEmitSlots arcs per lane, keep the candidates in registers
       float cand[kEmitSlots];
       int arc[kEmitSlots];
@@ -656,6 +678,33 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     }
   }
   wg_barrier<kLds>();
+  if (sh->n_big > 0) {
+    // the parked long rows: every wave takes every NW-th group of 64 arcs
+    const int nbig = min(sh->n_big, kBigRows);
+    for (int r = 0; r < nbig; ++r) {
+      const int first = sh->big_first[r], deg = sh->big_deg[r];
+      const float c_own = sh->big_cost[r];
+      const uint32_t src = sh->big_src[r];
+      for (int j0 = wave * 64; j0 < deg; j0 += NW * 64) {
+        int jj = j0 + lane;
+        bool act = jj < deg;
+        int a = first + jj;
+        float cand = 0.0f;
+        ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
+        if (act) {
+          rec = p.arcs[a];
+          float w = rec.weight;
+          if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
+          cand = (c_own + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u);
+        }
+        uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
+        if (lane == 0) atomicMin(&sh->m_ord, wmin);
+        bool imp; uint32_t hh; RowInfo rr;
+        commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand, a, rec, src, 0.0f, n_cand, lane, true, imp, hh, rr);
+      }
+    }
+    wg_barrier<kLds>();
+  }
 
   // ---- step 3: the emission minimum fixes the frame's cutoff
   const float m = ord2f(sh->m_ord);

@@ -16,8 +16,13 @@ from . import synth
 
 
 def default_hash_log2(w: synth.Workload) -> int:
-    """Device-memory tables (used by the rare frames that outgrow LDS): 8192 tokens per frame."""
-    return 14
+    """Device-memory tables (used by the frames that outgrow LDS): 8192 tokens per frame; the
+    lexicon-loop workload holds a table entry per word start, so it gets 32768."""
+    return 16 if w.name.startswith("e2e") else 14
+
+
+def default_records_per_frame(w: synth.Workload) -> int:
+    return 24_576 if w.name.startswith("e2e") else DEFAULT_RECORDS_PER_FRAME
 
 
 # Back-pointer records reserved per frame and channel (the workloads here average 350-500 tokens a frame).
@@ -61,7 +66,7 @@ class Session:
         self.dh = B.cbd_decoder_create(
             self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
-            records_per_frame or DEFAULT_RECORDS_PER_FRAME, table_location, lds_token_cap,
+            records_per_frame or default_records_per_frame(w), table_location, lds_token_cap,
             w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu,
             hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode

@@ -61,6 +61,10 @@ WORKLOADS: Dict[str, Workload] = {
                         10, 1_000, -8.0, -2.0, segments=20, lookup_mode=1, config_id=3),
     "stress": Workload("stress", 10_000_000, 6_000, 200_000, 0.10, 2_048, 300, 50, 16.0, 20_000, 4.0,
                        1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4),
+    # second workload: lexicon loop over end-to-end units (dense token activity, a 20,000-arc hub row,
+    # max-active pruning engaged); contexts are word-end arcs (unigram boosting)
+    "e2e": Workload("e2e", 0, 96, 20_000, 0.0, 64, 200, 50, 10.0, 2_500, 2.0,
+                    100, 300, -2.0, -2.0, ctx_walks=False, lookup_mode=1, partial_every_chunk=True, config_id=5),
 }
 
 
@@ -150,7 +154,49 @@ def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
                  weight, final, src.astype(np.int32))
 
 
+def make_lexicon_graph(num_units: int, num_words: int, seed_stream: Tuple[int, ...] = (0,),
+                       min_len: int = 2, max_len: int = 6) -> Graph:
+    """Lexicon loop over end-to-end model units (Sec. 6: decoding with characters or subwords
+    instead of words' HMM states).
+
+    State 0 is the word-boundary hub.  Every word is a chain of `min_len..max_len` unit states
+    entered from the hub by an emitting arc on its first unit; each chain state has a self-loop
+    on its own unit (the unit lasts several frames) and an arc to the next state on the next
+    unit; the last state returns to the hub through an epsilon-input arc that carries the word
+    label.  So the hub row has `num_words` arcs, chains are dense in tokens, and the epsilon
+    arcs alone form no cycle.  Unit u is pdf u; weights are -ln U(0.05, 1).
+    """
+    rng = _rng(6, *seed_stream)
+    lens = rng.integers(min_len, max_len + 1, num_words)
+    units = [rng.integers(0, num_units, int(n)) for n in lens]
+    first_state = np.zeros(num_words, dtype=np.int64)
+    nxt = 1
+    for w in range(num_words):
+        first_state[w] = nxt
+        nxt += int(lens[w])
+    S = nxt
+    row, dst, il, ol = [0], [], [], []
+    for w in range(num_words):                      # hub row
+        dst.append(int(first_state[w])); il.append(int(units[w][0]) + 1); ol.append(0)
+    row.append(len(dst))
+    for w in range(num_words):
+        for k in range(int(lens[w])):
+            s = int(first_state[w]) + k
+            dst.append(s); il.append(int(units[w][k]) + 1); ol.append(0)          # self-loop
+            if k + 1 < lens[w]:
+                dst.append(s + 1); il.append(int(units[w][k + 1]) + 1); ol.append(0)
+            else:
+                dst.append(0); il.append(0); ol.append(w + 1)                        # word end, back to the hub
+            row.append(len(dst))
+    A = len(dst)
+    weight = (-np.log(rng.uniform(0.05, 1.0, A))).astype(np.float32)
+    return Graph(S, A, int(num_units), int(num_words), 0, np.array(row, np.int32), np.array(dst, np.int32),
+                 np.array(il, np.int32), np.array(ol, np.int32), weight, None)
+
+
 def graph_for(w: Workload, with_finals: bool = False) -> Graph:
+    if w.name.startswith("e2e"):
+        return make_lexicon_graph(w.num_pdfs, w.num_words, seed_stream=(w.config_id,))
     return make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob,
                       seed_stream=(w.config_id,), mean_degree=w.mean_degree,
                       word_frac=w.word_frac, with_finals=with_finals)

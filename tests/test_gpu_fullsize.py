@@ -90,6 +90,15 @@ def test_medium_all_channels(torch_cuda):
     check_workload(torch_cuda, w, g, og, sample=range(w.channels), prop_channels=range(w.channels))
 
 
+def test_e2e_units_lexicon_loop(torch_cuda):
+    """Second workload: 64 channels over a 20,000-word lexicon loop of end-to-end units."""
+    w = synth.WORKLOADS["e2e"]
+    g = synth.graph_for(w)
+    og = OracleGraph.from_graph(g)
+    total = check_workload(torch_cuda, w, g, og, sample=[0, 31, 63], prop_channels=range(0, w.channels, 8))
+    assert total["slow_frames"] == total["frames"]
+
+
 @pytest.mark.timeout(900)
 def test_large_online(torch_cuda, big_graph):
     g, og = big_graph

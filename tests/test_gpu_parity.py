@@ -183,6 +183,21 @@ def test_shared_compute_units_and_unstaged_rows(torch_cuda, wgs):
         assert s["info"]["lds_bytes"] <= 163_840 // wgs
 
 
+def test_lexicon_loop_units_workload(torch_cuda):
+    """Second workload (Sec. 6: end-to-end model units): a lexicon loop with a 3000-arc hub row, self-loops,
+    thousands of tokens per frame (device-memory tables on every frame), max-active pruning engaged,
+    boosted epsilon-input word-end arcs."""
+    torch = torch_cuda
+    g = synth.make_lexicon_graph(48, 3000, seed_stream=(21,))
+    L = synth.make_loglikes(3, 40, 48, 2.0, seed_stream=(21,), device="cuda")
+    w = synth.scaled(synth.WORKLOADS["e2e"], channels=3, config_id=61)
+    ctxs, offs = synth.make_contexts(w, g)
+    assert all(np.all(g.ilabel[c] == 0) for c in ctxs)     # word-end arcs are epsilon-input arcs
+    s = run_batch(torch, g, L, ctxs, offs, beam=10.0, max_active=800, chunks=[3, 17, 20], hash_log2=14, lookup_mode=1)
+    assert s["slow_frames"] == s["frames"] and s["max_tokens"] > 2500
+    assert s["active_tokens"] < 0.5 * s["tokens"]           # the histogram cut did most of the pruning
+
+
 def test_histogram_pruning_engages(torch_cuda):
     """max_active small enough that the 256-bin cut decides the survivors in most frames."""
     g, L, ctxs, offs = mid_inputs(torch_cuda, C=4, T=40, seed=12)
