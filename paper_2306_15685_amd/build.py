@@ -13,6 +13,9 @@ LIB = os.path.join(HERE, "libcbdec.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the kernels already combine a wave's updates into one atomic issued by one lane; the compiler's own
+    # wave-level combining of atomics would only wrap each of them in more code
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-result", "-pthread",
 ]
 

@@ -144,14 +144,14 @@ struct Shared {
   int32_t fault;       // capacity overflow seen
   int32_t n_tok, frame_base, n_rec, status, cut_bin, fr_begin, fr_end, rounds;
   float best;
-  uint32_t c_active, c_emit, c_eps, c_cand;
   int32_t diverged;
+  int32_t halt;               // fault or diverged, latched by one thread between two barriers
   int32_t n_big;              // rows too long for one wave, expanded by the whole workgroup (emit)
   int32_t big_first[kBigRows], big_deg[kBigRows];
   float big_cost[kBigRows];
   uint32_t big_src[kBigRows];
   int32_t a_maxtok, a_slow;   // counters of this call
-  long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
+  unsigned long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
 
 __device__ __forceinline__ int sh_log_n(const Shared *sh) { return (int)(uint32_t)sh->log_claim; }
@@ -442,7 +442,8 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
   if (pmask == 0) return;
   n_cand += (uint32_t)__popcll(pmask);
   uint32_t co = pass ? f2ord(cand) : 0xFFFFFFFFu;
-  if (!kEmit) {
+  if (!kEmit && __ballot(co < f2ord(m_fixed)) != 0) {
+    // the frame's minimum is min(m, closure candidates): only a candidate below m can move it
     uint32_t wmin = wave_min_u32(co);
     if (lane == 0) atomicMin(&sh->best_ord, wmin);
   }
@@ -450,7 +451,7 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
   uint32_t src = src_tag;
   if (pass && !fault) {
     row = row_of(p, rec);
-    if (flag_children && row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;
+    if (flag_children && row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;   // flag_children may differ per lane
     uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
     improved = table_min<kLds>(M, sh, (uint32_t)rec.dst, key, h, claimed);
   }
@@ -488,34 +489,91 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
   }
 }
 
-// Epsilon closure from this wave's pending states: lane i holds a state whose value changed
-// (its epsilon row [first, first+deg), its cost, its table slot).  While a level has at most 64
-// arcs, each lane takes one arc and, if it lowered a state that has epsilon arcs of its own,
-// keeps that state for the next level: no barrier, no change-log round trip.  A bigger level is
-// expanded in bulk and its children are left flagged in the change log for the next round.
+// A state whose value a lane has just lowered and whose epsilon-input arcs it will expand itself:
+// the row [first, first+deg), the value, the state's table slot, and the row's first arc record,
+// fetched ahead of need.
+struct Pending {
+  int first, deg;
+  float cost;
+  uint32_t slot;
+  ArcRec nxt;
+  bool have_nxt;
+  // a second state waiting behind the first (taken up when the lane's current chain ends)
+  int first2, deg2;
+  float cost2;
+  uint32_t slot2;
+};
+
+__device__ __forceinline__ void pending_clear(Pending &pd) {
+  pd.first = 0; pd.deg = 0; pd.cost = 0.0f; pd.slot = 0; pd.have_nxt = false;
+  pd.nxt.dst = 0; pd.nxt.weight = 0.0f; pd.nxt.row = 0; pd.nxt.meta = 0;
+  pd.first2 = 0; pd.deg2 = 0; pd.cost2 = 0.0f; pd.slot2 = 0;
+}
+
+// Epsilon closure from this wave's pending states.  While every pending row has one arc (the
+// usual case) each lane expands its own arc: no scan, no cross-lane traffic, and the record
+// of the next level's arc is requested before the table update that decides whether it is
+// needed.  Rows with several arcs go through the wave's arc list, one lane per arc; a level of
+// more than 64 arcs is expanded in bulk and its children are left flagged in the change log
+// for the next round.  No barrier anywhere: a wave follows the chains it starts.
 template <bool kLds>
 __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
-                                      const Ctx &cx, const Rows &Lrow, int no, uint8_t *owner_map, int first, int deg,
-                                      float cost, uint32_t slot, float m, uint32_t &n_eps, uint32_t &n_cand,
-                                      int &levels, int lane) {
+                                      const Ctx &cx, const Rows &Lrow, int no, uint8_t *owner_map, Pending &pd, float m,
+                                      uint32_t &n_eps, uint32_t &n_cand, int &levels, int lane) {
   typedef LogT<kLds> LogE;
   while (true) {
-    ArcList AL = make_arc_list(first, deg, lane, owner_map);
-    if (AL.total == 0) return;
-    n_eps += (uint32_t)AL.total;
+    if (pd.deg == 0 && pd.deg2 > 0) {
+      pd.first = pd.first2; pd.deg = pd.deg2; pd.cost = pd.cost2; pd.slot = pd.slot2; pd.have_nxt = false;
+      pd.deg2 = 0;
+    }
+    unsigned long long pend = __ballot(pd.deg > 0);
+    if (pend == 0) return;
     if (++levels > p.max_eps_iters) {
       if (lane == 0) sh->diverged = 1;
+      pd.deg = 0;
       return;
     }
-    uint32_t tag = slot | LogE::kSrcEps;
+    if (__ballot(pd.deg > 1) == 0) {
+      // every pending row is a single arc: each lane takes its own
+      n_eps += (uint32_t)__popcll(pend);
+      const bool act = pd.deg > 0;
+      const int a = pd.first;
+      ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
+      float cand = 0.0f;
+      Pending nx; pending_clear(nx);
+      if (act) {
+        if (!pd.have_nxt) pd.nxt = p.arcs[a];
+        rec = pd.nxt;
+        float w = rec.weight;
+        if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
+        cand = pd.cost + w;
+        if (!(cand - m > p.beam)) {
+          RowInfo ahead = row_of(p, rec);
+          if (ahead.end > ahead.eps) { nx.nxt = p.arcs[ahead.eps]; nx.have_nxt = true; }   // ahead of need
+        }
+      }
+      bool improved; uint32_t h; RowInfo row;
+      commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, pd.slot | LogE::kSrcEps, m, n_cand, lane, false,
+                          improved, h, row);
+      const bool go = improved && row.end > row.eps;
+      nx.first = go ? row.eps : 0; nx.deg = go ? row.end - row.eps : 0; nx.cost = cand; nx.slot = h;
+      nx.have_nxt = nx.have_nxt && go;
+      nx.first2 = pd.first2; nx.deg2 = pd.deg2; nx.cost2 = pd.cost2; nx.slot2 = pd.slot2;
+      pd = nx;
+      continue;
+    }
+    ArcList AL = make_arc_list(pd.first, pd.deg, lane, owner_map);
+    n_eps += (uint32_t)AL.total;
+    const uint32_t tag = pd.slot | LogE::kSrcEps;
     if (AL.total > 64) {
-      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, cost, tag, m, n_cand, lane);
-      return;
+      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, pd.cost, tag, m, n_cand, lane);
+      pd.deg = 0;
+      continue;   // lanes with a second state still have it to do
     }
     bool act = lane < AL.total;
     int owner = arc_owner(AL, lane, 0);
     int a = __shfl(AL.rel, owner, 64) + lane;
-    float c_own = __shfl(cost, owner, 64);
+    float c_own = __shfl(pd.cost, owner, 64);
     uint32_t s_own = (uint32_t)__shfl((int)tag, owner, 64);
     float cand = 0.0f;
     ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
@@ -528,10 +586,11 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     bool improved; uint32_t h; RowInfo row;
     commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, s_own, m, n_cand, lane, false, improved, h, row);
     bool go = improved && row.end > row.eps;
-    first = go ? row.eps : 0;
-    deg = go ? row.end - row.eps : 0;
-    cost = cand;
-    slot = h;
+    pd.first = go ? row.eps : 0;
+    pd.deg = go ? row.end - row.eps : 0;
+    pd.cost = cand;
+    pd.slot = h;
+    pd.have_nxt = false;
   }
 }
 
@@ -544,9 +603,9 @@ __device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool star
   for (int k = 0; k < 4; ++k) hist[lane * 4 + k] = 0;
   if (lane == 0) {
     sh->m_ord = start ? f2ord(0.0f) : 0xFFFFFFFFu;
+    sh->best_ord = 0xFFFFFFFFu;   // minimum over closure candidates; the table's minimum is min(m, this)
     sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
-    sh->fault = 0; sh->diverged = 0; sh->n_big = 0;
-    sh->c_active = sh->c_emit = sh->c_eps = sh->c_cand = 0;
+    sh->fault = 0; sh->diverged = 0; sh->halt = 0; sh->n_big = 0;
   }
 }
 
@@ -575,6 +634,8 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   uint8_t *owner_map = owner_maps + wave * kOwnerMap;
 
   uint32_t n_active = 0, n_emit = 0, n_eps = 0, n_cand = 0;   // this wave's share of the frame's counters
+  Pending pd; pending_clear(pd);   // the state this lane will start the closure from
+  uint32_t pd_arc = 0, pd_arc2 = 0;   // the arcs that produced them: a state's value names its arc
   if (f < 0) {
     // reset: one start token at cost 0
     if (wave == 0) {
@@ -667,9 +728,22 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       for (int r = 0; r < kEmitSlots; ++r) {
         if (r * 64 < AL.total) {
           bool act = r * 64 + lane < AL.total;
+          // a lane that lowers a state with epsilon-input arcs keeps it for the closure (the first of them;
+          // any further ones are flagged in the change log) and asks for the row's first arc right away
           bool imp; uint32_t hh; RowInfo rr;
+          const bool flag = pd.deg2 > 0;
           commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane,
-                             true, imp, hh, rr);
+                             flag, imp, hh, rr);
+          if (imp && !flag && rr.end > rr.eps) {
+            if (pd.deg == 0) {
+              pd.first = rr.eps; pd.deg = rr.end - rr.eps; pd.cost = cand[r]; pd.slot = hh;
+              pd.nxt = p.arcs[rr.eps]; pd.have_nxt = true;
+              pd_arc = (uint32_t)arc[r];
+            } else {
+              pd.first2 = rr.eps; pd.deg2 = rr.end - rr.eps; pd.cost2 = cand[r]; pd.slot2 = hh;
+              pd_arc2 = (uint32_t)arc[r];
+            }
+          }
         }
       }
       if (AL.total > kEmitSlots * 64)
@@ -708,50 +782,65 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 
   // ---- step 3: the emission minimum fixes the frame's cutoff
   const float m = ord2f(sh->m_ord);
-  if (tid == 0) { sh->best_ord = sh->m_ord; sh->fr_begin = 0; sh->fr_end = sh_log_n(sh); }
-  wg_barrier<kLds>();
-  if (sh->fault) return kFrameOverflow;
-  if (sh_n_claim(sh) == 0) return kFrameNoTokens;
+  // (no test of sh->fault here: waves already in the closure may set it while others have not read it yet;
+  // after an overflow the updates below do nothing, and the flag is read once every writer has passed a barrier)
+  if (sh_n_claim(sh) == 0) return kFrameNoTokens;   // stable: nothing can be added to an empty table
 
-  // ---- step 4: epsilon closure; round r reads the entries logged in round r-1 and counts the
-  // entries it logs for round r+1 in the other counter
+  // ---- step 4: epsilon closure.  First every lane follows the state it kept from the emit phase,
+  // provided that is still the state's value and survived the cutoff ...
   int levels = 0;   // passes this wave has made (bounds the closure depth)
-  for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
-    const int fb = sh->fr_begin, fe = sh->fr_end;
-    int32_t *front = &sh->n_front[(r + 1) & 1];
-    for (int base = fb; base < fe; base += kBlock) {
-      // the round's entries are shared evenly by the waves
-      const int nb = min(kBlock, fe - base);
-      const int tpw = (nb + NW - 1) / NW;
-      int j = lane < tpw ? base + wave * tpw + lane : fe;
-      if (j >= base + nb) j = fe;
-      float cost = 0.0f;
-      int first = 0, deg = 0;
-      uint32_t slot = 0;
-      if (j < fe) {
-        LogE e = M.log[j];
-        if (e.src & LogE::kSrcHasEps) {
-          uint64_t curv = ldv<kLds>(&M.hval[e.h]);
-          cost = ord2f((uint32_t)(curv >> 32));
-          // still this state's value, and not dropped by the emission cutoff
-          if ((uint32_t)curv == e.arc && curv != kEmptyVal && !(cost - m > p.beam)) {
-            uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
-            first = M.t_eps[no + idx];
-            deg = M.t_end[no + idx] - first;
-            slot = e.h;
+  if (pd.deg > 0) {
+    uint64_t curv = ldv<kLds>(&M.hval[pd.slot]);
+    if ((uint32_t)curv != pd_arc || pd.cost - m > p.beam) pd.deg = 0;
+  }
+  if (pd.deg2 > 0) {
+    uint64_t curv = ldv<kLds>(&M.hval[pd.slot2]);
+    if ((uint32_t)curv != pd_arc2 || pd.cost2 - m > p.beam) pd.deg2 = 0;
+  }
+  chase<kLds>(p, M, sh, &sh->n_front[0], cx, Lrow, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
+  wg_barrier<kLds>();
+  // ... then, rarely, rounds over the change log for what was left flagged there: round r reads the
+  // entries logged before it and counts the entries it flags for round r+1 in the other counter
+  if (sh->n_front[0] > 0 && !sh->diverged && !sh->fault) {
+    if (tid == 0) { sh->fr_begin = 0; sh->fr_end = sh_log_n(sh); }
+    wg_barrier<kLds>();
+    for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
+      const int fb = sh->fr_begin, fe = sh->fr_end;
+      int32_t *front = &sh->n_front[(r + 1) & 1];
+      for (int base = fb; base < fe; base += kBlock) {
+        // the round's entries are shared evenly by the waves
+        const int nb = min(kBlock, fe - base);
+        const int tpw = (nb + NW - 1) / NW;
+        int j = lane < tpw ? base + wave * tpw + lane : fe;
+        if (j >= base + nb) j = fe;
+        pending_clear(pd);
+        if (j < fe) {
+          LogE e = M.log[j];
+          if (e.src & LogE::kSrcHasEps) {
+            uint64_t curv = ldv<kLds>(&M.hval[e.h]);
+            float cost = ord2f((uint32_t)(curv >> 32));
+            // still this state's value, and not dropped by the emission cutoff
+            if ((uint32_t)curv == e.arc && curv != kEmptyVal && !(cost - m > p.beam)) {
+              uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
+              pd.first = M.t_eps[no + idx];
+              pd.deg = M.t_end[no + idx] - pd.first;
+              pd.cost = cost;
+              pd.slot = e.h;
+            }
           }
         }
+        chase<kLds>(p, M, sh, front, cx, Lrow, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
       }
-      chase<kLds>(p, M, sh, front, cx, Lrow, no, owner_map, first, deg, cost, slot, m, n_eps, n_cand, levels, lane);
+      wg_barrier<kLds>();
+      if (tid == 0) {
+        sh->fr_begin = fe; sh->fr_end = sh_log_n(sh);
+        sh->n_front[r & 1] = 0;
+        if (*front > 0 && r + 1 >= p.max_eps_iters) sh->diverged = 1;
+        sh->halt = sh->diverged | sh->fault;   // latched between barriers, so every wave takes the same branch
+      }
+      wg_barrier<kLds>();
+      if (sh->halt) break;
     }
-    wg_barrier<kLds>();
-    if (tid == 0) {
-      sh->fr_begin = fe; sh->fr_end = sh_log_n(sh);
-      sh->n_front[r & 1] = 0;
-      if (*front > 0 && r + 1 >= p.max_eps_iters) sh->diverged = 1;
-    }
-    wg_barrier<kLds>();
-    if (sh->diverged || sh->fault) break;
   }
   if (sh->fault) return kFrameOverflow;
   if (sh->diverged) return kFrameDiverged;
@@ -759,7 +848,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 
   // ---- step 5 and bookkeeping: every state's winning update writes the token
   {
-    const float best = ord2f(sh->best_ord);
+    const float best = ord2f(umin32(sh->m_ord, sh->best_ord));
     const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh_log_n(sh);
     int w_surv = 0, w_live = 0;   // per wave, counted with ballots (same-address LDS atomics from many lanes crawl)
     for (int j0 = wave * 64; j0 < log_n; j0 += kBlock) {
@@ -802,10 +891,11 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     if (lane == 0) {
       if (w_surv) atomicAdd(&sh->n_surv, w_surv);
       if (w_live) atomicAdd(&sh->n_live, w_live);
-      if (n_active) atomicAdd(&sh->c_active, n_active);
-      if (n_emit) atomicAdd(&sh->c_emit, n_emit);
-      if (n_eps) atomicAdd(&sh->c_eps, n_eps);
-      if (n_cand) atomicAdd(&sh->c_cand, n_cand);
+      // (no failure return lies behind this point, so a frame is counted once)
+      if (n_active) atomicAdd(&sh->a_active, (unsigned long long)n_active);
+      if (n_emit) atomicAdd(&sh->a_emit, (unsigned long long)n_emit);
+      if (n_eps) atomicAdd(&sh->a_eps, (unsigned long long)n_eps);
+      if (n_cand) atomicAdd(&sh->a_cand, (unsigned long long)n_cand);
       if (levels) atomicMax(&sh->rounds, levels);
     }
   }
@@ -834,15 +924,15 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       sh->n_tok = sh_n_claim(sh);
       sh->frame_base = sh->n_rec;
       sh->n_rec += sh_n_claim(sh);
-      sh->best = ord2f(sh->best_ord);
+      sh->best = ord2f(umin32(sh->m_ord, sh->best_ord));
       if (f >= 0) {  // the table made at reset is not a decoded frame
-        sh->a_frames++;
-        sh->a_tokens += sh->n_live;
-        if (sh->n_live > sh->a_maxtok) sh->a_maxtok = sh->n_live;
-        if (!kLds) sh->a_slow++;
+        atomicAdd(&sh->a_frames, 1ull);
+        atomicAdd(&sh->a_tokens, (unsigned long long)sh->n_live);
+        atomicMax(&sh->a_maxtok, sh->n_live);
+        if (!kLds) atomicAdd(&sh->a_slow, 1);
       }
-      sh->a_active += sh->c_active; sh->a_emit += sh->c_emit; sh->a_eps += sh->c_eps; sh->a_cand += sh->c_cand;
-      sh->a_impr += sh_log_n(sh); sh->a_rounds += sh->rounds;
+      atomicAdd(&sh->a_impr, (unsigned long long)sh_log_n(sh));
+      atomicAdd(&sh->a_rounds, (unsigned long long)sh->rounds);
     }
     frame_init(sh, hist, false, lane);   // for the next frame
   }
