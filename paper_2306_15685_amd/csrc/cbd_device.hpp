@@ -328,6 +328,11 @@ __device__ __forceinline__ RowInfo row_of(const AdvanceParams &p, const ArcRec &
   return r;
 }
 
+// The overflow flag as some wave last wrote it (a hint: the decision is taken after a barrier).
+__device__ __forceinline__ int load_fault(const Shared *sh) {
+  return __hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 // Recombination: E[state] = min key.  Returns true if this call lowered the
 // state's value (old > key); h receives the slot, claimed tells whether this
 // lane created the state's entry.
@@ -335,21 +340,27 @@ template <bool kLds>
 __device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, uint32_t state, uint64_t key, uint32_t &h_out,
                                           bool &claimed) {
   uint32_t h = __umulhi(state * 2654435761u, M.slots);
-  claimed = false;
-  for (uint32_t probe = 0; probe < M.slots; ++probe) {
-    // most candidates open a new state: try to take the slot straight away
-    uint32_t k = atomicCAS(&M.hkey[h], kEmptyKey, state);
-    if (k == kEmptyKey || k == state) {
-      uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
-      claimed = k == kEmptyKey;
-      h_out = h;
-      return old > key;
+  // most candidates open a new state or find theirs at the home slot: try to take it straight away,
+  // and walk on only after a collision
+  uint32_t k = atomicCAS(&M.hkey[h], kEmptyKey, state);
+  if (__builtin_expect(k != kEmptyKey && k != state, 0)) {
+    uint32_t probe = 1;
+    do {
+      h = h + 1 == M.slots ? 0 : h + 1;
+      k = atomicCAS(&M.hkey[h], kEmptyKey, state);
+      // (a long walk means a nearly full table: stop as soon as anybody has declared the overflow)
+    } while (k != kEmptyKey && k != state && ++probe < M.slots && !((probe & 63u) == 0 && load_fault(sh)));
+    if (k != kEmptyKey && k != state) {   // every slot holds another state, or the frame is being given up
+      sh->fault = 1;
+      claimed = false;
+      h_out = 0;
+      return false;
     }
-    h = h + 1 == M.slots ? 0 : h + 1;
   }
-  sh->fault = 1;
-  h_out = 0;
-  return false;
+  uint64_t old = atomicMin((unsigned long long *)&M.hval[h], (unsigned long long)key);
+  claimed = k == kEmptyKey;
+  h_out = h;
+  return old > key;
 }
 
 // Book the updates of this wave's lanes: one atomic on the packed counter yields the
@@ -429,11 +440,11 @@ __device__ __forceinline__ int arc_owner(const ArcList &L, int jj, int j0) {
 template <bool kLds, bool kEmit>
 __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front, int no,
                                        bool act, float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed,
-                                       uint32_t &n_cand, int lane, bool flag_children, bool &improved, uint32_t &h,
-                                       RowInfo &row) {
+                                       uint32_t &n_cand, int lane, bool flag_children, int fault, bool &improved,
+                                       uint32_t &h, RowInfo &row) {
+  // fault: a recent reading of the overflow flag (see load_fault); once set, the tables are left alone
   improved = false; h = 0; row.first = row.eps = row.end = 0;
   bool pass = false;
-  const int fault = __hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   if (act) {
     float mref = kEmit ? ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) : m_fixed;
     pass = !(cand - mref > p.beam);
@@ -467,6 +478,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
   for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
     int jj = j0 + lane;
     bool act = jj < AL.total;
+    const int fault = load_fault(sh);
     int owner = arc_owner(AL, jj, j0);
     int a = __shfl(AL.rel, owner, 64) + jj;
     float c_own = __shfl(cost, owner, 64);
@@ -485,7 +497,7 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       if (lane == 0) atomicMin(&sh->m_ord, wmin);
     }
     bool imp; uint32_t hh; RowInfo rr;
-    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane, true, imp, hh, rr);
+    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane, true, fault, imp, hh, rr);
   }
 }
 
@@ -528,6 +540,7 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     }
     unsigned long long pend = __ballot(pd.deg > 0);
     if (pend == 0) return;
+    const int fault = load_fault(sh);   // asked for here, back by the time the arcs have arrived
     if (++levels > p.max_eps_iters) {
       if (lane == 0) sh->diverged = 1;
       pd.deg = 0;
@@ -554,7 +567,7 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
       }
       bool improved; uint32_t h; RowInfo row;
       commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, pd.slot | LogE::kSrcEps, m, n_cand, lane, false,
-                          improved, h, row);
+                          fault, improved, h, row);
       const bool go = improved && row.end > row.eps;
       nx.first = go ? row.eps : 0; nx.deg = go ? row.end - row.eps : 0; nx.cost = cand; nx.slot = h;
       nx.have_nxt = nx.have_nxt && go;
@@ -584,7 +597,7 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
       cand = c_own + w;
     }
     bool improved; uint32_t h; RowInfo row;
-    commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, s_own, m, n_cand, lane, false, improved, h, row);
+    commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, s_own, m, n_cand, lane, false, fault, improved, h, row);
     bool go = improved && row.end > row.eps;
     pd.first = go ? row.eps : 0;
     pd.deg = go ? row.end - row.eps : 0;
@@ -688,7 +701,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       unsigned long long am = __ballot(alive);
       ArcList AL = make_arc_list(first, deg, lane, owner_map);
       n_active += (uint32_t)__popcll(am); n_emit += (uint32_t)AL.total;
-      {
+      if (__ballot(big_arcs > 0) != 0) {
         int wb = wave_incl_scan(big_arcs);
         n_emit += (uint32_t)__builtin_amdgcn_readlane(wb, 63);
         big_arcs = 0;
@@ -724,6 +737,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
       wg_barrier<kLds>();   // the batch minimum is known: few doomed candidates reach the table
       // phase B: cutoff, recombination
+      const int fault = load_fault(sh);
 #pragma unroll
       for (int r = 0; r < kEmitSlots; ++r) {
         if (r * 64 < AL.total) {
@@ -733,7 +747,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
           bool imp; uint32_t hh; RowInfo rr;
           const bool flag = pd.deg2 > 0;
           commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane,
-                             flag, imp, hh, rr);
+                             flag, fault, imp, hh, rr);
           if (imp && !flag && rr.end > rr.eps) {
             if (pd.deg == 0) {
               pd.first = rr.eps; pd.deg = rr.end - rr.eps; pd.cost = cand[r]; pd.slot = hh;
@@ -774,7 +788,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
         if (lane == 0) atomicMin(&sh->m_ord, wmin);
         bool imp; uint32_t hh; RowInfo rr;
-        commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand, a, rec, src, 0.0f, n_cand, lane, true, imp, hh, rr);
+        commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand, a, rec, src, 0.0f, n_cand, lane, true, load_fault(sh), imp, hh, rr);
       }
     }
     wg_barrier<kLds>();
