@@ -257,7 +257,8 @@ template <bool kLds, typename T> __device__ __forceinline__ void stv(T *p, T v) 
 }
 
 // Sec. 4.2: the listed arc indices are kept sorted and searched per expanded arc.
-__device__ __forceinline__ bool sorted_contains(const int32_t *list, int n, int32_t a) {
+template <typename ListPtr>
+__device__ __forceinline__ bool sorted_contains(ListPtr list, int n, int32_t a) {
   int lo = 0, hi = n;
   while (lo < hi) {
     int mid = (lo + hi) >> 1;
@@ -270,8 +271,12 @@ constexpr int kBloomWords = 512;  // 16K bits, two hash functions
 __device__ __forceinline__ uint32_t bloom_bit0(int32_t a) { return ((uint32_t)a * 2654435761u) >> 18; }
 __device__ __forceinline__ uint32_t bloom_bit1(int32_t a) { return ((uint32_t)a * 2246822519u + 0x9E3779B9u) >> 18; }
 
+// LDS-typed pointers: reads through them are plain LDS reads, not generic loads
+typedef const __attribute__((address_space(3))) float *lds_cfloat_ptr;
+typedef const __attribute__((address_space(3))) int32_t *lds_cint_ptr;
+
 struct Ctx {
-  const int32_t *lds_list;
+  lds_cint_ptr lds_list;
   const int32_t *g_list;
   const uint32_t *bitmap;
   int n;
@@ -283,10 +288,13 @@ struct Ctx {
 // The current frame's log-likelihood row: the LDS copy, or (when LDS is kept for more resident
 // workgroups instead) the row in device memory, which stays in L2 while the frame lasts.
 struct Rows {
-  const float *lds;
+  lds_cfloat_ptr lds;   // typed as LDS so that the staged case is a plain LDS read, not a generic load
   const float *glob;
   bool staged;
-  __device__ __forceinline__ float at(uint32_t i) const { return staged ? lds[i] : glob[i]; }
+  __device__ __forceinline__ float at(uint32_t i) const {
+    if (staged) return lds[i];
+    return glob[i];
+  }
 };
 
 __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
@@ -864,6 +872,8 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   {
     const float best = ord2f(umin32(sh->m_ord, sh->best_ord));
     const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh_log_n(sh);
+    // the histogram only matters when more tokens than max_active can survive; the table holds at least as many
+    const bool hist_need = hist_on && sh_n_claim(sh) > p.max_active;
     int w_surv = 0, w_live = 0;   // per wave, counted with ballots (same-address LDS atomics from many lanes crawl)
     for (int j0 = wave * 64; j0 < log_n; j0 += kBlock) {
       const int j = j0 + lane;
@@ -889,7 +899,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
           float r = cost - best;
           if (!(r > p.beam)) {
             surv = true;
-            if (hist_on) {
+            if (hist_need) {
               int bin = (int)floorf(r * inv);
               bin = bin > 255 ? 255 : bin;
               atomicAdd(&hist[bin], 1u);
@@ -1021,7 +1031,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   const int cslot = cs->ctx_slot;
   cx.n = p.ctx_n[cslot]; cx.offset = p.ctx_off[cslot];
   cx.g_list = p.ctx + (size_t)cslot * p.max_ctx;
-  cx.lds_list = ctx_lds; cx.bitmap = bitmap;
+  cx.lds_list = (lds_cint_ptr)ctx_lds; cx.bitmap = bitmap;
   cx.in_lds = cx.n <= p.ctx_lds_cap;
   cx.use_bitmap = p.lookup_mode == 1;
   if (cx.in_lds) for (int i = tid; i < cx.n; i += kBlock) ctx_lds[i] = cx.g_list[i];
@@ -1053,7 +1063,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
     const float *Lnext = (p.stage_rows && f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
     Rows rows;
-    rows.lds = Lrow; rows.glob = Lbase + (long long)(f < 0 ? 0 : f) * p.num_pdfs; rows.staged = p.stage_rows != 0;
+    rows.lds = (lds_cfloat_ptr)Lrow; rows.glob = Lbase + (long long)(f < 0 ? 0 : f) * p.num_pdfs; rows.staged = p.stage_rows != 0;
     const bool last = f == p.n_frames - 1;
     bool slow = !fast;
     if (fast) {
