@@ -123,7 +123,7 @@ struct cbd_decoder {
   cbd::ChanState *d_chan = nullptr;
   int32_t *d_tok_state = nullptr;
   float *d_tok_cost = nullptr;
-  int32_t *d_tok_first = nullptr, *d_tok_eps = nullptr, *d_tok_end = nullptr;
+  int4 *d_tok_row = nullptr;
   int2 *d_bp = nullptr;
   cbd::LogT<false> *d_log = nullptr;
   int32_t *d_ctx = nullptr;      // [C + pool][max_ctx]
@@ -188,7 +188,7 @@ AdvanceParams base_params(const cbd_decoder *d) {
   p.g_tok_cap = d->g_tok_cap; p.g_slots = d->g_slots; p.g_log_cap = d->g_log_cap;
   p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap; p.stage_rows = d->stage_rows;
   p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost;
-  p.tok_first = d->d_tok_first; p.tok_eps = d->d_tok_eps; p.tok_end = d->d_tok_end;
+  p.tok_row = d->d_tok_row;
   p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx; p.ctx_n = d->d_ctx_n; p.ctx_off = d->d_ctx_off;
   p.g_hkey = d->d_hkey; p.g_hval = d->d_hval; p.g_hidx = d->d_hidx;
   return p;
@@ -594,9 +594,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   DCHK(dmalloc(&d->d_chan, C, &d->bytes));
   DCHK(dmalloc(&d->d_tok_state, C * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_tok_cost, C * d->g_tok_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_tok_first, C * 2 * d->g_tok_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_tok_eps, C * 2 * d->g_tok_cap, &d->bytes));
-  DCHK(dmalloc(&d->d_tok_end, C * 2 * d->g_tok_cap, &d->bytes));
+  DCHK(dmalloc(&d->d_tok_row, C * 2 * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_bp, C * (size_t)d->bp_cap, &d->bytes));
   DCHK(dmalloc(&d->d_log, C * (size_t)d->g_log_cap, &d->bytes));
   d->pool = cfg->max_pool_contexts;
@@ -630,7 +628,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
 int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
-  void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_first, d->d_tok_eps, d->d_tok_end, d->d_bp,
+  void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);

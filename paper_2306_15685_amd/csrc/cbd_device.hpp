@@ -82,7 +82,7 @@ struct __attribute__((aligned(128))) ChanState {
   float best;           // minimum cost of the current table
   int32_t cut_bin;      // histogram cut for the next prune; 255 = none
   int32_t ctx_slot;     // which stored context the channel decodes with
-  int32_t pad0;
+  int32_t row_buf;      // which of the two row buffers (tok_row) belongs to the current token list
   long long frames, active_tokens, emit_arcs, eps_arcs, candidates, improvements, tokens, eps_rounds;
   int32_t max_tokens;
   int32_t slow_frames;  // frames decoded with the device-memory tables
@@ -117,9 +117,7 @@ struct AdvanceParams {
   // per channel, device memory
   int32_t *tok_state;      // [C][g_tok_cap] states of the current tokens (written on the last frame of a call)
   float *tok_cost;         // [C][g_tok_cap]
-  int32_t *tok_first;      // [C][2][g_tok_cap] first emitting arc / first epsilon arc / end of row, two buffers
-  int32_t *tok_eps;
-  int32_t *tok_end;
+  int4 *tok_row;           // [C][2][g_tok_cap] per token: first emitting arc, first epsilon arc, end of row (two buffers)
   int2 *bp;                // [C][bp_cap] (arc, predecessor record or -1)
   LogT<false> *g_log;      // [C][g_log_cap]
   const int32_t *ctx;      // [C + pool][max_ctx] stored contexts: sorted, library arc order
@@ -158,7 +156,7 @@ __device__ __forceinline__ int sh_log_n(const Shared *sh) { return (int)(uint32_
 __device__ __forceinline__ int sh_n_claim(const Shared *sh) { return (int)(uint32_t)(sh->log_claim >> 32); }
 
 struct LdsLayout {
-  uint32_t sh, hist, bitmap, owner, ctx, L, hval, hkey, hidx, tfirst, teps, tend, tcost, log, total;
+  uint32_t sh, hist, bitmap, owner, ctx, L, hval, hkey, hidx, tcost, log, total;
 };
 
 __host__ __device__ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
@@ -175,16 +173,14 @@ __host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, 
   l.hval = o; o += (uint32_t)slots * 8;
   l.hkey = o; o += (uint32_t)slots * 4;
   l.hidx = o; o += align_up((uint32_t)slots * 2, 16);
-  l.tfirst = o; o += align_up((uint32_t)tok_cap * 8, 16);  // two buffers each
-  l.teps = o; o += align_up((uint32_t)tok_cap * 8, 16);
-  l.tend = o; o += align_up((uint32_t)tok_cap * 8, 16);
   l.tcost = o; o += align_up((uint32_t)tok_cap * 4, 16);
   l.log = o; o += align_up((uint32_t)log_cap * 8, 16);
   l.total = o;
   return l;
 }
 
-// LDS per token of capacity: 1.5 slots x 14 B + 28 B of token arrays + 1.5 log entries x 8 B = 61 B.
+// LDS per token of capacity: 1.5 slots x 14 B + 4 B of cost + 1.5 log entries x 8 B = 37 B.  (The tokens' arc
+// rows, written once and read once a frame later, live in device memory: they stream, they are not looked up.)
 __host__ __device__ inline int lds_slots_for(int tok_cap) { return tok_cap + tok_cap / 2; }
 __host__ __device__ inline int lds_log_for(int tok_cap) { return tok_cap + tok_cap / 2; }
 
@@ -314,11 +310,11 @@ template <bool kLds> struct Mem {
   uint64_t *hval;
   uint32_t *hkey;
   idx_t *hidx;
-  int32_t *t_first, *t_eps, *t_end;   // two buffers each: buffer b starts at b * tok_cap
+  int4 *t_row;   // device memory, two buffers: buffer b starts at b * row_cap
   float *t_cost;
   LogT<kLds> *log;
   uint32_t slots;
-  int tok_cap, log_cap;
+  int tok_cap, log_cap, row_cap;
 };
 
 struct RowInfo { int first, eps, end; };
@@ -373,7 +369,7 @@ __device__ __forceinline__ bool table_min(const Mem<kLds> &M, Shared *sh, uint32
 
 // Book the updates of this wave's lanes: one atomic on the packed counter yields the
 // change-log positions and, for lanes that created a state, the token indices; those
-// lanes file the state's row under their index (no = offset of the token buffer being built).
+// lanes file the state's row under their index (no = offset of the row buffer being built).
 template <bool kLds>
 __device__ __forceinline__ void record(const Mem<kLds> &M, Shared *sh, int32_t *front, int no, bool improved,
                                        bool claimed, uint32_t arc, uint32_t h, uint32_t src, const RowInfo &row,
@@ -396,7 +392,7 @@ __device__ __forceinline__ void record(const Mem<kLds> &M, Shared *sh, int32_t *
   if (claimed) {
     int idx = base_tok + __popcll(cmask & below);
     if (idx < M.tok_cap) {
-      M.t_first[no + idx] = row.first; M.t_eps[no + idx] = row.eps; M.t_end[no + idx] = row.end;
+      M.t_row[no + idx] = make_int4(row.first, row.eps, row.end, 0);
       stv<kLds>(&M.hidx[h], (typename Mem<kLds>::idx_t)idx);
     } else {
       sh->fault = 1;
@@ -639,6 +635,18 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
                                          int cur, int2 *bp, int32_t *g_tok_state, bool last_frame) {
   // Lnext: the next frame's log-likelihood row in HBM (null: none).  It starts its way now, waits in
   // registers during the frame and is parked in the LDS row Lstage right before the frame's last barrier.
+  constexpr int NW = kBlock / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int co = cur * M.row_cap, no = (cur ^ 1) * M.row_cap;   // row buffer read / built
+  // The arc row of this lane's token in the first batch comes from device memory: ask for it before
+  // anything else (loads return in order), so that it is there when the token's cost has been looked at.
+  int2 fe0 = make_int2(0, 0);
+  if (f >= 0) {
+    const int nb0 = min(kBlock, sh->n_tok);
+    const int tpw0 = (nb0 + NW - 1) / NW;
+    const int i0 = wave * tpw0 + lane;
+    if (lane < tpw0 && i0 < nb0) fe0 = *(const int2 *)&M.t_row[co + i0];
+  }
   constexpr int kPre = kBlock >= 1024 ? 6 : 8;
   float pre[kPre];
 #pragma unroll
@@ -646,9 +654,6 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     int i = threadIdx.x + k * kBlock;
     pre[k] = (Lnext && i < p.num_pdfs) ? Lnext[i] : 0.0f;
   }
-  constexpr int NW = kBlock / 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int co = cur * M.tok_cap, no = (cur ^ 1) * M.tok_cap;   // token buffer read / built
   const bool hist_on = p.max_active > 0 && p.beam > 0.0f && p.beam < __builtin_inff();
   const float inv = 256.0f / p.beam;
   typedef LogT<kLds> LogE;
@@ -695,7 +700,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
           bin = bin > 255 ? 255 : bin;
           alive = bin <= cut;
         }
-        if (alive) { first = M.t_first[co + i]; deg = M.t_eps[co + i] - first; }
+        if (alive) { int2 fe = b == 0 ? fe0 : *(const int2 *)&M.t_row[co + i]; first = fe.x; deg = fe.y - first; }
       }
       if (deg > kBigRowArcs) {
         // a hub-like row: one wave would walk it alone, so park it for the whole workgroup
@@ -825,7 +830,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   // entries logged before it and counts the entries it flags for round r+1 in the other counter
   if (sh->n_front[0] > 0 && !sh->diverged && !sh->fault) {
     if (tid == 0) { sh->fr_begin = 0; sh->fr_end = sh_log_n(sh); }
-    wg_barrier<kLds>();
+    __syncthreads();   // (full: the rounds read token rows that other waves stored to device memory)
     for (int r = 0; sh->n_front[r & 1] > 0; ++r) {
       const int fb = sh->fr_begin, fe = sh->fr_end;
       int32_t *front = &sh->n_front[(r + 1) & 1];
@@ -844,8 +849,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
             // still this state's value, and not dropped by the emission cutoff
             if ((uint32_t)curv == e.arc && curv != kEmptyVal && !(cost - m > p.beam)) {
               uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
-              pd.first = M.t_eps[no + idx];
-              pd.deg = M.t_end[no + idx] - pd.first;
+              int4 rw = M.t_row[no + idx];
+              pd.first = rw.y;
+              pd.deg = rw.z - rw.y;
               pd.cost = cost;
               pd.slot = e.h;
             }
@@ -860,7 +866,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         if (*front > 0 && r + 1 >= p.max_eps_iters) sh->diverged = 1;
         sh->halt = sh->diverged | sh->fault;   // latched between barriers, so every wave takes the same branch
       }
-      wg_barrier<kLds>();
+      __syncthreads();
       if (sh->halt) break;
     }
   }
@@ -968,7 +974,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     }
     for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lstage[i] = Lnext[i];
   }
-  wg_barrier<kLds>();
+  __syncthreads();   // (full: the next frame reads the token rows stored to device memory in this one)
   return kFrameOk;
 }
 
@@ -991,23 +997,19 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   ML.hval = (uint64_t *)(smem + lay.hval);
   ML.hkey = (uint32_t *)(smem + lay.hkey);
   ML.hidx = (uint16_t *)(smem + lay.hidx);
-  ML.t_first = (int32_t *)(smem + lay.tfirst);
-  ML.t_eps = (int32_t *)(smem + lay.teps);
-  ML.t_end = (int32_t *)(smem + lay.tend);
   ML.t_cost = (float *)(smem + lay.tcost);
   ML.log = (LogT<true> *)(smem + lay.log);
-  ML.slots = (uint32_t)p.lds_slots; ML.tok_cap = p.lds_tok_cap; ML.log_cap = p.lds_log_cap;
+  ML.t_row = p.tok_row + (size_t)c * 2 * p.g_tok_cap;
+  ML.slots = (uint32_t)p.lds_slots; ML.tok_cap = p.lds_tok_cap; ML.log_cap = p.lds_log_cap; ML.row_cap = p.g_tok_cap;
 
   Mem<false> MG;
   MG.hval = p.g_hval + (size_t)c * p.g_slots;
   MG.hkey = p.g_hkey + (size_t)c * p.g_slots;
   MG.hidx = p.g_hidx + (size_t)c * p.g_slots;
-  MG.t_first = p.tok_first + (size_t)c * 2 * p.g_tok_cap;
-  MG.t_eps = p.tok_eps + (size_t)c * 2 * p.g_tok_cap;
-  MG.t_end = p.tok_end + (size_t)c * 2 * p.g_tok_cap;
+  MG.t_row = ML.t_row;
   MG.t_cost = p.tok_cost + (size_t)c * p.g_tok_cap;
   MG.log = p.g_log + (size_t)c * p.g_log_cap;
-  MG.slots = (uint32_t)p.g_slots; MG.tok_cap = p.g_tok_cap; MG.log_cap = p.g_log_cap;
+  MG.slots = (uint32_t)p.g_slots; MG.tok_cap = p.g_tok_cap; MG.log_cap = p.g_log_cap; MG.row_cap = p.g_tok_cap;
 
   int32_t *g_tok_state = p.tok_state + (size_t)c * p.g_tok_cap;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
@@ -1044,15 +1046,12 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       atomicOr(&bitmap[b1 >> 5], 1u << (b1 & 31));
     }
   }
-  // tokens enter through device-memory buffer 0; LDS takes them over when they fit
+  // the tokens' costs enter through device memory; LDS takes them over when they fit
   bool fast = p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap;
-  int cur = 0;
+  int cur = p.do_reset ? 0 : (cs->row_buf & 1);
   for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
   if (fast) {
-    for (int i = tid; i < sh->n_tok; i += kBlock) {
-      ML.t_cost[i] = MG.t_cost[i]; ML.t_first[i] = MG.t_first[i];
-      ML.t_eps[i] = MG.t_eps[i]; ML.t_end[i] = MG.t_end[i];
-    }
+    for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = MG.t_cost[i];
   }
   if (p.n_frames > 0 && p.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = Lbase[i];
   __syncthreads();
@@ -1069,30 +1068,22 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     if (fast) {
       outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
       if (outcome == kFrameOverflow) {
-        // redo the frame with the tables in device memory: wipe the LDS table, hand the tokens over
-        const int lo = cur * p.lds_tok_cap;
+        // redo the frame with the tables in device memory: wipe the LDS table, hand the costs over
         for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
-        for (int i = tid; i < sh->n_tok; i += kBlock) {
-          MG.t_cost[i] = ML.t_cost[i]; MG.t_first[i] = ML.t_first[lo + i];
-          MG.t_eps[i] = ML.t_eps[lo + i]; MG.t_end[i] = ML.t_end[lo + i];
-        }
+        for (int i = tid; i < sh->n_tok; i += kBlock) MG.t_cost[i] = ML.t_cost[i];
         __syncthreads();
         if (tid < 64) frame_init(sh, hist, f < 0, tid);
         __syncthreads();
-        fast = false; cur = 0; slow = true;
+        fast = false; slow = true;
       }
     }
     if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
     if (outcome != kFrameOk) break;
     cur ^= 1;
     if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {
-      // the token list fits LDS again (the next frame's first barrier orders these LDS writes)
-      const int go = cur * p.g_tok_cap;
-      for (int i = tid; i < sh->n_tok; i += kBlock) {
-        ML.t_cost[i] = MG.t_cost[i]; ML.t_first[i] = MG.t_first[go + i];
-        ML.t_eps[i] = MG.t_eps[go + i]; ML.t_end[i] = MG.t_end[go + i];
-      }
-      fast = true; cur = 0;
+      // the token list fits LDS again
+      for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = MG.t_cost[i];
+      fast = true;
       __syncthreads();
     }
   }
@@ -1104,19 +1095,10 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   else if (outcome == kFrameNoTokens) status = kStatusNoTokens;
   else if (outcome == kFrameDiverged) status = kStatusEpsDiverged;
   if (status == kStatusOk) {
-    // tokens leave through device-memory buffer 0
+    // the tokens' costs leave through device memory
     const int n = sh->n_tok;
     if (fast) {
-      const int lo = cur * p.lds_tok_cap;
-      for (int i = tid; i < n; i += kBlock) {
-        MG.t_cost[i] = ML.t_cost[i]; MG.t_first[i] = ML.t_first[lo + i];
-        MG.t_eps[i] = ML.t_eps[lo + i]; MG.t_end[i] = ML.t_end[lo + i];
-      }
-    } else if (cur != 0) {
-      const int go = p.g_tok_cap;
-      for (int i = tid; i < n; i += kBlock) {
-        MG.t_first[i] = MG.t_first[go + i]; MG.t_eps[i] = MG.t_eps[go + i]; MG.t_end[i] = MG.t_end[go + i];
-      }
+      for (int i = tid; i < n; i += kBlock) MG.t_cost[i] = ML.t_cost[i];
     }
   } else if (outcome != kFrameNoTokens) {
     // leave the device-memory table empty for the next utterance
@@ -1129,6 +1111,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     cs->n_rec = sh->n_rec;
     cs->best = sh->best;
     cs->cut_bin = sh->cut_bin;
+    cs->row_buf = status == kStatusOk ? cur : 0;
     if (p.do_reset) {
       cs->frames = 0; cs->active_tokens = 0; cs->emit_arcs = 0; cs->eps_arcs = 0; cs->candidates = 0;
       cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0; cs->slow_frames = 0;

@@ -96,7 +96,7 @@ def test_e2e_units_lexicon_loop(torch_cuda):
     g = synth.graph_for(w)
     og = OracleGraph.from_graph(g)
     total = check_workload(torch_cuda, w, g, og, sample=[0, 31, 63], prop_channels=range(0, w.channels, 8))
-    assert total["slow_frames"] == total["frames"]
+    assert total["max_tokens"] > 2500   # far denser token activity than the HCLG-style workloads
 
 
 @pytest.mark.timeout(900)

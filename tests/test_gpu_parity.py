@@ -185,7 +185,7 @@ def test_shared_compute_units_and_unstaged_rows(torch_cuda, wgs):
 
 def test_lexicon_loop_units_workload(torch_cuda):
     """Second workload (Sec. 6: end-to-end model units): a lexicon loop with a 3000-arc hub row, self-loops,
-    thousands of tokens per frame (device-memory tables on every frame), max-active pruning engaged,
+    thousands of tokens per frame, max-active pruning engaged,
     boosted epsilon-input word-end arcs."""
     torch = torch_cuda
     g = synth.make_lexicon_graph(48, 3000, seed_stream=(21,))
@@ -193,9 +193,17 @@ def test_lexicon_loop_units_workload(torch_cuda):
     w = synth.scaled(synth.WORKLOADS["e2e"], channels=3, config_id=61)
     ctxs, offs = synth.make_contexts(w, g)
     assert all(np.all(g.ilabel[c] == 0) for c in ctxs)     # word-end arcs are epsilon-input arcs
-    s = run_batch(torch, g, L, ctxs, offs, beam=10.0, max_active=800, chunks=[3, 17, 20], hash_log2=14, lookup_mode=1)
+    # once with the device-memory tables on every frame, once with whatever the LDS tables can carry
+    s = run_batch(torch, g, L, ctxs, offs, beam=10.0, max_active=800, chunks=[3, 17, 20], hash_log2=14, lookup_mode=1,
+                  table_location=2)
     assert s["slow_frames"] == s["frames"] and s["max_tokens"] > 2500
     assert s["active_tokens"] < 0.5 * s["tokens"]           # the histogram cut did most of the pruning
+    s2 = run_batch(torch, g, L, ctxs, offs, beam=10.0, max_active=800, chunks=[3, 17, 20], hash_log2=14, lookup_mode=1)
+    assert s2["tokens"] == s["tokens"] and s2["emit_arcs"] == s["emit_arcs"]
+    # and with an LDS capacity that many frames exceed: tables move between LDS and device memory and back
+    s3 = run_batch(torch, g, L, ctxs, offs, beam=10.0, max_active=800, chunks=[3, 17, 20], hash_log2=14, lookup_mode=1,
+                   lds_token_cap=1024)
+    assert 0 < s3["slow_frames"] and s3["tokens"] == s["tokens"]
 
 
 def test_histogram_pruning_engages(torch_cuda):
