@@ -97,6 +97,7 @@ struct cbd_graph {
   int2 *d_off2 = nullptr;
   cbd::ArcRec *d_arcs = nullptr;
   int32_t *d_int2pub = nullptr;
+  int32_t *d_pub2int = nullptr;   // caller's arc numbering -> library numbering (context lists are translated on the device)
   int32_t *d_olabel = nullptr;
   float *d_final = nullptr;
   std::vector<int32_t> pub2int, int2pub;
@@ -372,11 +373,13 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   GCHK(dmalloc(&g->d_off2, (size_t)S + 1, &g->bytes));
   GCHK(dmalloc(&g->d_arcs, (size_t)A, &g->bytes));
   GCHK(dmalloc(&g->d_int2pub, (size_t)A, &g->bytes));
+  GCHK(dmalloc(&g->d_pub2int, (size_t)A, &g->bytes));
   GCHK(dmalloc(&g->d_olabel, (size_t)A, &g->bytes));
   GCHK(hipMemcpy(g->d_off2, off2.data(), sizeof(int2) * ((size_t)S + 1), hipMemcpyHostToDevice));
   if (A > 0) {
     GCHK(hipMemcpy(g->d_arcs, arcs.data(), sizeof(cbd::ArcRec) * (size_t)A, hipMemcpyHostToDevice));
     GCHK(hipMemcpy(g->d_int2pub, g->int2pub.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_pub2int, g->pub2int.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
     GCHK(hipMemcpy(g->d_olabel, olab.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
   }
   if (desc->final_cost) {
@@ -496,6 +499,7 @@ int32_t cbd_graph_free(cbd_graph *g) {
   if (g->d_off2) (void)hipFree(g->d_off2);
   if (g->d_arcs) (void)hipFree(g->d_arcs);
   if (g->d_int2pub) (void)hipFree(g->d_int2pub);
+  if (g->d_pub2int) (void)hipFree(g->d_pub2int);
   if (g->d_olabel) (void)hipFree(g->d_olabel);
   if (g->d_final) (void)hipFree(g->d_final);
   delete g;
@@ -564,7 +568,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     int cap = best_cap(g->P);
     d->stage_rows = 1;
     const bool row_fits = (int64_t)cbd::make_layout(g->P, d->ctx_lds_cap, 0, 0, 0).total <= budget;
-    if (!row_fits || (wgs > 1 && cfg->table_location != 2 && cap < 1024 && cfg->lds_token_cap == 0)) {
+    if (!row_fits || (wgs > 1 && cfg->table_location != 2 && cap < 2048 && cfg->lds_token_cap == 0)) {
       d->stage_rows = 0;
       cap = best_cap(0);
     }
@@ -756,6 +760,65 @@ int32_t upload_lists(cbd_decoder *d, int32_t n, const int32_t *slots, const int3
   return CBD_OK;
 }
 
+// Checks n lists as given by the caller (offsets, arc numbers in range) without changing anything;
+// longest receives the length of the longest list.
+int32_t check_raw_lists(const cbd_decoder *d, int32_t n, const int32_t *arc_idx, const int32_t *list_offsets,
+                        const float *offsets, const char *who, int32_t *longest) {
+  const std::string w(who);
+  if (list_offsets[0] != 0) return fail(CBD_E_INVALID, w + ": list_offsets[0] != 0");
+  int32_t mx = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (list_offsets[i + 1] < list_offsets[i]) return fail(CBD_E_INVALID, w + ": list_offsets not monotone");
+    if (!std::isfinite(offsets[i])) return fail(CBD_E_INVALID, w + ": non-finite offset");
+    mx = std::max(mx, list_offsets[i + 1] - list_offsets[i]);
+  }
+  const int32_t total = list_offsets[n];
+  if (total > 0 && !arc_idx) return fail(CBD_E_INVALID, w + ": null list");
+  const uint32_t num_arcs = (uint32_t)d->g->A;
+  uint32_t bad = 0;
+  for (int32_t k = 0; k < total; ++k) bad |= (uint32_t)((uint32_t)arc_idx[k] >= num_arcs);
+  if (bad) return fail(CBD_E_INVALID, w + ": arc index out of range");
+  *longest = mx;
+  return CBD_OK;
+}
+
+// Can the device prepare these lists?  (Each must fit its slot even if no entry repeats, and the sort's LDS.)
+bool device_can_prepare(const cbd_decoder *d, int32_t longest) {
+  return longest <= d->cfg.max_context_arcs && longest <= cbd::kPrepMaxList;
+}
+
+// Uploads the caller's lists as they are; the device translates, sorts and de-duplicates them (slots / bind
+// as in upload_lists).
+int32_t upload_raw_lists(cbd_decoder *d, int32_t n, const int32_t *slots, const int32_t *bind, const float *offsets,
+                         const int32_t *arc_idx, const int32_t *list_offsets) {
+  for (int32_t i0 = 0; i0 < n; i0 += d->C) {
+    const int32_t m = std::min(d->C, n - i0);
+    int slot = 0;
+    HIPCHK(d->ctxs.acquire(&slot));
+    int32_t *h = (int32_t *)d->ctxs.host[slot];
+    const size_t mm = (size_t)m;
+    const int32_t base = list_offsets[i0], cnt = list_offsets[(size_t)i0 + mm] - base;
+    int32_t longest = 0;
+    memcpy(h, slots + i0, sizeof(int32_t) * mm);
+    if (bind) memcpy(h + mm, bind + i0, sizeof(int32_t) * mm);
+    for (size_t k = 0; k <= mm; ++k) h[2 * mm + k] = list_offsets[(size_t)i0 + k] - base;
+    for (size_t k = 0; k < mm; ++k) longest = std::max(longest, h[2 * mm + k + 1] - h[2 * mm + k]);
+    memcpy(h + 3 * mm + 1, offsets + i0, sizeof(float) * mm);
+    if (cnt > 0) memcpy(h + 4 * mm + 1, arc_idx + base, sizeof(int32_t) * (size_t)cnt);
+    HIPCHK(d->ctxs.upload(slot, sizeof(int32_t) * (4 * mm + 1 + (size_t)cnt), d->stream));
+    const int32_t *dv = (const int32_t *)d->ctxs.dev[slot];
+    int pow2 = 1;
+    while (pow2 < longest) pow2 <<= 1;
+    hipLaunchKernelGGL(cbd::prepare_contexts_kernel, dim3((unsigned)m), dim3(cbd::kPrepThreads),
+                       sizeof(int32_t) * (size_t)pow2, d->stream, dv, bind ? dv + mm : (const int32_t *)nullptr,
+                       dv + 2 * mm, (const float *)(dv + 3 * mm + 1), dv + 4 * mm + 1, d->g->d_pub2int, d->d_ctx,
+                       d->max_ctx, d->d_ctx_n, d->d_ctx_off, d->d_chan);
+    HIPCHK(hipGetLastError());
+    HIPCHK(d->ctxs.release(slot, d->stream));
+  }
+  return CBD_OK;
+}
+
 int32_t check_channel_list(cbd_decoder *d, const int32_t *channels, int32_t n, const char *who) {
   const std::string w(who);
   if (!channels || n <= 0 || n > d->C) return fail(CBD_E_INVALID, w + ": bad channel count");
@@ -777,10 +840,16 @@ int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_chan
   // validate everything before anything changes
   int32_t rc = check_channel_list(d, channels, n_channels, "set_contexts");
   if (rc != CBD_OK) return rc;
+  int32_t longest = 0;
+  rc = check_raw_lists(d, n_channels, arc_idx, list_offsets, offsets, "set_contexts", &longest);
+  if (rc != CBD_OK) return rc;
+  // a channel's own context lives in store slot `channel`
+  if (device_can_prepare(d, longest))
+    return upload_raw_lists(d, n_channels, channels, channels, offsets, arc_idx, list_offsets);
+  // very long lists, or lists that only fit once their repeats are gone: prepared here
   std::vector<int32_t> packed, off;
   rc = prepare_lists(d, n_channels, arc_idx, list_offsets, offsets, packed, off, "set_contexts");
   if (rc != CBD_OK) return rc;
-  // a channel's own context lives in store slot `channel`
   return upload_lists(d, n_channels, channels, channels, offsets, packed, off);
 }
 
@@ -791,9 +860,15 @@ int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *a
   int32_t free_ids = 0;
   for (uint8_t u : d->pool_used) free_ids += !u;
   if (n_contexts > free_ids) return fail(CBD_E_CAPACITY, "contexts_create: context pool full");
-  std::vector<int32_t> packed, off;
-  int32_t rc = prepare_lists(d, n_contexts, arc_idx, list_offsets, offsets, packed, off, "contexts_create");
+  int32_t longest = 0;
+  int32_t rc = check_raw_lists(d, n_contexts, arc_idx, list_offsets, offsets, "contexts_create", &longest);
   if (rc != CBD_OK) return rc;
+  const bool on_device = device_can_prepare(d, longest);
+  std::vector<int32_t> packed, off;
+  if (!on_device) {
+    rc = prepare_lists(d, n_contexts, arc_idx, list_offsets, offsets, packed, off, "contexts_create");
+    if (rc != CBD_OK) return rc;
+  }
   std::vector<int32_t> slots((size_t)n_contexts);
   int32_t next = 0;
   for (int32_t i = 0; i < n_contexts; ++i) {
@@ -802,7 +877,8 @@ int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *a
     context_ids[i] = next;
     slots[(size_t)i] = d->C + next;
   }
-  rc = upload_lists(d, n_contexts, slots.data(), nullptr, offsets, packed, off);
+  rc = on_device ? upload_raw_lists(d, n_contexts, slots.data(), nullptr, offsets, arc_idx, list_offsets)
+                 : upload_lists(d, n_contexts, slots.data(), nullptr, offsets, packed, off);
   if (rc != CBD_OK)
     for (int32_t i = 0; i < n_contexts; ++i) d->pool_used[(size_t)context_ids[i]] = 0;
   return rc;

@@ -1150,6 +1150,63 @@ __global__ void scatter_contexts_kernel(const int32_t *slots, const int32_t *bin
   }
 }
 
+// Sec. 4.2 asks for the listed arc indices sorted; the list is a set.  One workgroup per uploaded list does
+// all of it on the device: caller's arc numbering -> library numbering, bitonic sort in LDS, removal of
+// repeats, and the store into the list's slot (with `bind`, channel bind[i] is switched to that slot too).
+// Lists longer than kPrepMaxList are prepared on the host instead.
+constexpr int kPrepMaxList = 8192;
+constexpr int kPrepThreads = 256;
+
+__global__ __launch_bounds__(kPrepThreads) void prepare_contexts_kernel(
+    const int32_t *slots, const int32_t *bind, const int32_t *list_off, const float *offsets, const int32_t *lists,
+    const int32_t *pub2int, int32_t *ctx, int max_ctx, int32_t *ctx_n, float *ctx_off, ChanState *chan) {
+  extern __shared__ __align__(16) int32_t prep_v[];   // the next power of two >= the longest list of the launch
+  __shared__ int32_t prep_cnt[kPrepThreads];
+  const int tid = threadIdx.x;
+  const int i = blockIdx.x;
+  const int slot = slots[i];
+  const int b = list_off[i], n = list_off[i + 1] - b;
+  int N = 1;
+  while (N < n) N <<= 1;
+  const int32_t kPad = 0x7FFFFFFF;   // no arc has this number; pads sort to the end
+  for (int k = tid; k < N; k += kPrepThreads) prep_v[k] = k < n ? pub2int[lists[b + k]] : kPad;
+  __syncthreads();
+  for (int k = 2; k <= N; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int t = tid; t < (N >> 1); t += kPrepThreads) {
+        const int lo = 2 * j * (t / j) + (t % j), hi = lo + j;
+        const bool ascending = (lo & k) == 0;
+        const int32_t x = prep_v[lo], y = prep_v[hi];
+        if ((x > y) == ascending) { prep_v[lo] = y; prep_v[hi] = x; }
+      }
+      __syncthreads();
+    }
+  }
+  // each thread owns a run of consecutive positions: count the first occurrences in it, ...
+  const int per = (N + kPrepThreads - 1) / kPrepThreads;
+  const int e0 = min(tid * per, N), e1 = min(e0 + per, N);
+  int cnt = 0;
+  for (int e = e0; e < e1; ++e) cnt += prep_v[e] != kPad && (e == 0 || prep_v[e] != prep_v[e - 1]);
+  prep_cnt[tid] = cnt;
+  __syncthreads();
+  // ... turn the counts into positions (inclusive scan over the threads), ...
+  for (int d = 1; d < kPrepThreads; d <<= 1) {
+    const int add = tid >= d ? prep_cnt[tid - d] : 0;
+    __syncthreads();
+    prep_cnt[tid] += add;
+    __syncthreads();
+  }
+  // ... and store them in order
+  int pos = prep_cnt[tid] - cnt;
+  int32_t *out = ctx + (size_t)slot * max_ctx;
+  for (int e = e0; e < e1; ++e)
+    if (prep_v[e] != kPad && (e == 0 || prep_v[e] != prep_v[e - 1])) out[pos++] = prep_v[e];   // pos < n <= max_ctx
+  if (tid == 0) {
+    ctx_n[slot] = prep_cnt[kPrepThreads - 1]; ctx_off[slot] = offsets[i];
+    if (bind) chan[bind[i]].ctx_slot = slot;
+  }
+}
+
 // Sec. 4.3: switching a channel to a context that is already on the device is one store.
 __global__ void bind_contexts_kernel(const int32_t *chan_ids, const int32_t *slots, int n, ChanState *chan) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;

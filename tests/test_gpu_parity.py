@@ -226,6 +226,33 @@ def test_hashed_bitmap_lookup_and_heavy_bias(torch_cuda):
     assert a["emit_arcs"] == b["emit_arcs"] and a["tokens"] == b["tokens"]
 
 
+def test_context_lists_prepared_on_device_and_on_host(torch_cuda):
+    """The list is a set (Sec. 4.2): given shuffled and with every entry three times it decodes like the plain
+    list, whether the device sorts it (it fits its slot as given) or the host does (it fits only without repeats);
+    list lengths on both sides of the powers of two the device sort pads to."""
+    torch = torch_cuda
+    g, L, _, offs = mid_inputs(torch, C=4, T=30, seed=15)
+    rng = np.random.default_rng(15)
+    ctxs = [np.sort(rng.choice(g.num_arcs, size=k, replace=False)).astype(np.int32) for k in (0, 1, 257, 512)]
+    tripled = [rng.permutation(np.concatenate([x, x, x])).astype(np.int32) for x in ctxs]
+    og = OracleGraph.from_graph(g)
+    orcs = GH.oracle_channels(g, 4, 13.0, 0, og=og)
+    Lh = L.cpu().numpy()
+    for c in range(4):
+        orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset(); orcs[c].advance(Lh[c])
+    for lists, cap in ((ctxs, 512), (tripled, 1536), (tripled, 512)):
+        dec = GH.GpuDecoder(g, 4, 13.0, 0, max_frames=30, max_context_arcs=cap)
+        try:
+            dec.set_contexts(lists, offs)
+            dec.reset()
+            dec.advance(L, 0, 30)
+            for c in range(4):
+                GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"cap {cap} ch {c}")
+                GH.assert_tables_equal(dec.tokens(c), orcs[c].tokens(), f"cap {cap} ch {c}")
+        finally:
+            dec.close()
+
+
 def test_context_swap_mid_utterance_and_finals(torch_cuda):
     """Contexts replaced between chunks without a reset (Sec. 4.3); final costs pick the end token."""
     torch = torch_cuda
