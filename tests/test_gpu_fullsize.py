@@ -125,3 +125,40 @@ def test_throughput_stress(torch_cuda, big_graph):
     rng = np.random.default_rng(2)
     sample = [0, w.channels - 1] + rng.choice(w.channels, 4, replace=False).tolist()
     check_workload(torch_cuda, w, g, og, sample=sample, prop_channels=range(0, w.channels, 64))
+
+
+@pytest.mark.timeout(600)
+def test_three_minute_utterance(torch_cuda):
+    """Sec. 5.3 decodes 3-minute recordings: 6000 frames of 30 ms in one utterance, in 50-frame chunks, with a
+    partial result now and then.  All back-pointer records of the utterance stay in device memory (no
+    garbage collection is needed at these sizes), so this checks record indices and the long traceback."""
+    torch = torch_cuda
+    w = synth.scaled(synth.WORKLOADS["medium"], channels=4, frames=6000, chunk=50, config_id=62)
+    g = synth.graph_for(synth.WORKLOADS["medium"])
+    og = OracleGraph.from_graph(g)
+    L = synth.make_loglikes(w.channels, w.frames, w.num_pdfs, w.sigma, seed_stream=(62,), device="cuda")
+    ctxs, offs = synth.make_contexts(w, g)
+    dec = GH.GpuDecoder(g, w.channels, w.beam, w.max_active, max_frames=w.frames, records_per_frame=1024,
+                        max_context_arcs=max(len(x) for x in ctxs))
+    try:
+        orcs = GH.oracle_channels(g, 2, w.beam, w.max_active, og=og)
+        Lh = L[:2].cpu().numpy()
+        dec.set_contexts(ctxs, offs)
+        dec.reset()
+        for c in range(2):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset()
+        for t in range(0, w.frames, w.chunk):
+            dec.advance(L, t, t + w.chunk)
+            for c in range(2):
+                orcs[c].advance(Lh[c, t:t + w.chunk])
+            if (t // w.chunk) % 40 == 39:
+                for c in range(2):
+                    GH.assert_best_equal(dec.best(c), orcs[c].best_path(False), f"partial at frame {t + w.chunk} ch {c}")
+        for c in range(2):
+            rc, words, arcs, cost = dec.best(c, True)
+            GH.assert_best_equal((rc, words, arcs, cost), orcs[c].best_path(True), f"final ch {c}")
+            assert len(arcs) >= w.frames
+        st = dec.stats(-1)
+        assert st["status"] == 0 and st["frames"] == w.channels * w.frames
+    finally:
+        dec.close()
