@@ -526,6 +526,145 @@ __device__ __forceinline__ void pending_clear(Pending &pd) {
   pd.first2 = 0; pd.deg2 = 0; pd.cost2 = 0.0f; pd.slot2 = 0;
 }
 
+constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimum settles
+
+// Recombination of the emit phase's candidates, slots r0 and r0 + 1 of each lane (slot r is in use if
+// r * 64 < total).  Same steps as commit(), but taken for both slots together, so that a lane with two candidates
+// waits once per step, not once per candidate: cutoff against the running minimum; home-slot claims; (rarely)
+// walks after collisions; minima; one counter update for the wave; rows, table indices and log entries.  A lane
+// keeps the first two states it lowered that have epsilon-input arcs as its own pending work for the closure
+// (asking for the first one's arc record right away); any further ones are flagged in the change log.
+constexpr int kPair = 2;
+template <bool kLds>
+__device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no,
+                                                 int total, int r0, const float *cand, const int *arc,
+                                                 const ArcRec *rec, const uint32_t *srct, uint32_t &n_cand, int lane,
+                                                 Pending &pd, uint32_t &pd_arc, uint32_t &pd_arc2) {
+  typedef LogT<kLds> LogE;
+  const int fault = load_fault(sh);
+  const float mref = ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+  bool ok[kPair], claimed[kPair], improved[kPair];
+  uint32_t h[kPair], k[kPair], src[kPair];
+  unsigned long long any = 0;
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    const int r = r0 + q;
+    ok[q] = r * 64 + lane < total && !(cand[q] - mref > p.beam) && !fault;   // for now: "passes and will be tried"
+    claimed[q] = false; improved[q] = false; h[q] = 0; k[q] = 0; src[q] = srct[q];
+    if (r * 64 < total) {
+      unsigned long long pm = __ballot(r * 64 + lane < total && !(cand[q] - mref > p.beam));
+      n_cand += (uint32_t)__popcll(pm);
+      any |= pm;
+    }
+  }
+  if (any == 0) return;
+  // home slots
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    if ((r0 + q) * 64 < total && ok[q]) {
+      h[q] = __umulhi((uint32_t)rec[q].dst * 2654435761u, M.slots);
+      k[q] = atomicCAS(&M.hkey[h[q]], kEmptyKey, (uint32_t)rec[q].dst);
+    }
+  }
+  // collisions: walk on (rare)
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    if ((r0 + q) * 64 < total) {
+      const uint32_t state = (uint32_t)rec[q].dst;
+      const bool collided = ok[q] && k[q] != kEmptyKey && k[q] != state;
+      if (__ballot(collided) != 0) {
+        if (collided) {
+          uint32_t hh = h[q], kk = k[q], probe = 1;
+          do {
+            hh = hh + 1 == M.slots ? 0 : hh + 1;
+            kk = atomicCAS(&M.hkey[hh], kEmptyKey, state);
+          } while (kk != kEmptyKey && kk != state && ++probe < M.slots && !((probe & 63u) == 0 && load_fault(sh)));
+          if (kk == kEmptyKey || kk == state) { h[q] = hh; k[q] = kk; }
+          else { ok[q] = false; sh->fault = 1; }   // every slot holds another state, or the frame is being given up
+        }
+      }
+    }
+  }
+  // minima
+  uint64_t old[kPair];
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    old[q] = 0;
+    if ((r0 + q) * 64 < total && ok[q]) {
+      const uint64_t key = ((uint64_t)f2ord(cand[q]) << 32) | (uint32_t)arc[q];
+      old[q] = atomicMin((unsigned long long *)&M.hval[h[q]], (unsigned long long)key);
+    }
+  }
+  // who lowered what; which states the lane keeps for the closure
+  unsigned long long imask[kPair], cmask[kPair];
+  RowInfo row[kPair];
+  int n_imp = 0, n_claim = 0, n_flag = 0;
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    imask[q] = cmask[q] = 0;
+    row[q].first = row[q].eps = row[q].end = 0;
+    if ((r0 + q) * 64 < total) {
+      const uint64_t key = ((uint64_t)f2ord(cand[q]) << 32) | (uint32_t)arc[q];
+      improved[q] = ok[q] && old[q] > key;
+      claimed[q] = ok[q] && k[q] == kEmptyKey;
+      if (improved[q] || claimed[q]) row[q] = row_of(p, rec[q]);
+      if (improved[q] && row[q].end > row[q].eps) {
+        if (pd.deg == 0) {
+          pd.first = row[q].eps; pd.deg = row[q].end - row[q].eps; pd.cost = cand[q]; pd.slot = h[q];
+          pd.nxt = p.arcs[row[q].eps]; pd.have_nxt = true;
+          pd_arc = (uint32_t)arc[q];
+        } else if (pd.deg2 == 0) {
+          pd.first2 = row[q].eps; pd.deg2 = row[q].end - row[q].eps; pd.cost2 = cand[q]; pd.slot2 = h[q];
+          pd_arc2 = (uint32_t)arc[q];
+        } else {
+          src[q] |= LogE::kSrcHasEps;
+        }
+      }
+      imask[q] = __ballot(improved[q]);
+      cmask[q] = __ballot(claimed[q]);
+      n_imp += __popcll(imask[q]); n_claim += __popcll(cmask[q]);
+      n_flag += __popcll(__ballot(improved[q] && (src[q] & LogE::kSrcHasEps)));
+    }
+  }
+  // (a lane can create a state's entry and still lose the minimum to a lane of another wave
+  // that reached the value first: it must get its token index all the same)
+  if ((n_imp | n_claim) == 0) return;
+  unsigned long long base = 0;
+  if (lane == 0) {
+    base = atomicAdd(&sh->log_claim, (unsigned long long)n_imp | ((unsigned long long)n_claim << 32));
+    if (n_flag) atomicAdd(&sh->n_front[0], n_flag);
+  }
+  int base_log = __builtin_amdgcn_readfirstlane((int)(uint32_t)base);
+  int base_tok = __builtin_amdgcn_readfirstlane((int)(uint32_t)(base >> 32));
+  const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int q = 0; q < kPair; ++q) {
+    if ((r0 + q) * 64 < total) {
+      if (claimed[q]) {
+        int idx = base_tok + __popcll(cmask[q] & below);
+        if (idx < M.tok_cap) {
+          M.t_row[no + idx] = make_int4(row[q].first, row[q].eps, row[q].end, 0);
+          stv<kLds>(&M.hidx[h[q]], (typename Mem<kLds>::idx_t)idx);
+        } else {
+          sh->fault = 1;
+        }
+      }
+      if (improved[q]) {
+        int pos = base_log + __popcll(imask[q] & below);
+        if (pos < M.log_cap) {
+          LogE e;
+          e.arc = (uint32_t)arc[q]; e.h = (decltype(e.h))h[q]; e.src = (decltype(e.src))src[q];
+          M.log[pos] = e;
+        } else {
+          sh->fault = 1;
+        }
+      }
+      base_tok += __popcll(cmask[q]);
+      base_log += __popcll(imask[q]);
+    }
+  }
+}
+
 // Epsilon closure from this wave's pending states.  While every pending row has one arc (the
 // usual case) each lane expands its own arc: no scan, no cross-lane traffic, and the record
 // of the next level's arc is requested before the table update that decides whether it is
@@ -610,8 +749,6 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     pd.have_nxt = false;
   }
 }
-
-constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimum settles
 
 // Per-frame scalars and the pruning histogram, set by one wave; a barrier must follow before use.
 // start: the frame is the start of an utterance (its cutoff reference is the start token's cost 0).
@@ -750,29 +887,10 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
       wg_barrier<kLds>();   // the batch minimum is known: few doomed candidates reach the table
       // phase B: cutoff, recombination
-      const int fault = load_fault(sh);
-#pragma unroll
-      for (int r = 0; r < kEmitSlots; ++r) {
-        if (r * 64 < AL.total) {
-          bool act = r * 64 + lane < AL.total;
-          // a lane that lowers a state with epsilon-input arcs keeps it for the closure (the first of them;
-          // any further ones are flagged in the change log) and asks for the row's first arc right away
-          bool imp; uint32_t hh; RowInfo rr;
-          const bool flag = pd.deg2 > 0;
-          commit<kLds, true>(p, M, sh, &sh->n_front[0], no, act, cand[r], arc[r], rec[r], srct[r], 0.0f, n_cand, lane,
-                             flag, fault, imp, hh, rr);
-          if (imp && !flag && rr.end > rr.eps) {
-            if (pd.deg == 0) {
-              pd.first = rr.eps; pd.deg = rr.end - rr.eps; pd.cost = cand[r]; pd.slot = hh;
-              pd.nxt = p.arcs[rr.eps]; pd.have_nxt = true;
-              pd_arc = (uint32_t)arc[r];
-            } else {
-              pd.first2 = rr.eps; pd.deg2 = rr.end - rr.eps; pd.cost2 = cand[r]; pd.slot2 = hh;
-              pd_arc2 = (uint32_t)arc[r];
-            }
-          }
-        }
-      }
+      commit_emit_pair<kLds>(p, M, sh, no, AL.total, 0, &cand[0], &arc[0], &rec[0], &srct[0], n_cand, lane, pd, pd_arc, pd_arc2);
+      if (AL.total > 128)
+        commit_emit_pair<kLds>(p, M, sh, no, AL.total, 2, &cand[2], &arc[2], &rec[2], &srct[2], n_cand, lane, pd, pd_arc,
+                               pd_arc2);
       if (AL.total > kEmitSlots * 64)
         expand_direct<kLds, true>(p, M, sh, &sh->n_front[0], cx, Lrow, no, AL, kEmitSlots * 64, cost,
                                   (uint32_t)(tile0 + lane), 0.0f, n_cand, lane);
