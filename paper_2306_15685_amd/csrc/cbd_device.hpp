@@ -324,7 +324,11 @@ __device__ __forceinline__ RowInfo row_of(const AdvanceParams &p, const ArcRec &
   uint32_t ed = (rec.meta >> 16) & 255u, xd = rec.meta >> 24;
   r.first = rec.row;
   if (ed == kDegEscape || xd == kDegEscape) {
+    // a long row (rare): its bounds come from the offsets.  The wait is taken here, inside the rare branch, so
+    // that code after it never has to wait for "a load that may have happened" (which would also make it wait
+    // for the arc records requested ahead of need).
     int2 o = p.off2[rec.dst], o2 = p.off2[rec.dst + 1];
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
     r.eps = o.y; r.end = o2.x;
   } else {
     r.eps = r.first + (int)ed; r.end = r.eps + (int)xd;
@@ -445,9 +449,11 @@ template <bool kLds, bool kEmit>
 __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front, int no,
                                        bool act, float cand, int a, const ArcRec &rec, uint32_t src_tag, float m_fixed,
                                        uint32_t &n_cand, int lane, bool flag_children, int fault, bool &improved,
-                                       uint32_t &h, RowInfo &row) {
-  // fault: a recent reading of the overflow flag (see load_fault); once set, the tables are left alone
-  improved = false; h = 0; row.first = row.eps = row.end = 0;
+                                       uint32_t &h, RowInfo &row, bool have_row = false) {
+  // fault: a recent reading of the overflow flag (see load_fault); once set, the tables are left alone.
+  // have_row: row already holds the destination's row (else it is worked out here for candidates that pass).
+  improved = false; h = 0;
+  if (!have_row) row.first = row.eps = row.end = 0;
   bool pass = false;
   if (act) {
     float mref = kEmit ? ord2f(__hip_atomic_load(&sh->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) : m_fixed;
@@ -465,7 +471,7 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
   bool claimed = false;
   uint32_t src = src_tag;
   if (pass && !fault) {
-    row = row_of(p, rec);
+    if (!have_row) row = row_of(p, rec);
     if (flag_children && row.end > row.eps) src |= LogT<kLds>::kSrcHasEps;   // flag_children may differ per lane
     uint64_t key = ((uint64_t)co << 32) | (uint32_t)a;
     improved = table_min<kLds>(M, sh, (uint32_t)rec.dst, key, h, claimed);
@@ -694,23 +700,21 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
       n_eps += (uint32_t)__popcll(pend);
       const bool act = pd.deg > 0;
       const int a = pd.first;
-      ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
-      float cand = 0.0f;
-      Pending nx; pending_clear(nx);
-      if (act) {
-        if (!pd.have_nxt) pd.nxt = p.arcs[a];
-        rec = pd.nxt;
-        float w = rec.weight;
-        if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
-        cand = pd.cost + w;
-        if (!(cand - m > p.beam)) {
-          RowInfo ahead = row_of(p, rec);
-          if (ahead.end > ahead.eps) { nx.nxt = p.arcs[ahead.eps]; nx.have_nxt = true; }   // ahead of need
-        }
-      }
-      bool improved; uint32_t h; RowInfo row;
+      if (act && !pd.have_nxt) pd.nxt = p.arcs[a];
+      const ArcRec rec = pd.nxt;
+      float w = rec.weight;
+      if (act && ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
+      const float cand = pd.cost + w;
+      // the record of the next level's arc is asked for now, by every lane (lanes without one ask for record 0:
+      // no branch around the load, so nothing downstream has to wait for it before it is needed)
+      const RowInfo ahead = row_of(p, rec);
+      const bool more = act && !(cand - m > p.beam) && ahead.end > ahead.eps;
+      Pending nx;
+      nx.nxt = p.arcs[more ? ahead.eps : 0];
+      nx.have_nxt = more;
+      bool improved; uint32_t h; RowInfo row = ahead;
       commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, pd.slot | LogE::kSrcEps, m, n_cand, lane, false,
-                          fault, improved, h, row);
+                          fault, improved, h, row, true);
       const bool go = improved && row.end > row.eps;
       nx.first = go ? row.eps : 0; nx.deg = go ? row.end - row.eps : 0; nx.cost = cand; nx.slot = h;
       nx.have_nxt = nx.have_nxt && go;
