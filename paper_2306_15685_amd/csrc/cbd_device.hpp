@@ -601,10 +601,12 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
       old[q] = atomicMin((unsigned long long *)&M.hval[h[q]], (unsigned long long)key);
     }
   }
+  __builtin_amdgcn_sched_barrier(0);   // both minima are on their way before anything below is looked at
   // who lowered what; which states the lane keeps for the closure
   unsigned long long imask[kPair], cmask[kPair];
   RowInfo row[kPair];
   int n_imp = 0, n_claim = 0, n_flag = 0;
+  bool took_first = false;
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
     imask[q] = cmask[q] = 0;
@@ -617,8 +619,8 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
       if (improved[q] && row[q].end > row[q].eps) {
         if (pd.deg == 0) {
           pd.first = row[q].eps; pd.deg = row[q].end - row[q].eps; pd.cost = cand[q]; pd.slot = h[q];
-          pd.nxt = p.arcs[row[q].eps]; pd.have_nxt = true;
           pd_arc = (uint32_t)arc[q];
+          took_first = true;
         } else if (pd.deg2 == 0) {
           pd.first2 = row[q].eps; pd.deg2 = row[q].end - row[q].eps; pd.cost2 = cand[q]; pd.slot2 = h[q];
           pd_arc2 = (uint32_t)arc[q];
@@ -631,6 +633,13 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
       n_imp += __popcll(imask[q]); n_claim += __popcll(cmask[q]);
       n_flag += __popcll(__ballot(improved[q] && (src[q] & LogE::kSrcHasEps)));
     }
+  }
+  // The first arc record of the lane's first pending row is asked for now.  Every lane issues the load (lanes
+  // that took nothing new ask again for what they hold, or for record 0): with no branch around it, nothing
+  // below has to wait for it, and it has arrived by the time the closure starts.
+  if (__ballot(took_first) != 0) {
+    pd.nxt = p.arcs[(took_first || pd.have_nxt) ? pd.first : 0];
+    pd.have_nxt = pd.have_nxt || took_first;
   }
   // (a lane can create a state's entry and still lose the minimum to a lane of another wave
   // that reached the value first: it must get its token index all the same)
