@@ -304,6 +304,16 @@ __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
   return sorted_contains(cx.g_list, cx.n, a);
 }
 
+// A token's arc row as another wave of the workgroup stored it to device memory: read past the L1.
+__device__ __forceinline__ int2 load_row_fe(const int4 *row) {
+  unsigned long long v = __hip_atomic_load((const unsigned long long *)row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_int2((int)(uint32_t)v, (int)(uint32_t)(v >> 32));
+}
+__device__ __forceinline__ int2 load_row_end(const int4 *row) {
+  unsigned long long v = __hip_atomic_load((const unsigned long long *)row + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_int2((int)(uint32_t)v, (int)(uint32_t)(v >> 32));
+}
+
 // Where a frame's working set lives.
 template <bool kLds> struct Mem {
   typedef typename IdxT<kLds>::type idx_t;
@@ -759,15 +769,17 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     pd.deg = go ? row.end - row.eps : 0;
     pd.cost = cand;
     pd.slot = h;
-    pd.have_nxt = false;
+    pd.have_nxt = false;   // (asking for the child's first record here was measured: it costs more than it saves)
   }
 }
 
 // Per-frame scalars and the pruning histogram, set by one wave; a barrier must follow before use.
 // start: the frame is the start of an utterance (its cutoff reference is the start token's cost 0).
-__device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool start, int lane) {
+__device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool start, int lane, bool zero_hist = true) {
+  if (zero_hist) {   // (uniform) a frame that did not fill the histogram leaves it empty
 #pragma unroll
-  for (int k = 0; k < 4; ++k) hist[lane * 4 + k] = 0;
+    for (int k = 0; k < 4; ++k) hist[lane * 4 + k] = 0;
+  }
   if (lane == 0) {
     sh->m_ord = start ? f2ord(0.0f) : 0xFFFFFFFFu;
     sh->best_ord = 0xFFFFFFFFu;   // minimum over closure candidates; the table's minimum is min(m, this)
@@ -784,7 +796,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
                                          uint8_t *owner_maps, int f,
                                          int cur, int2 *bp, int32_t *g_tok_state, bool last_frame) {
   // Lnext: the next frame's log-likelihood row in HBM (null: none).  It starts its way now, waits in
-  // registers during the frame and is parked in the LDS row Lstage right before the frame's last barrier.
+  // registers during the emit phase and is parked in the LDS row Lstage once the emit phase is over.
   constexpr int NW = kBlock / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int co = cur * M.row_cap, no = (cur ^ 1) * M.row_cap;   // row buffer read / built
@@ -795,7 +807,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     const int nb0 = min(kBlock, sh->n_tok);
     const int tpw0 = (nb0 + NW - 1) / NW;
     const int i0 = wave * tpw0 + lane;
-    if (lane < tpw0 && i0 < nb0) fe0 = *(const int2 *)&M.t_row[co + i0];
+    if (lane < tpw0 && i0 < nb0) fe0 = load_row_fe(&M.t_row[co + i0]);
   }
   constexpr int kPre = kBlock >= 1024 ? 6 : 8;
   float pre[kPre];
@@ -850,7 +862,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
           bin = bin > 255 ? 255 : bin;
           alive = bin <= cut;
         }
-        if (alive) { int2 fe = b == 0 ? fe0 : *(const int2 *)&M.t_row[co + i]; first = fe.x; deg = fe.y - first; }
+        if (alive) { int2 fe = b == 0 ? fe0 : load_row_fe(&M.t_row[co + i]); first = fe.x; deg = fe.y - first; }
       }
       if (deg > kBigRowArcs) {
         // a hub-like row: one wave would walk it alone, so park it for the whole workgroup
@@ -956,6 +968,19 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     if ((uint32_t)curv != pd_arc2 || pd.cost2 - m > p.beam) pd.deg2 = 0;
   }
   chase<kLds>(p, M, sh, &sh->n_front[0], cx, Lrow, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
+  // This wave has stored the last token row it will store in this frame (the rare rounds below have full
+  // barriers of their own): once the stores have landed, the barrier makes them the next frame's to read.
+  // The frame's log-likelihood row is no longer needed either (only the emit phase reads it), so the next
+  // one is parked now, by waves that would otherwise just wait for the deepest chain.
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+  if (Lnext) {
+#pragma unroll
+    for (int k = 0; k < kPre; ++k) {
+      int i = tid + k * kBlock;
+      if (i < p.num_pdfs) Lstage[i] = pre[k];
+    }
+    for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lstage[i] = Lnext[i];
+  }
   wg_barrier<kLds>();
   // ... then, rarely, rounds over the change log for what was left flagged there: round r reads the
   // entries logged before it and counts the entries it flags for round r+1 in the other counter
@@ -980,9 +1005,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
             // still this state's value, and not dropped by the emission cutoff
             if ((uint32_t)curv == e.arc && curv != kEmptyVal && !(cost - m > p.beam)) {
               uint32_t idx = ldv<kLds>(&M.hidx[e.h]);
-              int4 rw = M.t_row[no + idx];
-              pd.first = rw.y;
-              pd.deg = rw.z - rw.y;
+              const int eps0 = load_row_fe(&M.t_row[no + idx]).y, end0 = load_row_end(&M.t_row[no + idx]).x;
+              pd.first = eps0;
+              pd.deg = end0 - eps0;
               pd.cost = cost;
               pd.slot = e.h;
             }
@@ -1006,11 +1031,11 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   if (sh->n_rec + sh_n_claim(sh) > p.bp_cap) return kFrameRecordsFull;
 
   // ---- step 5 and bookkeeping: every state's winning update writes the token
+  // (the histogram only matters when more tokens than max_active can survive; the table holds at least as many)
+  const bool hist_need = hist_on && sh_n_claim(sh) > p.max_active;
   {
     const float best = ord2f(umin32(sh->m_ord, sh->best_ord));
     const int base_cur = sh->n_rec, base_prev = sh->frame_base, log_n = sh_log_n(sh);
-    // the histogram only matters when more tokens than max_active can survive; the table holds at least as many
-    const bool hist_need = hist_on && sh_n_claim(sh) > p.max_active;
     int w_surv = 0, w_live = 0;   // per wave, counted with ballots (same-address LDS atomics from many lanes crawl)
     for (int j0 = wave * 64; j0 < log_n; j0 += kBlock) {
       const int j = j0 + lane;
@@ -1065,7 +1090,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   // ---- close the frame
   if (wave == 0) {
     int cut = 255;
-    if (hist_on && sh->n_surv > p.max_active) {
+    if (hist_need && sh->n_surv > p.max_active) {
       // largest bin B whose cumulative count fits max_active (0 if bin 0 alone does not)
       int loc[4], sum = 0;
 #pragma unroll
@@ -1095,17 +1120,9 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       atomicAdd(&sh->a_impr, (unsigned long long)sh_log_n(sh));
       atomicAdd(&sh->a_rounds, (unsigned long long)sh->rounds);
     }
-    frame_init(sh, hist, false, lane);   // for the next frame
+    frame_init(sh, hist, false, lane, hist_need);   // for the next frame
   }
-  if (Lnext) {
-#pragma unroll
-    for (int k = 0; k < kPre; ++k) {
-      int i = tid + k * kBlock;
-      if (i < p.num_pdfs) Lstage[i] = pre[k];
-    }
-    for (int i = tid + kPre * kBlock; i < p.num_pdfs; i += kBlock) Lstage[i] = Lnext[i];
-  }
-  __syncthreads();   // (full: the next frame reads the token rows stored to device memory in this one)
+  wg_barrier<kLds>();   // (back-pointer stores need not have landed: nothing in the next frame reads them)
   return kFrameOk;
 }
 
@@ -1202,6 +1219,8 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the costs over
         for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
         for (int i = tid; i < sh->n_tok; i += kBlock) MG.t_cost[i] = ML.t_cost[i];
+        // (the abandoned attempt has already parked the next frame's log-likelihood row: bring this frame's back)
+        if (p.stage_rows && f >= 0) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = rows.glob[i];
         __syncthreads();
         if (tid < 64) frame_init(sh, hist, f < 0, tid);
         __syncthreads();
