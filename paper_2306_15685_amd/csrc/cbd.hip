@@ -138,8 +138,11 @@ struct cbd_decoder {
   // best-path results: slot 0 serves the synchronous calls, the others asynchronous requests
   static constexpr int kOutSlots = 5;
   struct OutSlot {
-    int32_t *d_arcs = nullptr, *d_words = nullptr, *d_meta = nullptr, *d_snap = nullptr;
+    int32_t *d_arcs = nullptr, *d_snap = nullptr;
     int32_t *h_arcs = nullptr, *h_words = nullptr, *h_meta = nullptr;   // pinned
+    // words and the per-channel header are written by the kernels straight into the pinned host buffers (through
+    // these device-side addresses): no copy, and no copy kernel competing with the decoding for compute units
+    int32_t *dv_words = nullptr, *dv_meta = nullptr;
     int32_t rows = 0, capacity = 0;
     int32_t n = 0, req_capacity = 0;
     bool want_arcs = false, pending = false;
@@ -170,12 +173,14 @@ template <int kBlock> hipError_t set_attr_t(uint32_t lds) {
 hipError_t set_attr(int block, uint32_t lds) {
   if (block == 256) return set_attr_t<256>(lds);
   if (block == 512) return set_attr_t<512>(lds);
+  if (block == 960) return set_attr_t<960>(lds);
   return set_attr_t<1024>(lds);
 }
 
 hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {
   if (d->block == 256) return launch_advance_t<256>(p, grid, d->lds_bytes, d->stream);
   if (d->block == 512) return launch_advance_t<512>(p, grid, d->lds_bytes, d->stream);
+  if (d->block == 960) return launch_advance_t<960>(p, grid, d->lds_bytes, d->stream);
   return launch_advance_t<1024>(p, grid, d->lds_bytes, d->stream);
 }
 
@@ -197,13 +202,11 @@ AdvanceParams base_params(const cbd_decoder *d) {
 
 void free_out_slot(cbd_decoder::OutSlot &o) {
   if (o.d_arcs) (void)hipFree(o.d_arcs);
-  if (o.d_words) (void)hipFree(o.d_words);
-  if (o.d_meta) (void)hipFree(o.d_meta);
   if (o.d_snap) (void)hipFree(o.d_snap);
   if (o.h_arcs) (void)hipHostFree(o.h_arcs);
   if (o.h_words) (void)hipHostFree(o.h_words);
   if (o.h_meta) (void)hipHostFree(o.h_meta);
-  o.d_arcs = o.d_words = o.d_meta = o.d_snap = o.h_arcs = o.h_words = o.h_meta = nullptr;
+  o.d_arcs = o.d_snap = o.h_arcs = o.h_words = o.h_meta = o.dv_words = o.dv_meta = nullptr;
   o.rows = o.capacity = 0;
 }
 
@@ -214,12 +217,12 @@ int32_t size_out_slot(cbd_decoder *d, cbd_decoder::OutSlot &o, int32_t n, int32_
   HIPCHK(hipStreamSynchronize(d->stream));
   free_out_slot(o);
   HIPCHK(dmalloc(&o.d_arcs, (size_t)rows * cap, nullptr));
-  HIPCHK(dmalloc(&o.d_words, (size_t)rows * cap, nullptr));
-  HIPCHK(dmalloc(&o.d_meta, (size_t)rows * 4, nullptr));
   HIPCHK(dmalloc(&o.d_snap, (size_t)rows * cbd::kSnapInts, nullptr));
   HIPCHK(hipHostMalloc((void **)&o.h_arcs, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
   HIPCHK(hipHostMalloc((void **)&o.h_words, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
   HIPCHK(hipHostMalloc((void **)&o.h_meta, sizeof(int32_t) * (size_t)rows * 4, hipHostMallocDefault));
+  HIPCHK(hipHostGetDevicePointer((void **)&o.dv_words, o.h_words, 0));
+  HIPCHK(hipHostGetDevicePointer((void **)&o.dv_meta, o.h_meta, 0));
   o.rows = rows; o.capacity = cap;
   return CBD_OK;
 }
@@ -231,32 +234,28 @@ cbd::BestParams best_params(const cbd_decoder *d, const cbd_decoder::OutSlot &o,
   bp.bp = d->d_bp; bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
   bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
   bp.row_pitch = o.capacity;
-  bp.out_arcs = o.d_arcs; bp.out_words = o.d_words; bp.out_meta = o.d_meta; bp.snap = o.d_snap;
+  bp.out_arcs = o.d_arcs; bp.out_words = o.dv_words; bp.out_meta = o.dv_meta; bp.snap = o.d_snap;
   return bp;
 }
 
-// Copies the header, then only as many columns of the word / arc rows as the longest path needs,
-// through pinned staging on stream `st`, waits, and hands the rows to the caller.
+// Waits for the kernels on stream `st` (headers and words are then in the slot's pinned host buffers), copies as
+// many columns of the arc rows as the longest path needs if arcs are wanted, and hands the rows to the caller.
 int32_t fetch_results(cbd_decoder *d, cbd_decoder::OutSlot &o, hipStream_t st, int32_t n, int32_t capacity,
                       int32_t *words, int32_t *arcs, int32_t *n_words, int32_t *n_arcs, float *cost,
                       int32_t *status) {
   int32_t *meta = o.h_meta;
-  HIPCHK(hipMemcpyAsync(meta, o.d_meta, sizeof(int32_t) * 4 * (size_t)n, hipMemcpyDeviceToHost, st));
-  HIPCHK(hipStreamSynchronize(st));
-  int32_t max_na = 0, max_nw = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    if (meta[(size_t)i * 4] != CBD_OK) continue;
-    max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
-    max_nw = std::max(max_nw, meta[(size_t)i * 4 + 2]);
+  HIPCHK(hipStreamSynchronize(st));   // the kernel has written headers and words into host memory
+  if (arcs) {
+    int32_t max_na = 0;
+    for (int32_t i = 0; i < n; ++i)
+      if (meta[(size_t)i * 4] == CBD_OK) max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
+    const size_t pitch = sizeof(int32_t) * (size_t)o.capacity;
+    if (max_na > 0) {
+      HIPCHK(hipMemcpy2DAsync(o.h_arcs, pitch, o.d_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
+                              hipMemcpyDeviceToHost, st));
+      HIPCHK(hipStreamSynchronize(st));
+    }
   }
-  const size_t pitch = sizeof(int32_t) * (size_t)o.capacity;
-  if (max_nw > 0)
-    HIPCHK(hipMemcpy2DAsync(o.h_words, pitch, o.d_words, pitch, sizeof(int32_t) * (size_t)max_nw, (size_t)n,
-                            hipMemcpyDeviceToHost, st));
-  if (arcs && max_na > 0)
-    HIPCHK(hipMemcpy2DAsync(o.h_arcs, pitch, o.d_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
-                            hipMemcpyDeviceToHost, st));
-  if (max_nw > 0 || (arcs && max_na > 0)) HIPCHK(hipStreamSynchronize(st));
   for (int32_t i = 0; i < n; ++i) {
     status[i] = meta[(size_t)i * 4 + 0];
     n_arcs[i] = meta[(size_t)i * 4 + 1];
@@ -589,7 +588,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     const char *env = getenv("CBD_BLOCK");
     if (env) {
       int b = atoi(env);
-      if (b == 256 || b == 512 || b == 1024) d->block = b;
+      if (b == 256 || b == 512 || b == 960 || b == 1024) d->block = b;
     }
   }
   DCHK(set_attr(d->block, d->lds_bytes));

@@ -542,10 +542,11 @@ __device__ __forceinline__ void pending_clear(Pending &pd) {
   pd.first2 = 0; pd.deg2 = 0; pd.cost2 = 0.0f; pd.slot2 = 0;
 }
 
-constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimum settles
+constexpr int kEmitSlots = 2;  // candidates a lane holds while the batch minimum settles (more cost registers:
+                               // at 2 the kernel fits 120 VGPRs, which leaves room on every SIMD for a wave of another kernel)
 
-// Recombination of the emit phase's candidates, slots r0 and r0 + 1 of each lane (slot r is in use if
-// r * 64 < total).  Same steps as commit(), but taken for both slots together, so that a lane with two candidates
+// Recombination of the emit phase's candidates: the two slots of each lane hold list positions jb + lane and
+// jb + 64 + lane (a slot is in use if its first position lies below total).  Same steps as commit(), but taken for both slots together, so that a lane with two candidates
 // waits once per step, not once per candidate: cutoff against the running minimum; home-slot claims; (rarely)
 // walks after collisions; minima; one counter update for the wave; rows, table indices and log entries.  A lane
 // keeps the first two states it lowered that have epsilon-input arcs as its own pending work for the closure
@@ -553,7 +554,7 @@ constexpr int kEmitSlots = 4;  // candidates a lane holds while the batch minimu
 constexpr int kPair = 2;
 template <bool kLds>
 __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no,
-                                                 int total, int r0, const float *cand, const int *arc,
+                                                 int total, int jb, const float *cand, const int *arc,
                                                  const ArcRec *rec, const uint32_t *srct, uint32_t &n_cand, int lane,
                                                  Pending &pd, uint32_t &pd_arc, uint32_t &pd_arc2) {
   typedef LogT<kLds> LogE;
@@ -564,11 +565,11 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
   unsigned long long any = 0;
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
-    const int r = r0 + q;
-    ok[q] = r * 64 + lane < total && !(cand[q] - mref > p.beam) && !fault;   // for now: "passes and will be tried"
+    const int j0 = jb + q * 64;
+    ok[q] = j0 + lane < total && !(cand[q] - mref > p.beam) && !fault;   // for now: "passes and will be tried"
     claimed[q] = false; improved[q] = false; h[q] = 0; k[q] = 0; src[q] = srct[q];
-    if (r * 64 < total) {
-      unsigned long long pm = __ballot(r * 64 + lane < total && !(cand[q] - mref > p.beam));
+    if (j0 < total) {
+      unsigned long long pm = __ballot(j0 + lane < total && !(cand[q] - mref > p.beam));
       n_cand += (uint32_t)__popcll(pm);
       any |= pm;
     }
@@ -577,7 +578,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
   // home slots
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
-    if ((r0 + q) * 64 < total && ok[q]) {
+    if (jb + q * 64 < total && ok[q]) {
       h[q] = __umulhi((uint32_t)rec[q].dst * 2654435761u, M.slots);
       k[q] = atomicCAS(&M.hkey[h[q]], kEmptyKey, (uint32_t)rec[q].dst);
     }
@@ -585,7 +586,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
   // collisions: walk on (rare)
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
-    if ((r0 + q) * 64 < total) {
+    if (jb + q * 64 < total) {
       const uint32_t state = (uint32_t)rec[q].dst;
       const bool collided = ok[q] && k[q] != kEmptyKey && k[q] != state;
       if (__ballot(collided) != 0) {
@@ -606,7 +607,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
     old[q] = 0;
-    if ((r0 + q) * 64 < total && ok[q]) {
+    if (jb + q * 64 < total && ok[q]) {
       const uint64_t key = ((uint64_t)f2ord(cand[q]) << 32) | (uint32_t)arc[q];
       old[q] = atomicMin((unsigned long long *)&M.hval[h[q]], (unsigned long long)key);
     }
@@ -621,7 +622,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
   for (int q = 0; q < kPair; ++q) {
     imask[q] = cmask[q] = 0;
     row[q].first = row[q].eps = row[q].end = 0;
-    if ((r0 + q) * 64 < total) {
+    if (jb + q * 64 < total) {
       const uint64_t key = ((uint64_t)f2ord(cand[q]) << 32) | (uint32_t)arc[q];
       improved[q] = ok[q] && old[q] > key;
       claimed[q] = ok[q] && k[q] == kEmptyKey;
@@ -664,7 +665,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
   const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
   for (int q = 0; q < kPair; ++q) {
-    if ((r0 + q) * 64 < total) {
+    if (jb + q * 64 < total) {
       if (claimed[q]) {
         int idx = base_tok + __popcll(cmask[q] & below);
         if (idx < M.tok_cap) {
@@ -809,7 +810,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     const int i0 = wave * tpw0 + lane;
     if (lane < tpw0 && i0 < nb0) fe0 = load_row_fe(&M.t_row[co + i0]);
   }
-  constexpr int kPre = kBlock >= 1024 ? 6 : 8;
+  constexpr int kPre = kBlock >= 1024 ? 6 : (kBlock >= 960 ? 7 : 8);
   float pre[kPre];
 #pragma unroll
   for (int k = 0; k < kPre; ++k) {
@@ -881,44 +882,42 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         n_emit += (uint32_t)__builtin_amdgcn_readlane(wb, 63);
         big_arcs = 0;
       }
-      // phase A: fetch up to kEmitSlots arcs per lane, keep the candidates in registers
-      float cand[kEmitSlots];
-      int arc[kEmitSlots];
-      ArcRec rec[kEmitSlots];
-      uint32_t srct[kEmitSlots];
-      uint32_t lmin = 0xFFFFFFFFu;
+      // The wave's arcs are taken kEmitSlots * 64 at a time (one round is the rule).  Phase A fetches the
+      // records and keeps the candidates in registers; phase B cuts and recombines them.  Before the first
+      // round's phase B every wave waits for the others' minima (few doomed candidates reach the table);
+      // later rounds cut against the running minimum, which never lies below the final one.
+      for (int jb = 0; jb == 0 || jb < AL.total; jb += kEmitSlots * 64) {
+        float cand[kEmitSlots];
+        int arc[kEmitSlots];
+        ArcRec rec[kEmitSlots];
+        uint32_t srct[kEmitSlots];
+        uint32_t lmin = 0xFFFFFFFFu;
 #pragma unroll
-      for (int r = 0; r < kEmitSlots; ++r) {
-        int jj = r * 64 + lane;
-        bool act = jj < AL.total;
-        cand[r] = 0.0f; arc[r] = 0; srct[r] = 0;
-        rec[r].dst = 0; rec[r].weight = 0.0f; rec[r].row = 0; rec[r].meta = 0;
-        if (r * 64 < AL.total) {   // uniform
-          int owner = arc_owner(AL, jj, r * 64);
-          arc[r] = __shfl(AL.rel, owner, 64) + jj;
-          float c_own = __shfl(cost, owner, 64);
-          srct[r] = (uint32_t)(tile0 + owner);
-          if (act) {
-            rec[r] = p.arcs[arc[r]];
-            float w = rec[r].weight;
-            if (ctx_contains(cx, arc[r])) w = w + cx.offset;   // Sec. 4.1
-            cand[r] = (c_own + w) - Lrow.at((rec[r].meta & 0xFFFFu) - 1u);
-            uint32_t o = f2ord(cand[r]);
-            lmin = o < lmin ? o : lmin;
+        for (int r = 0; r < kEmitSlots; ++r) {
+          const int j0 = jb + r * 64, jj = j0 + lane;
+          bool act = jj < AL.total;
+          cand[r] = 0.0f; arc[r] = 0; srct[r] = 0;
+          rec[r].dst = 0; rec[r].weight = 0.0f; rec[r].row = 0; rec[r].meta = 0;
+          if (j0 < AL.total) {   // uniform
+            int owner = arc_owner(AL, jj, j0);
+            arc[r] = __shfl(AL.rel, owner, 64) + jj;
+            float c_own = __shfl(cost, owner, 64);
+            srct[r] = (uint32_t)(tile0 + owner);
+            if (act) {
+              rec[r] = p.arcs[arc[r]];
+              float w = rec[r].weight;
+              if (ctx_contains(cx, arc[r])) w = w + cx.offset;   // Sec. 4.1
+              cand[r] = (c_own + w) - Lrow.at((rec[r].meta & 0xFFFFu) - 1u);
+              uint32_t o = f2ord(cand[r]);
+              lmin = o < lmin ? o : lmin;
+            }
           }
         }
+        uint32_t wmin = wave_min_u32(lmin);
+        if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
+        if (jb == 0) wg_barrier<kLds>();   // (every wave passes here exactly once per batch)
+        commit_emit_pair<kLds>(p, M, sh, no, AL.total, jb, cand, arc, rec, srct, n_cand, lane, pd, pd_arc, pd_arc2);
       }
-      uint32_t wmin = wave_min_u32(lmin);
-      if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
-      wg_barrier<kLds>();   // the batch minimum is known: few doomed candidates reach the table
-      // phase B: cutoff, recombination
-      commit_emit_pair<kLds>(p, M, sh, no, AL.total, 0, &cand[0], &arc[0], &rec[0], &srct[0], n_cand, lane, pd, pd_arc, pd_arc2);
-      if (AL.total > 128)
-        commit_emit_pair<kLds>(p, M, sh, no, AL.total, 2, &cand[2], &arc[2], &rec[2], &srct[2], n_cand, lane, pd, pd_arc,
-                               pd_arc2);
-      if (AL.total > kEmitSlots * 64)
-        expand_direct<kLds, true>(p, M, sh, &sh->n_front[0], cx, Lrow, no, AL, kEmitSlots * 64, cost,
-                                  (uint32_t)(tile0 + lane), 0.0f, n_cand, lane);
     }
   }
   wg_barrier<kLds>();

@@ -131,12 +131,14 @@ class Session:
                 t += n
                 if w.partial_every_chunk and t < w.frames:
                     if self.async_partials:
-                        # one request in flight: the walk and copy of chunk k overlap the decoding of chunk k+1
-                        tk = B.cbd_best_paths_begin(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
+                        # one request in flight: the walk and copy of chunk k overlap the decoding of chunk k+1.
+                        # The previous request is collected first: its copies are queued on the side stream and
+                        # must not end up behind the walk that is about to be queued there.
                         if pending is not None:
                             r = B.cbd_best_paths_finish(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
                             if keep_results:
                                 self.partials.append((s, pending[1], r))
+                        tk = B.cbd_best_paths_begin(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
                         pending = (tk, t)
                     else:
                         r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
