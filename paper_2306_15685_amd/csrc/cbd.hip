@@ -146,9 +146,15 @@ struct cbd_decoder {
     int32_t rows = 0, capacity = 0;
     int32_t n = 0, req_capacity = 0;
     bool want_arcs = false, pending = false;
+    int snap_slot = -1;   // ring slot of d_auto_snap the request reads (-1: its own snapshot)
     hipEvent_t done = nullptr;
   } out[kOutSlots];
   hipStream_t side = nullptr;      // walks and copies of asynchronous requests
+  // Best-token snapshots left by the decoding kernel itself, one ring slot per advance / reset call
+  static constexpr int kSnapRing = 8;
+  int32_t *d_auto_snap = nullptr;  // [kSnapRing][C][kSnapInts]
+  int64_t adv_calls = 0;           // advance / reset calls so far
+  std::vector<int32_t> last_list;  // channel list of the latest one (empty: none)
   hipEvent_t snap_ev = nullptr;
   StageRing ids;   // channel lists
   StageRing ctxs;  // context uploads
@@ -267,6 +273,18 @@ int32_t fetch_results(cbd_decoder *d, cbd_decoder::OutSlot &o, hipStream_t st, i
     if (arcs)
       memcpy(arcs + (size_t)i * capacity, o.h_arcs + (size_t)i * o.capacity, sizeof(int32_t) * (size_t)n_arcs[i]);
   }
+  return CBD_OK;
+}
+
+// Gives the coming advance / reset call the next slot of the snapshot ring (the stream first waits for any
+// unfinished request that still reads that slot) and remembers the call's channel list.
+int32_t claim_snapshot_slot(cbd_decoder *d, const int32_t *channels, int32_t n, AdvanceParams *p) {
+  const int s = (int)(d->adv_calls % cbd_decoder::kSnapRing);
+  for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
+    if (d->out[k].pending && d->out[k].snap_slot == s) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
+  p->auto_snap = d->d_auto_snap + (size_t)s * d->C * cbd::kSnapInts;
+  d->last_list.assign(channels, channels + n);
+  d->adv_calls++;
   return CBD_OK;
 }
 
@@ -595,6 +613,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
 
   const size_t C = (size_t)d->C;
   DCHK(dmalloc(&d->d_chan, C, &d->bytes));
+  DCHK(dmalloc(&d->d_auto_snap, (size_t)cbd_decoder::kSnapRing * C * cbd::kSnapInts, &d->bytes));
   DCHK(dmalloc(&d->d_tok_state, C * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_tok_cost, C * d->g_tok_cap, &d->bytes));
   DCHK(dmalloc(&d->d_tok_row, C * 2 * d->g_tok_cap, &d->bytes));
@@ -632,7 +651,7 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
-                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx};
+                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->side) (void)hipStreamSynchronize(d->side);
@@ -669,6 +688,8 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
     if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = nullptr; p.channel_stride = 0; p.n_frames = 0; p.do_reset = 1;
+  rc = claim_snapshot_slot(d, channels, n, &p);
+  if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n));
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
@@ -936,6 +957,8 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   if (rc != CBD_OK) return rc;
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
+  rc = claim_snapshot_slot(d, channels, n_channels, &p);
+  if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n_channels));
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
@@ -968,10 +991,18 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
   for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
     if (!d->out[k].pending) { t = k; break; }
   if (t < 0) return fail(CBD_E_CAPACITY, "best_paths_begin: too many requests in flight (finish one first)");
+  // The decoding kernel leaves each channel's best token behind when it finishes.  A request for the channels
+  // of the latest advance / reset call, in the same order and without final costs, walks from those; any other
+  // request takes its own snapshot on the decode stream first.
+  const bool reuse = !use_final && channels && n > 0 && (size_t)n == d->last_list.size() &&
+                     memcmp(channels, d->last_list.data(), sizeof(int32_t) * (size_t)n) == 0;
   const int32_t *dev = nullptr;
   int slot = 0;
-  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
-  if (rc != CBD_OK) return rc;
+  int32_t rc = CBD_OK;
+  if (!reuse) {
+    rc = stage_channels(d, channels, n, &dev, &slot);
+    if (rc != CBD_OK) return rc;
+  }
   cbd_decoder::OutSlot &o = d->out[t];
   rc = size_out_slot(d, o, n, capacity);
   if (rc != CBD_OK) return rc;
@@ -979,10 +1010,16 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
   if (!d->snap_ev) HIPCHK(hipEventCreateWithFlags(&d->snap_ev, hipEventDisableTiming));
   if (!o.done) HIPCHK(hipEventCreateWithFlags(&o.done, hipEventDisableTiming));
   cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
-  // decode stream: pick the best tokens now, before a later call changes the channels
-  hipLaunchKernelGGL(cbd::best_snapshot_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
-  HIPCHK(hipGetLastError());
-  HIPCHK(d->ids.release(slot, d->stream));
+  if (reuse) {
+    o.snap_slot = (int)((d->adv_calls - 1) % cbd_decoder::kSnapRing);
+    bp.snap = d->d_auto_snap + (size_t)o.snap_slot * d->C * cbd::kSnapInts;
+  } else {
+    o.snap_slot = -1;
+    // decode stream: pick the best tokens now, before a later call changes the channels
+    hipLaunchKernelGGL(cbd::best_snapshot_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
+    HIPCHK(hipGetLastError());
+    HIPCHK(d->ids.release(slot, d->stream));
+  }
   HIPCHK(hipEventRecord(d->snap_ev, d->stream));
   // side stream: the walk reads only records that are already final, so it runs beside later decoding
   HIPCHK(hipStreamWaitEvent(d->side, d->snap_ev, 0));

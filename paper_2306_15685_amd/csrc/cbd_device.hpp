@@ -126,7 +126,10 @@ struct AdvanceParams {
   uint32_t *g_hkey;        // [C][g_slots]
   uint64_t *g_hval;
   uint32_t *g_hidx;
+  int32_t *auto_snap;      // [grid][kSnapInts] or null: where each workgroup leaves its channel's best token when done
 };
+
+constexpr int kSnapInts = 8;   // a best-token snapshot: status, best record, cost bits, records in use, channel
 
 constexpr int kBigRows = 32;      // slots for such rows per frame
 constexpr int kBigRowArcs = 512;  // a row with more arcs than this is shared out over all waves
@@ -1173,7 +1176,13 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     sh->a_frames = sh->a_active = sh->a_emit = sh->a_eps = sh->a_cand = sh->a_impr = sh->a_tokens = sh->a_rounds = 0;
   }
   __syncthreads();
-  if (sh->status != kStatusOk) return;  // uniform: the channel is parked until reset
+  if (sh->status != kStatusOk) {  // uniform: the channel is parked until reset
+    if (p.auto_snap && tid == 0) {
+      int32_t *snap = p.auto_snap + (size_t)blockIdx.x * kSnapInts;
+      snap[0] = sh->status; snap[1] = -1; snap[2] = (int)0xFFFFFFFFu; snap[3] = cs->n_rec; snap[4] = c;
+    }
+    return;
+  }
 
   // context of this call (Sec. 4.3: whichever list is current is the one used)
   Ctx cx;
@@ -1270,6 +1279,41 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
     if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
     cs->slow_frames += sh->a_slow;
+  }
+  // Sec. 1 / 3.2: the partial result is the best current token's sequence.  The workgroup leaves that token
+  // here (arg-min of (cost, arc) over its final table, as the stand-alone snapshot kernel would find it), so a
+  // request for partial results right after this call only has to walk.
+  if (p.auto_snap) {
+    __syncthreads();   // this call's last costs and records are in device memory
+    if (tid < 64) {
+      const int lane = tid;
+      uint64_t bestk = kEmptyVal;
+      int besti = -1;
+      if (status == kStatusOk) {
+        const int n = sh->n_tok, base = sh->frame_base;
+        for (int t = lane; t < n; t += 64) {
+          const float cost = __hip_atomic_load(&MG.t_cost[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (!(cost < __builtin_inff())) continue;   // dropped by the frame cutoff
+          const unsigned long long rec = __hip_atomic_load((const unsigned long long *)&bp[base + t], __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_AGENT);
+          const uint64_t k = ((uint64_t)f2ord(cost) << 32) | (uint32_t)rec;   // low word of a record: its arc
+          if (k < bestk) { bestk = k; besti = t; }
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+          uint64_t ok = (uint64_t)__shfl_xor((long long)bestk, d, 64);
+          int oi = __shfl_xor(besti, d, 64);
+          if (ok < bestk) { bestk = ok; besti = oi; }
+        }
+      }
+      if (lane == 0) {
+        int32_t *snap = p.auto_snap + (size_t)blockIdx.x * kSnapInts;
+        snap[0] = status != kStatusOk ? status : (besti < 0 ? kStatusNoTokens : kStatusOk);
+        snap[1] = besti < 0 ? -1 : sh->frame_base + besti;
+        snap[2] = (int)(uint32_t)(bestk >> 32);
+        snap[3] = sh->n_rec; snap[4] = c;
+      }
+    }
   }
 }
 
@@ -1398,7 +1442,6 @@ struct BestParams {
   int32_t *out_meta;        // [n][4]: status, n_arcs, n_words, cost bits
   int32_t *snap;            // [n][kSnapInts] snapshot taken on the decode stream (two-stage form only)
 };
-constexpr int kSnapInts = 8;   // status, best record, cost bits, records in use, channel
 
 // Best token of a channel's current table (Sec. 1: the current best token sequence is read
 // directly, no lattice).  One wave.  Returns the record index or -1; key receives (cost, arc).

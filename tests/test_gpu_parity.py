@@ -348,6 +348,22 @@ def test_asynchronous_partial_results(torch_cuda):
         for c in range(5):
             orcs[c].reset(); orcs[c].advance(Lh[c, :5])
             GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"after requests ch {c}")
+        # a request for the channels of the latest call walks from the tokens the decoding kernel left behind;
+        # one for other channels, another order or with final costs takes its own snapshot: same answers
+        sub = np.array([3, 0], np.int32)
+        st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, B.cbd_best_paths_begin(dec.dh, sub, False, capacity=200))
+        for i, c in enumerate(sub):
+            GH.assert_best_equal((int(st[i]), wl[i], al[i], float(cost[i])), orcs[c].best_path(False), f"subset ch {c}")
+        st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, B.cbd_best_paths_begin(dec.dh, dec.all, True, capacity=200))
+        for c in range(5):
+            GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), orcs[c].best_path(True), f"finals ch {c}")
+        st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, B.cbd_best_paths_begin(dec.dh, dec.all, False, capacity=200))
+        for c in range(5):
+            GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), orcs[c].best_path(False), f"again ch {c}")
+        # right after a reset the kernel-left token is the start token: empty path at cost 0
+        dec.reset(sub)
+        st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, B.cbd_best_paths_begin(dec.dh, sub, False, capacity=200))
+        assert list(st) == [0, 0] and list(na) == [0, 0] and list(cost) == [0.0, 0.0]
     finally:
         dec.close()
 
