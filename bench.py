@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--context-mode", default="upload", choices=["upload", "pool"],
                     help="upload every segment's lists, or pre-load all of them and switch by id")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-channels", type=int, default=32)
+    ap.add_argument("--cpu-channels", type=int, default=256, help="channels of the workload the CPU checker is timed on")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
                     help="only run a plain device copy of BYTES, ten times (scale for the profiler's HBM counters)")
     args = ap.parse_args()
