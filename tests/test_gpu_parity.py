@@ -422,6 +422,47 @@ def test_context_from_word_sequences(torch_cuda):
         B.cbd_graph_free(gh)
 
 
+@pytest.mark.parametrize("beam,max_active", [(0.0, 0), (1.0e30, 0), (9.0, 1), (9.0, 7)])
+def test_degenerate_beams(torch_cuda, beam, max_active):
+    """Beam 0 (only the best token survives: greedy), a beam nothing exceeds, and max-active limits far below
+    the table size (the histogram cut decides almost everything; with 1 even bin 0 overflows)."""
+    g, L, ctxs, offs = mid_inputs(torch_cuda, C=3, T=20, S=3000, P=40, seed=31, ctx_k=20)
+    s = run_batch(torch_cuda, g, L, ctxs, offs, beam=beam, max_active=max_active, chunks=[1, 9, 10], hash_log2=13)
+    if beam == 0.0:
+        assert s["active_tokens"] <= s["frames"] + 3
+
+
+def test_largest_row_length_and_empty_calls(torch_cuda):
+    """65535 pdfs, the most the arc record's label field can name: the row does not fit LDS and is read from
+    device memory.  Calls with zero frames change nothing."""
+    torch = torch_cuda
+    P = 65535
+    g = synth.make_graph(3000, P, 500, 0.10, seed_stream=(32,))
+    assert int(g.ilabel.max()) > 60000
+    L = synth.make_loglikes(2, 6, P, 4.0, seed_stream=(32,), device="cuda")
+    w = synth.scaled(synth.WORKLOADS["large"], channels=2, ctx_min=5, ctx_max=20, config_id=82)
+    ctxs, offs = synth.make_contexts(w, g)
+    dec = GH.GpuDecoder(g, 2, 14.0, 0, max_frames=6, hash_log2=13)
+    try:
+        orcs = GH.oracle_channels(g, 2, 14.0, 0)
+        Lh = L.cpu().numpy()
+        dec.set_contexts(ctxs, offs)
+        dec.reset()
+        for c in range(2):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset()
+        dec.advance(L, 0, 0)                      # nothing to do
+        for (t0, t1) in [(0, 1), (1, 1), (1, 6)]:
+            dec.advance(L, t0, t1)
+            for c in range(2):
+                orcs[c].advance(Lh[c, t0:t1])
+        for c in range(2):
+            GH.assert_tables_equal(dec.tokens(c), orcs[c].tokens(), f"ch {c}")
+            GH.assert_best_equal(dec.best(c), orcs[c].best_path(), f"ch {c}")
+        assert dec.stats(-1)["frames"] == 12
+    finally:
+        dec.close()
+
+
 def test_channel_subset_and_reuse_after_reset(torch_cuda):
     """A subset of channels advances while the others wait; a channel reset for a second utterance
     gives the same result as a fresh decoder."""
