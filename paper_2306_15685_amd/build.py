@@ -33,5 +33,30 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def resource_usage() -> dict:
+    """Compiles the device code once more with the compiler's resource remarks on and returns, per kernel,
+    {"vgprs", "vgpr_spill", "scratch", "lds"} (name = demangled-ish substring of the kernel symbol)."""
+    import re
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-Wall", "-Wno-unused-result")]
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [hipcc, *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage",
+               "-o", os.path.join(tmp, "dev.o"), SRC]
+        out = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    usage, cur = {}, None
+    for line in out.splitlines():
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            cur = usage.setdefault(m.group(1), {})
+            continue
+        for key, pat in (("vgprs", r"remark:\s+VGPRs: (\d+)"), ("vgpr_spill", r"VGPRs Spill: (\d+)"),
+                         ("scratch", r"ScratchSize \[bytes/lane\]: (\d+)"), ("lds", r"LDS Size \[bytes/block\]: (\d+)")):
+            m = re.search(pat, line)
+            if m and cur is not None:
+                cur[key] = int(m.group(1))
+    return usage
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))

@@ -492,12 +492,12 @@ __device__ __forceinline__ void commit(const AdvanceParams &p, const Mem<kLds> &
   record<kLds>(M, sh, front, no, improved, claimed, (uint32_t)a, h, src, row, lane);
 }
 
-// Expand positions [j_begin, total) of the wave's arc list, one lane per arc, committing
-// each candidate at once (closure rounds, and the rare emit overflow beyond the register batch).
-template <bool kLds, bool kEmit>
+// Expand positions [j_begin, total) of the wave's arc list of epsilon-input arcs, one lane per arc, committing
+// each candidate at once and leaving the children flagged in the change log (closure levels of more than 64 arcs).
+template <bool kLds>
 __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
-                                              const Ctx &cx, const Rows &Lrow, int no, const ArcList &AL, int j_begin,
-                                              float cost, uint32_t src_tag, float m_fixed, uint32_t &n_cand, int lane) {
+                                              const Ctx &cx, int no, const ArcList &AL, int j_begin, float cost,
+                                              uint32_t src_tag, float m_fixed, uint32_t &n_cand, int lane) {
   for (int j0 = j_begin; j0 < AL.total; j0 += 64) {
     int jj = j0 + lane;
     bool act = jj < AL.total;
@@ -512,15 +512,10 @@ __device__ __forceinline__ void expand_direct(const AdvanceParams &p, const Mem<
       rec = p.arcs[a];
       float w = rec.weight;
       if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1: boosted weight = weight + discount
-      if (kEmit) cand = (c_own + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u);
-      else cand = c_own + w;
-    }
-    if (kEmit) {
-      uint32_t wmin = wave_min_u32(act ? f2ord(cand) : 0xFFFFFFFFu);
-      if (lane == 0) atomicMin(&sh->m_ord, wmin);
+      cand = c_own + w;
     }
     bool imp; uint32_t hh; RowInfo rr;
-    commit<kLds, kEmit>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane, true, fault, imp, hh, rr);
+    commit<kLds, false>(p, M, sh, front, no, act, cand, a, rec, s_own, m_fixed, n_cand, lane, true, fault, imp, hh, rr);
   }
 }
 
@@ -548,15 +543,14 @@ __device__ __forceinline__ void pending_clear(Pending &pd) {
 constexpr int kEmitSlots = 2;  // candidates a lane holds while the batch minimum settles (more cost registers:
                                // at 2 the kernel fits 120 VGPRs, which leaves room on every SIMD for a wave of another kernel)
 
-// Recombination of the emit phase's candidates: the two slots of each lane hold list positions jb + lane and
-// jb + 64 + lane (a slot is in use if its first position lies below total).  Same steps as commit(), but taken for both slots together, so that a lane with two candidates
+// Recombination of the emit phase's candidates: kPair (1 or 2) slots of each lane, holding list positions
+// jb + lane and jb + 64 + lane (a slot is in use if its first position lies below total).  Same steps as commit(), but taken for both slots together, so that a lane with two candidates
 // waits once per step, not once per candidate: cutoff against the running minimum; home-slot claims; (rarely)
 // walks after collisions; minima; one counter update for the wave; rows, table indices and log entries.  A lane
 // keeps the first two states it lowered that have epsilon-input arcs as its own pending work for the closure
 // (asking for the first one's arc record right away); any further ones are flagged in the change log.
-constexpr int kPair = 2;
-template <bool kLds>
-__device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no,
+template <bool kLds, int kPair>
+__device__ __forceinline__ void commit_emit_n(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int no,
                                                  int total, int jb, const float *cand, const int *arc,
                                                  const ArcRec *rec, const uint32_t *srct, uint32_t &n_cand, int lane,
                                                  Pending &pd, uint32_t &pd_arc, uint32_t &pd_arc2) {
@@ -702,7 +696,7 @@ __device__ __forceinline__ void commit_emit_pair(const AdvanceParams &p, const M
 // for the next round.  No barrier anywhere: a wave follows the chains it starts.
 template <bool kLds>
 __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M, Shared *sh, int32_t *front,
-                                      const Ctx &cx, const Rows &Lrow, int no, uint8_t *owner_map, Pending &pd, float m,
+                                      const Ctx &cx, int no, uint8_t *owner_map, Pending &pd, float m,
                                       uint32_t &n_eps, uint32_t &n_cand, int &levels, int lane) {
   typedef LogT<kLds> LogE;
   while (true) {
@@ -749,7 +743,7 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     n_eps += (uint32_t)AL.total;
     const uint32_t tag = pd.slot | LogE::kSrcEps;
     if (AL.total > 64) {
-      expand_direct<kLds, false>(p, M, sh, front, cx, Lrow, no, AL, 0, pd.cost, tag, m, n_cand, lane);
+      expand_direct<kLds>(p, M, sh, front, cx, no, AL, 0, pd.cost, tag, m, n_cand, lane);
       pd.deg = 0;
       continue;   // lanes with a second state still have it to do
     }
@@ -919,7 +913,12 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
         uint32_t wmin = wave_min_u32(lmin);
         if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
         if (jb == 0) wg_barrier<kLds>();   // (every wave passes here exactly once per batch)
-        commit_emit_pair<kLds>(p, M, sh, no, AL.total, jb, cand, arc, rec, srct, n_cand, lane, pd, pd_arc, pd_arc2);
+        commit_emit_n<kLds, 2>(p, M, sh, no, AL.total, jb, cand, arc, rec, srct, n_cand, lane, pd, pd_arc, pd_arc2);
+        if constexpr (kEmitSlots > 2) {
+          if (jb + 128 < AL.total)
+            commit_emit_n<kLds, kEmitSlots - 2>(p, M, sh, no, AL.total, jb + 128, &cand[2], &arc[2], &rec[2], &srct[2], n_cand,
+                                                lane, pd, pd_arc, pd_arc2);
+        }
       }
     }
   }
@@ -969,7 +968,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
     uint64_t curv = ldv<kLds>(&M.hval[pd.slot2]);
     if ((uint32_t)curv != pd_arc2 || pd.cost2 - m > p.beam) pd.deg2 = 0;
   }
-  chase<kLds>(p, M, sh, &sh->n_front[0], cx, Lrow, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
+  chase<kLds>(p, M, sh, &sh->n_front[0], cx, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
   // This wave has stored the last token row it will store in this frame (the rare rounds below have full
   // barriers of their own): once the stores have landed, the barrier makes them the next frame's to read.
   // The frame's log-likelihood row is no longer needed either (only the emit phase reads it), so the next
@@ -1015,7 +1014,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
             }
           }
         }
-        chase<kLds>(p, M, sh, front, cx, Lrow, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
+        chase<kLds>(p, M, sh, front, cx, no, owner_map, pd, m, n_eps, n_cand, levels, lane);
       }
       wg_barrier<kLds>();
       if (tid == 0) {

@@ -69,3 +69,17 @@ def test_product_code_does_not_touch_the_checker():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f"{f} mentions the checker"
+
+
+def test_decoding_kernel_leaves_registers_for_a_second_kernel():
+    """The 1024-thread decoding kernel keeps four waves on every SIMD.  At 120 vector registers or fewer they leave
+    32 of the 512 per lane free, enough for a wave of the partial-result walk to run beside a decoding workgroup;
+    above that each workgroup of a launch waits for the walk wave on its compute unit (measured: +15 % per launch).
+    No register may spill either."""
+    from paper_2306_15685_amd import build
+    usage = build.resource_usage()
+    k1024 = [v for k, v in usage.items() if "advance_kernelILi1024E" in k]
+    assert len(k1024) == 1
+    assert k1024[0]["vgprs"] <= 120 and k1024[0]["vgpr_spill"] == 0 and k1024[0]["scratch"] == 0
+    walk = [v for k, v in usage.items() if "best_walk_kernel" in k]
+    assert len(walk) == 1 and walk[0]["vgprs"] <= 32
