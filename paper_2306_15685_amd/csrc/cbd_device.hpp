@@ -699,6 +699,7 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
                                       const Ctx &cx, int no, uint8_t *owner_map, Pending &pd, float m,
                                       uint32_t &n_eps, uint32_t &n_cand, int &levels, int lane) {
   typedef LogT<kLds> LogE;
+  int depth = 0;   // levels of this call: bounds the length of the chains it follows (a lane's second chain included)
   while (true) {
     if (pd.deg == 0 && pd.deg2 > 0) {
       pd.first = pd.first2; pd.deg = pd.deg2; pd.cost = pd.cost2; pd.slot = pd.slot2; pd.have_nxt = false;
@@ -707,7 +708,8 @@ __device__ __forceinline__ void chase(const AdvanceParams &p, const Mem<kLds> &M
     unsigned long long pend = __ballot(pd.deg > 0);
     if (pend == 0) return;
     const int fault = load_fault(sh);   // asked for here, back by the time the arcs have arrived
-    if (++levels > p.max_eps_iters) {
+    levels = max(levels, ++depth);
+    if (depth > p.max_eps_iters) {
       if (lane == 0) sh->diverged = 1;
       pd.deg = 0;
       return;
@@ -959,7 +961,7 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
 
   // ---- step 4: epsilon closure.  First every lane follows the state it kept from the emit phase,
   // provided that is still the state's value and survived the cutoff ...
-  int levels = 0;   // passes this wave has made (bounds the closure depth)
+  int levels = 0;   // deepest run of closure levels this wave has made in one go
   if (pd.deg > 0) {
     uint64_t curv = ldv<kLds>(&M.hval[pd.slot]);
     if ((uint32_t)curv != pd_arc || pd.cost - m > p.beam) pd.deg = 0;
