@@ -26,7 +26,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # what the same counter reads for a plain 1 GiB device copy (2.000 and 1.000); the runs and their commands are
 # summarised under profiles/.  Counters cannot be read from inside this process, so the figure is carried here for the
 # default configuration of the workloads that were profiled.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"large": 1199013259, "stress": 16781844107}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {"large": 1199013259, "stress": 16781844107, "dynamic": 4625000000,
+                                     "e2e": 31783300000}
 
 
 def log(*a):
