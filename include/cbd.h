@@ -191,10 +191,11 @@ int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_
                       int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost);
 
 /*
- * The same for many channels with one kernel and one copy.  Row i of words /
- * arcs ([n][capacity], HOST) belongs to channels[i]; status[i] (HOST [n])
- * receives that channel's result code; the function itself fails only for
- * invalid arguments or HIP errors.
+ * The same for many channels with one kernel, which writes words and counts
+ * straight into pinned host memory of the library's (arcs, if wanted, come by
+ * one copy).  Row i of words / arcs ([n][capacity], HOST) belongs to
+ * channels[i]; status[i] (HOST [n]) receives that channel's result code; the
+ * function itself fails only for invalid arguments or HIP errors.
  */
 int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
                        int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
@@ -202,9 +203,10 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
 
 /*
  * The same in two steps, so that intermediate results leave the GPU without interrupting the
- * decoding (Sec. 2.2).  cbd_best_paths_begin notes the best tokens on the decoder's stream and
- * enqueues the path walks and the copy on a stream of the library's own; it returns at once with a
- * ticket.  Calls enqueued afterwards (cbd_advance, context changes) do not disturb the request;
+ * decoding (Sec. 2.2).  cbd_best_paths_begin notes the best tokens on the decoder's stream (for the
+ * channel list of the latest cbd_advance / cbd_reset_channels call and use_final = 0 the decoding
+ * kernel has left them behind already) and enqueues the path walks on a stream of the library's own;
+ * it returns at once with a ticket.  Calls enqueued afterwards (cbd_advance, context changes) do not disturb the request;
  * cbd_reset_channels waits on the device for outstanding walks.  cbd_best_paths_finish waits for the
  * request and fills the caller's arrays exactly like cbd_best_paths (same capacity as at begin; arcs
  * only if want_arcs was set).  At most four requests may be in flight (CBD_E_CAPACITY).
@@ -230,7 +232,7 @@ typedef struct cbd_stats {
   int64_t candidates;     /* candidates that passed the cutoff and reached the state table */
   int64_t improvements;   /* table updates (change-log entries) */
   int64_t tokens;         /* sum over frames of the table size */
-  int64_t eps_rounds;     /* closure rounds */
+  int64_t eps_rounds;     /* per frame the longest run of closure levels any wave made, summed over frames */
   int64_t records;        /* back-pointer records in use */
   int64_t slow_frames;    /* frames decoded with the device-memory tables */
   int32_t status;         /* sticky cbd_status of the channel */
