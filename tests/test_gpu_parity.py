@@ -253,6 +253,19 @@ def test_context_lists_prepared_on_device_and_on_host(torch_cuda):
             dec.close()
 
 
+@pytest.mark.parametrize("lookup_mode", [0, 1])
+def test_context_lists_longer_than_the_lds_copy(torch_cuda, lookup_mode):
+    """Lists of more than 2,048 arcs stay in device memory and are searched there (Sec. 4.2's binary search, with
+    and without the bitmap in front); 5,000 and 8,192 entries also reach the largest size the device sorts."""
+    torch = torch_cuda
+    g, L, _, _ = mid_inputs(torch, C=3, T=24, seed=16)
+    rng = np.random.default_rng(16)
+    ctxs = [rng.choice(g.num_arcs, size=k, replace=False).astype(np.int32) for k in (5000, 8192, 2049)]
+    offs = np.array([-4.0, -1.5, -6.0], np.float32)
+    s = run_batch(torch, g, L, ctxs, offs, beam=12.0, max_active=0, chunks=[5, 19], lookup_mode=lookup_mode)
+    assert s["status"] == 0
+
+
 def test_context_swap_mid_utterance_and_finals(torch_cuda):
     """Contexts replaced between chunks without a reset (Sec. 4.3); final costs pick the end token."""
     torch = torch_cuda
