@@ -264,6 +264,10 @@ def test_context_lists_longer_than_the_lds_copy(torch_cuda, lookup_mode):
     offs = np.array([-4.0, -1.5, -6.0], np.float32)
     s = run_batch(torch, g, L, ctxs, offs, beam=12.0, max_active=0, chunks=[5, 19], lookup_mode=lookup_mode)
     assert s["status"] == 0
+    # one list beyond that size: the whole upload is then prepared on the host
+    ctxs[1] = rng.choice(g.num_arcs, size=10000, replace=False).astype(np.int32)
+    s = run_batch(torch, g, L, ctxs, offs, beam=12.0, max_active=0, chunks=[24], lookup_mode=lookup_mode)
+    assert s["status"] == 0
 
 
 def test_context_swap_mid_utterance_and_finals(torch_cuda):
@@ -474,6 +478,40 @@ def test_largest_row_length_and_empty_calls(torch_cuda):
         assert dec.stats(-1)["frames"] == 12
     finally:
         dec.close()
+
+
+def test_two_decoders_share_one_graph(torch_cuda):
+    """The graph is immutable and shareable: two decoders with different beams and contexts, calls interleaved
+    on one stream."""
+    torch = torch_cuda
+    g, L, ctxs, offs = mid_inputs(torch, C=2, T=30, seed=19)
+    Lh = L.cpu().numpy()
+    gh = B.cbd_graph_load(g.num_states, g.num_pdfs, g.start_state, g.row_offsets, g.dst, g.ilabel, g.olabel, g.weight,
+                          g.final_cost)
+    decs = [GH.GpuDecoder(g, 2, beam, 0, max_frames=30, graph_handle=gh) for beam in (11.0, 14.0)]
+    try:
+        og = OracleGraph.from_graph(g)
+        orcs = [GH.oracle_channels(g, 2, beam, 0, og=og) for beam in (11.0, 14.0)]
+        for k, dec in enumerate(decs):
+            lists = ctxs if k == 0 else ctxs[::-1]
+            o = offs if k == 0 else offs[::-1].copy()
+            dec.set_contexts(lists, o)
+            dec.reset()
+            for c in range(2):
+                orcs[k][c].set_context(lists[c], o[c]); orcs[k][c].reset()
+        for (t0, t1) in [(0, 7), (7, 18), (18, 30)]:
+            for k, dec in enumerate(decs):
+                dec.advance(L, t0, t1)
+                for c in range(2):
+                    orcs[k][c].advance(Lh[c, t0:t1])
+        for k, dec in enumerate(decs):
+            for c in range(2):
+                GH.assert_tables_equal(dec.tokens(c), orcs[k][c].tokens(), f"decoder {k} ch {c}")
+                GH.assert_best_equal(dec.best(c), orcs[k][c].best_path(), f"decoder {k} ch {c}")
+    finally:
+        for dec in decs:
+            dec.close()
+        B.cbd_graph_free(gh)
 
 
 def test_channel_subset_and_reuse_after_reset(torch_cuda):
