@@ -86,6 +86,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "dynamic", "stress", "e2e"])
     ap.add_argument("--channels", type=int, default=0, help="override the channel count (smaller trial runs)")
+    ap.add_argument("--frames", type=int, default=0, help="override the utterance length in frames")
+    ap.add_argument("--chunk", type=int, default=0, help="override the frames per advance call")
+    ap.add_argument("--compact-records-above", type=int, default=0,
+                    help="compact a channel's back-pointer records once it holds more than this many new ones")
+    ap.add_argument("--record-frames", type=int, default=0,
+                    help="size the back-pointer buffer for this many frames (default: the utterance)")
     ap.add_argument("--hash-log2", type=int, default=0)
     ap.add_argument("--table-location", type=int, default=0)
     ap.add_argument("--lds-token-cap", type=int, default=0)
@@ -125,6 +131,10 @@ def main():
         w = synth.scaled(w, channels=args.channels)
     if args.lookup_mode >= 0:
         w = synth.scaled(w, lookup_mode=args.lookup_mode)
+    if args.frames:
+        w = synth.scaled(w, frames=args.frames)
+    if args.chunk:
+        w = synth.scaled(w, chunk=args.chunk)
     t0 = time.perf_counter()
     inp = runner.make_inputs(w)
     torch.cuda.synchronize()
@@ -132,7 +142,8 @@ def main():
         f"{w.segments} x {w.frames} frames x {w.num_pdfs} pdfs in {time.perf_counter() - t0:.1f} s")
     sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
                           biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
-                          async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu)
+                          async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu,
+                          compact_records_above=args.compact_records_above, record_frames=args.record_frames)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -169,7 +180,8 @@ def main():
 
     default_cfg = (not args.unbiased and args.context_mode == "upload" and not args.channels and not args.hash_log2
                    and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu
-                   and args.lookup_mode < 0 and not args.sync_partials)
+                   and args.lookup_mode < 0 and not args.sync_partials and not args.frames and not args.chunk
+                   and not args.compact_records_above and not args.record_frames)
     traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name) if default_cfg else None
 
     out = {
@@ -182,7 +194,8 @@ def main():
                    "beam": w.beam, "max_active": w.max_active, "biased": not args.unbiased,
                    "context_mode": args.context_mode, "async_partials": not args.sync_partials,
                    "lookup_mode": w.lookup_mode, "lds_token_cap": info["lds_token_cap"],
-                   "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"]},
+                   "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"],
+                   "compact_records_above": args.compact_records_above, "device_bytes": info["device_bytes"]},
         "arcs_per_s": arcs / (wall / args.steps),
         "frames_per_s": w.channels * w.segments * w.frames / (wall / args.steps),
         "tokens_per_frame": st["tokens"] / max(st["frames"], 1),

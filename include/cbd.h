@@ -117,6 +117,10 @@ typedef struct cbd_config {
   int32_t workgroups_per_cu;  /* channels decoded side by side on one compute unit (they share its LDS, so each
                                  gets a smaller table): 1, 2 or 4; 0 = chosen by the library (1 while the decoder has
                                  no more channels than the device has compute units, else 2) */
+  int32_t compact_records_above; /* 0 = records are only compacted on request (cbd_compact_records); N > 0 = every
+                                 cbd_advance call first compacts those of its channels that hold more than N records
+                                 above the part their paths share, and with them (so that the call is held up once,
+                                 not once per channel) those that hold more than N / 2 */
 } cbd_config;
 
 /*
@@ -179,6 +183,20 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
                     int64_t channel_stride, int32_t n_frames);
 
 /*
+ * Drops, on the listed channels (HOST, n entries, no duplicates), the back-pointer records that no token of
+ * the current frame has on its path, and renumbers the rest.  Results are read off the best current token's
+ * sequence only (Sec. 1, Sec. 3.2), so nothing a later cbd_best_path* call returns changes; what changes is
+ * the room left: an utterance as long as the 3-minute recordings of Sec. 5.3, or an endless stream, then
+ * needs a buffer (max_frames x records_per_frame) for the stretch between two compactions only, plus what
+ * the compactions keep.  Channels that have written at most min_new_records (>= 0) records since their last
+ * compaction are left alone, as are channels in an error state.  Records kept by one compaction are never
+ * examined again by a later one, so the cost of a call follows the frames since the last one, not the
+ * length of the utterance.  Enqueues only; the stream first waits for unfinished cbd_best_paths_begin
+ * requests (their walks read the records).  CBD_E_INVALID for a bad channel list or a negative threshold.
+ */
+int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t min_new_records);
+
+/*
  * Best token of the channel's current frame and its back-pointer path (the
  * partial hypothesis of Sec. 1; with use_final != 0 the state's final cost is
  * added before the minimum is taken).  words: HOST [capacity] word ids in time
@@ -235,9 +253,22 @@ typedef struct cbd_stats {
   int64_t eps_rounds;     /* per frame the longest run of closure levels any wave made, summed over frames */
   int64_t records;        /* back-pointer records in use */
   int64_t slow_frames;    /* frames decoded with the device-memory tables */
+  int64_t records_dropped; /* back-pointer records removed by compactions */
+  int32_t compactions;    /* compactions that ran */
   int32_t status;         /* sticky cbd_status of the channel */
   int32_t max_tokens;     /* largest table so far */
 } cbd_stats;
+
+/*
+ * Diagnostic: the back-pointer records of one channel as they stand (Sec. 1: the token sequences partial
+ * results are read from).  Record i is (arcs[i], prev[i]): the arc that produced the token (caller's
+ * numbering; -1 for the start token) and the record of the token it came from (-1: none).  The tokens
+ * of the current frame are records [*frame_base, *n_records); records below *kept_base survived a
+ * compaction.  arcs, prev: HOST [capacity], or NULL to ask for the sizes only; CBD_E_BUFFER if capacity
+ * is too small (*n_records = needed size).  Synchronises.
+ */
+int32_t cbd_get_records(cbd_decoder *d, int32_t channel, int32_t *arcs, int32_t *prev, int32_t capacity,
+                        int32_t *n_records, int32_t *frame_base, int32_t *kept_base);
 
 /* Counters of one channel since its last reset (channel >= 0) or summed over all (-1; status = first error).
  * Synchronises. */

@@ -21,8 +21,8 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_context_from_words", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
-    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_get_tokens",
-    "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
+    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_compact_records", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_get_tokens",
+    "cbd_get_records", "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
 
 
@@ -38,14 +38,16 @@ class cbd_config(C.Structure):
                 ("max_frames", C.c_int32), ("max_context_arcs", C.c_int32), ("lookup_mode", C.c_int32),
                 ("hash_capacity_log2", C.c_int32), ("max_eps_iters", C.c_int32),
                 ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32),
-                ("max_pool_contexts", C.c_int32), ("workgroups_per_cu", C.c_int32)]
+                ("max_pool_contexts", C.c_int32), ("workgroups_per_cu", C.c_int32),
+                ("compact_records_above", C.c_int32)]
 
 
 class cbd_stats(C.Structure):
     _fields_ = [("frames", C.c_int64), ("active_tokens", C.c_int64), ("emit_arcs", C.c_int64),
                 ("eps_arcs", C.c_int64), ("candidates", C.c_int64), ("improvements", C.c_int64),
                 ("tokens", C.c_int64), ("eps_rounds", C.c_int64), ("records", C.c_int64),
-                ("slow_frames", C.c_int64), ("status", C.c_int32), ("max_tokens", C.c_int32)]
+                ("slow_frames", C.c_int64), ("records_dropped", C.c_int64), ("compactions", C.c_int32),
+                ("status", C.c_int32), ("max_tokens", C.c_int32)]
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
@@ -88,6 +90,8 @@ def lib():
     L.cbd_use_contexts.argtypes = [vp, vp, vp, i32]
     L.cbd_advance.restype = i32
     L.cbd_advance.argtypes = [vp, vp, i32, vp, i64, i32]
+    L.cbd_compact_records.restype = i32
+    L.cbd_compact_records.argtypes = [vp, vp, i32, i32]
     L.cbd_best_path.restype = i32
     L.cbd_best_path.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp]
     L.cbd_best_paths.restype = i32
@@ -98,6 +102,8 @@ def lib():
     L.cbd_best_paths_finish.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     L.cbd_get_tokens.restype = i32
     L.cbd_get_tokens.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    L.cbd_get_records.restype = i32
+    L.cbd_get_records.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp]
     L.cbd_get_stats.restype = i32
     L.cbd_get_stats.argtypes = [vp, i32, C.POINTER(cbd_stats)]
     L.cbd_decoder_info.restype = i32
@@ -170,10 +176,12 @@ def cbd_context_from_words(g, sequences) -> np.ndarray:
 
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,
                        hash_capacity_log2=14, max_eps_iters=0, records_per_frame=0, table_location=0,
-                       lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, hip_stream=0):
+                       lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, compact_records_above=0,
+                       hip_stream=0):
     cfg = cbd_config(int(num_channels), float(beam), int(max_active), int(max_frames), int(max_context_arcs),
                      int(lookup_mode), int(hash_capacity_log2), int(max_eps_iters), int(records_per_frame),
-                     int(table_location), int(lds_token_cap), int(max_pool_contexts), int(workgroups_per_cu))
+                     int(table_location), int(lds_token_cap), int(max_pool_contexts), int(workgroups_per_cu),
+                     int(compact_records_above))
     h = C.c_void_p()
     _check(lib().cbd_decoder_create(g, C.byref(cfg), C.c_void_p(int(hip_stream)), C.byref(h)), "cbd_decoder_create")
     return h
@@ -235,6 +243,11 @@ def cbd_advance(d, channels, loglikes_ptr: int, channel_stride: int, n_frames: i
     ch = _i32(channels)
     _check(lib().cbd_advance(d, _p(ch), int(ch.size), C.c_void_p(int(loglikes_ptr)), int(channel_stride),
                              int(n_frames)), "cbd_advance")
+
+
+def cbd_compact_records(d, channels, min_new_records=0):
+    ch = _i32(channels)
+    _check(lib().cbd_compact_records(d, _p(ch), int(ch.size), int(min_new_records)), "cbd_compact_records")
 
 
 def cbd_best_path(d, channel, use_final=False, capacity=4096) -> Tuple[int, np.ndarray, np.ndarray, float]:
@@ -329,6 +342,18 @@ def cbd_get_tokens(d, channel):
     st, co, ar = st[:k], co[:k], ar[:k]
     o = np.argsort(st, kind="stable")
     return rc, st[o], co[o], ar[o]
+
+
+def cbd_get_records(d, channel):
+    """-> (arcs, prev, frame_base, kept_base): the channel's back-pointer records."""
+    n, fb, kb = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    _check(lib().cbd_get_records(d, int(channel), None, None, 0, C.byref(n), C.byref(fb), C.byref(kb)),
+           "cbd_get_records")
+    arcs = np.zeros(max(n.value, 1), np.int32)
+    prev = np.zeros(max(n.value, 1), np.int32)
+    _check(lib().cbd_get_records(d, int(channel), _p(arcs), _p(prev), int(arcs.size), C.byref(n), C.byref(fb),
+                                 C.byref(kb)), "cbd_get_records")
+    return arcs[:n.value], prev[:n.value], fb.value, kb.value
 
 
 def cbd_get_stats(d, channel=-1) -> dict:

@@ -135,6 +135,10 @@ struct cbd_decoder {
   uint32_t *d_hkey = nullptr;
   uint64_t *d_hval = nullptr;
   uint32_t *d_hidx = nullptr;
+  // record compaction: one bit per back-pointer record, and two counts per bitmap word (allocated on first use)
+  uint32_t *d_gc_mark = nullptr, *d_gc_prefix = nullptr;
+  int32_t *d_gc_cross = nullptr, *d_gc_due = nullptr;
+  int32_t gc_words = 0;
   // best-path results: slot 0 serves the synchronous calls, the others asynchronous requests
   static constexpr int kOutSlots = 5;
   struct OutSlot {
@@ -302,6 +306,33 @@ int32_t stage_channels(cbd_decoder *d, const int32_t *channels, int32_t n, const
   memcpy(d->ids.host[*slot], channels, sizeof(int32_t) * (size_t)n);
   HIPCHK(d->ids.upload(*slot, sizeof(int32_t) * (size_t)n, d->stream));
   *dev = (const int32_t *)d->ids.dev[*slot];
+  return CBD_OK;
+}
+
+// Enqueues the record compaction for the channels in `dev` (a staged list of n).  It renumbers records, so the
+// stream first waits for every unfinished asynchronous walk, and snapshots left by earlier calls are retired.
+// together: a channel half-way to min_new joins in when another channel of the list is due.
+int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_t min_new, bool together) {
+  d->gc_words = (d->bp_cap + 31) / 32;
+  if (!d->d_gc_mark) HIPCHK(dmalloc(&d->d_gc_mark, (size_t)d->C * d->gc_words, &d->bytes));
+  if (!d->d_gc_prefix) HIPCHK(dmalloc(&d->d_gc_prefix, (size_t)d->C * d->gc_words, &d->bytes));
+  if (!d->d_gc_cross) HIPCHK(dmalloc(&d->d_gc_cross, (size_t)d->C * (d->gc_words + 2), &d->bytes));
+  if (!d->d_gc_due) HIPCHK(dmalloc(&d->d_gc_due, 1, &d->bytes));
+  for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
+    if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
+  d->last_list.clear();
+  cbd::CompactParams cp{};
+  cp.chan = d->d_chan; cp.chan_ids = dev; cp.bp = d->d_bp; cp.tok_cost = d->d_tok_cost;
+  cp.mark = d->d_gc_mark; cp.prefix = d->d_gc_prefix; cp.cross = d->d_gc_cross;
+  cp.bp_cap = d->bp_cap; cp.tok_cap = d->g_tok_cap; cp.mark_words = d->gc_words; cp.min_new = min_new;
+  if (together) {
+    hipLaunchKernelGGL(cbd::compact_due_kernel, dim3(1), dim3(256), 0, d->stream, d->d_chan, dev, n, min_new,
+                       d->d_gc_due);
+    HIPCHK(hipGetLastError());
+    cp.any_due = d->d_gc_due;
+  }
+  hipLaunchKernelGGL(cbd::compact_records_kernel, dim3((unsigned)n), dim3(cbd::kCompactBlock), 0, d->stream, cp);
+  HIPCHK(hipGetLastError());
   return CBD_OK;
 }
 
@@ -536,6 +567,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->lds_token_cap < 0) return fail(CBD_E_INVALID, "decoder: lds_token_cap");
   if (cfg->max_pool_contexts < 0) return fail(CBD_E_INVALID, "decoder: max_pool_contexts");
   if (cfg->workgroups_per_cu < 0 || cfg->workgroups_per_cu > 4) return fail(CBD_E_INVALID, "decoder: workgroups_per_cu");
+  if (cfg->compact_records_above < 0) return fail(CBD_E_INVALID, "decoder: compact_records_above");
   cbd_decoder *d = new (std::nothrow) cbd_decoder();
   if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
   d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
@@ -651,7 +683,8 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
-                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap};
+                  d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
+                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_gc_due};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->side) (void)hipStreamSynchronize(d->side);
@@ -955,11 +988,28 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n_channels, &dev, &slot);
   if (rc != CBD_OK) return rc;
+  if (d->cfg.compact_records_above > 0) {
+    rc = enqueue_compaction(d, dev, n_channels, d->cfg.compact_records_above, true);
+    if (rc != CBD_OK) return rc;
+  }
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
   rc = claim_snapshot_slot(d, channels, n_channels, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n_channels));
+  HIPCHK(d->ids.release(slot, d->stream));
+  return CBD_OK;
+}
+
+int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t min_new_records) {
+  if (!d) return fail(CBD_E_INVALID, "compact_records: null decoder");
+  if (min_new_records < 0) return fail(CBD_E_INVALID, "compact_records: negative threshold");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  rc = enqueue_compaction(d, dev, n, min_new_records, false);
+  if (rc != CBD_OK) return rc;
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
 }
@@ -1090,6 +1140,28 @@ int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *
   return CBD_OK;
 }
 
+int32_t cbd_get_records(cbd_decoder *d, int32_t channel, int32_t *arcs, int32_t *prev, int32_t capacity,
+                        int32_t *n_records, int32_t *frame_base, int32_t *kept_base) {
+  if (!d || !n_records) return fail(CBD_E_INVALID, "get_records: null argument");
+  if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_records: channel out of range");
+  HIPCHK(hipStreamSynchronize(d->stream));
+  cbd::ChanState cs;
+  HIPCHK(hipMemcpy(&cs, d->d_chan + channel, sizeof(cs), hipMemcpyDeviceToHost));
+  *n_records = cs.n_rec;
+  if (frame_base) *frame_base = cs.frame_base;
+  if (kept_base) *kept_base = cs.gc_base;
+  if (!arcs || !prev || capacity < cs.n_rec) return cs.n_rec > 0 && arcs && prev ? CBD_E_BUFFER : CBD_OK;
+  std::vector<int2> rec((size_t)std::max(cs.n_rec, 1));
+  if (cs.n_rec > 0)
+    HIPCHK(hipMemcpy(rec.data(), d->d_bp + (size_t)channel * d->bp_cap, sizeof(int2) * (size_t)cs.n_rec,
+                     hipMemcpyDeviceToHost));
+  for (int32_t i = 0; i < cs.n_rec; ++i) {
+    arcs[i] = (uint32_t)rec[i].x == cbd::kArcNone ? -1 : d->g->int2pub[rec[i].x];
+    prev[i] = rec[i].y;
+  }
+  return CBD_OK;
+}
+
 int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
   if (!d || !out) return fail(CBD_E_INVALID, "get_stats: null argument");
   if (channel < -1 || channel >= d->C) return fail(CBD_E_INVALID, "get_stats: channel out of range");
@@ -1102,6 +1174,7 @@ int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
     s.frames += c.frames; s.active_tokens += c.active_tokens; s.emit_arcs += c.emit_arcs; s.eps_arcs += c.eps_arcs;
     s.candidates += c.candidates; s.improvements += c.improvements; s.tokens += c.tokens;
     s.eps_rounds += c.eps_rounds; s.records += c.n_rec; s.slow_frames += c.slow_frames;
+    s.records_dropped += c.gc_dropped; s.compactions += c.gc_runs;
     if (s.status == CBD_OK && c.status != CBD_OK) s.status = c.status;
     s.max_tokens = std::max(s.max_tokens, c.max_tokens);
   }

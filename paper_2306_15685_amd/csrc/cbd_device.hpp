@@ -86,8 +86,12 @@ struct __attribute__((aligned(128))) ChanState {
   long long frames, active_tokens, emit_arcs, eps_arcs, candidates, improvements, tokens, eps_rounds;
   int32_t max_tokens;
   int32_t slow_frames;  // frames decoded with the device-memory tables
-  int32_t pad[6];
+  int32_t gc_base;      // records below this one survived the last compaction and are never examined again
+  int32_t gc_runs;      // compactions since reset
+  long long gc_dropped; // records they removed
+  int32_t pad[2];
 };
+static_assert(sizeof(ChanState) == 128, "one channel's state fills one 128-byte line");
 
 struct AdvanceParams {
   const int2 *off2;        // [S+1]: x = first arc of the state, y = first epsilon-input arc of the state
@@ -1274,6 +1278,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     if (p.do_reset) {
       cs->frames = 0; cs->active_tokens = 0; cs->emit_arcs = 0; cs->eps_arcs = 0; cs->candidates = 0;
       cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0; cs->slow_frames = 0;
+      cs->gc_base = 0; cs->gc_runs = 0; cs->gc_dropped = 0;
     }
     cs->frames += sh->a_frames; cs->active_tokens += sh->a_active; cs->emit_arcs += sh->a_emit;
     cs->eps_arcs += sh->a_eps; cs->candidates += sh->a_cand; cs->improvements += sh->a_impr;
@@ -1590,6 +1595,239 @@ __global__ __launch_bounds__(64) void best_walk_kernel(BestParams p) {
     return;
   }
   walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane);
+}
+
+// ---- compaction of the back-pointer records ------------------------------------------
+
+// Partial results are read off the best current token (Sec. 1, 3.2), so the only records ever read again are
+// those on a path from a token of the current frame.  This kernel drops the others and renumbers the rest,
+// which lets an utterance run on (the 3-minute recordings of Sec. 5.3 and beyond) in a buffer sized for the
+// stretch between two compactions.  Results are unaffected: every kept record keeps its arc, and its
+// predecessor is the same record under its new number.
+//
+// The paths of all current tokens share their beginning.  Records below gc_base are that shared beginning as
+// an earlier compaction found it: one chain, part of every path from now on, never examined again (the marking
+// walks stop there).  Above it lie the records examined each time: the tree the last compaction kept and
+// whatever has been written since.  After marking, the kernel looks for the highest place in this stretch that
+// exactly one marked link crosses: every path runs through that link, so the marked records below it are one
+// chain, and gc_base moves up to there.  The cost of a call therefore follows the frames since the last one
+// (plus the depth at which the paths merge), not the length of the utterance, and so does the memory in use.
+// The records of the current frame (one per token, dead ones included) are all kept.
+struct CompactParams {
+  ChanState *chan;
+  const int32_t *chan_ids;  // [grid]
+  int2 *bp;                 // [C][bp_cap]
+  const float *tok_cost;    // [C][tok_cap]
+  uint32_t *mark;           // [C][mark_words] one bit per examined record
+  uint32_t *prefix;         // [C][mark_words] marked records before each bitmap word
+  int32_t *cross;           // [C][mark_words + 2] marked links crossing the place before each bitmap word
+  int32_t bp_cap, tok_cap, mark_words;
+  int32_t min_new;          // channels with at most this many records above gc_base are left alone ...
+  const int32_t *any_due;   // ... or, where this is given and reads non-zero, with at most half as many
+};
+
+constexpr int kCompactBlock = 1024;
+constexpr int kCompactPerThread = 4;
+
+__device__ __forceinline__ uint32_t ld_agent_u32(const uint32_t *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// New number of record q: g0 = gc_base, fb = first record of the current frame, new_fb = where that one moves.
+__device__ __forceinline__ int compact_remap(int q, int g0, int fb, int new_fb, const uint32_t *mark,
+                                             const uint32_t *prefix) {
+  if (q < g0) return q;   // the shared beginning, or -1 (no predecessor)
+  if (q >= fb) return q - fb + new_fb;
+  const uint32_t r = (uint32_t)(q - g0), bit = 1u << (r & 31);
+  const uint32_t wv = ld_agent_u32(&mark[r >> 5]);
+  if (!(wv & bit)) return -1;   // only a dead token's record can point at a dropped one
+  return g0 + (int)ld_agent_u32(&prefix[r >> 5]) + __popc(wv & (bit - 1u));
+}
+
+// A marked link between examined positions lo < hi (relative to gc_base; -1 = below it) crosses the places
+// before bitmap words lo/32 + 1 .. hi/32: noted as +1 / -1 steps, summed up afterwards.
+__device__ __forceinline__ void compact_note_link(int32_t *cross, int a, int b) {
+  const int lo = a < b ? a : b, hi = a < b ? b : a;
+  const int b_lo = (lo >> 5) + 1, b_hi = hi >> 5;   // (arithmetic shift: -1 >> 5 = -1)
+  if (b_lo <= b_hi) {
+    atomicAdd(&cross[b_lo], 1);
+    atomicAdd(&cross[b_hi + 1], -1);
+  }
+}
+
+// Workgroup-wide exclusive prefix sums of one value per thread (s_tot: one int per wave); returns the total.
+__device__ __forceinline__ int compact_block_scan(int v, int &excl, int *s_tot, int lane, int wave) {
+  const int incl = wave_incl_scan(v);
+  if (lane == 63) s_tot[wave] = incl;
+  __syncthreads();
+  int before = 0, total = 0;
+#pragma unroll
+  for (int k = 0; k < kCompactBlock / 64; ++k) {
+    const int t = s_tot[k];
+    before += k < wave ? t : 0;
+    total += t;
+  }
+  excl = before + incl - v;
+  __syncthreads();
+  return total;
+}
+
+// A compaction holds up its call for as long as one lane needs to walk the frames since the last one, however
+// many channels take part.  So when one channel of a call is due, those that are half-way there join in: the
+// channels of a call then compact in the same calls rather than each delaying a call of its own.
+// One workgroup: *any_due = some listed channel has more than min_new records above its gc_base.
+__global__ __launch_bounds__(256) void compact_due_kernel(const ChanState *chan, const int32_t *chan_ids, int n,
+                                                          int32_t min_new, int32_t *any_due) {
+  __shared__ int s_due;
+  if (threadIdx.x == 0) s_due = 0;
+  __syncthreads();
+  int due = 0;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    const ChanState *cs = chan + chan_ids[i];
+    if (cs->status == kStatusOk && cs->n_rec - cs->gc_base > min_new) due = 1;
+  }
+  if (due) s_due = 1;
+  __syncthreads();
+  if (threadIdx.x == 0) *any_due = s_due;
+}
+
+__global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactParams p) {
+  __shared__ int s_tot[kCompactBlock / 64];
+  __shared__ int s_cut;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = p.chan_ids[blockIdx.x];
+  ChanState *cs = p.chan + c;
+  if (cs->status != kStatusOk) return;   // (uniform) a parked channel has nothing worth keeping
+  const int n_tok = cs->n_tok, fb = cs->frame_base, n_rec = cs->n_rec, g0 = cs->gc_base;
+  const int young = fb - g0;      // records examined
+  const int n_cur = n_rec - fb;   // records of the current frame
+  const int min_new = (p.any_due && *p.any_due) ? p.min_new / 2 : p.min_new;
+  if (young <= 0 || n_rec - g0 <= min_new) return;
+  int2 *bp = p.bp + (size_t)c * p.bp_cap;
+  const float *tc = p.tok_cost + (size_t)c * p.tok_cap;
+  uint32_t *mark = p.mark + (size_t)c * p.mark_words;
+  uint32_t *prefix = p.prefix + (size_t)c * p.mark_words;
+  int32_t *cross = p.cross + (size_t)c * (p.mark_words + 2);
+  const int W = (young + 31) >> 5;   // bitmap words in use (<= mark_words: the host sizes them for bp_cap records)
+  const int B = young >> 5;          // places 0..B: place b lies before examined record 32 b
+
+  for (int i = tid; i < W; i += kCompactBlock) mark[i] = 0;
+  for (int i = tid; i < B + 2; i += kCompactBlock) cross[i] = 0;
+  if (tid == 0) s_cut = -1;
+  __syncthreads();
+  // mark: from every live token's record, back to the first record that is already marked or lies below gc_base.
+  // Links inside the current frame (epsilon-input arcs) are not followed: their targets are tokens with walks of
+  // their own.  A walk that runs into a loop of predecessors stops at its first marked record like any other.
+  for (int i = tid; i < n_tok && i < n_cur; i += kCompactBlock) {
+    if (!(tc[i] < __builtin_inff())) continue;   // dropped by the frame cutoff
+    int q = bp[fb + i].y;
+    if (q < fb) compact_note_link(cross, q < g0 ? -1 : q - g0, young);
+    while (q >= g0 && q < fb) {
+      const uint32_t r = (uint32_t)(q - g0), bit = 1u << (r & 31);
+      const int nxt = bp[q].y;   // asked for before the mark's answer is in: one round trip per step, not two
+      if (atomicOr(&mark[r >> 5], bit) & bit) break;
+      q = nxt;
+    }
+  }
+  __syncthreads();
+  // the links of the marked records (noted here, by all threads, rather than by the walks: the long walk is one
+  // lane's chain of dependent loads and should wait for nothing else).  One bitmap word per thread: few bits
+  // are set, and a word's records are asked for four at a time.
+  for (int w = tid; w < W; w += kCompactBlock) {
+    uint32_t m = ld_agent_u32(&mark[w]);
+    while (m) {
+      int r[4], u[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        r[k] = -1;
+        if (m) { r[k] = (w << 5) + __builtin_ctz(m); m &= m - 1u; }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) u[k] = bp[g0 + (r[k] < 0 ? 0 : r[k])].y;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (r[k] >= 0) compact_note_link(cross, u[k] < g0 ? -1 : u[k] - g0, r[k]);
+    }
+  }
+  __syncthreads();
+  // how many marked records precede each bitmap word; how many marked links cross each place
+  int carry = 0, run = 0;
+  for (int base = 0; base < W || base < B + 1; base += kCompactBlock) {
+    const int w = base + tid;
+    int excl;
+    const int cnt = w < W ? __popc(ld_agent_u32(&mark[w])) : 0;
+    const int total = compact_block_scan(cnt, excl, s_tot, lane, wave);
+    if (w < W) prefix[w] = (uint32_t)(carry + excl);
+    carry += total;
+    const int step = w <= B ? __hip_atomic_load(&cross[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+    const int total2 = compact_block_scan(step, excl, s_tot, lane, wave);
+    if (w <= B && run + excl + step == 1) atomicMax(&s_cut, w);   // exactly one link crosses place w
+    run += total2;
+  }
+  __syncthreads();
+  const int n_keep = carry;
+  const int new_fb = g0 + n_keep;
+  // marked records below the highest place that a single link crosses: the new part of the shared beginning
+  const int cut = s_cut;
+  const int n_fixed = cut < 0 ? 0 : (cut < W ? (int)ld_agent_u32(&prefix[cut]) : n_keep);
+  if (n_keep < young) {   // (uniform) something to drop
+    // Move the kept records down, a tile at a time: a record never moves up, so a tile's destinations lie
+    // below every record that a later tile reads; the barrier keeps them off the tile's own sources.
+    constexpr int kTile = kCompactBlock * kCompactPerThread;
+    for (int base = 0; base < young; base += kTile) {
+      int2 rec[kCompactPerThread];
+      int dst[kCompactPerThread];
+#pragma unroll
+      for (int k = 0; k < kCompactPerThread; ++k) {
+        const int r = base + k * kCompactBlock + tid;
+        dst[k] = -1;
+        rec[k] = make_int2(0, 0);
+        if (r < young) {
+          const uint32_t bit = 1u << (r & 31);
+          const uint32_t wv = ld_agent_u32(&mark[r >> 5]);
+          if (wv & bit) {
+            rec[k] = bp[g0 + r];
+            dst[k] = g0 + (int)ld_agent_u32(&prefix[r >> 5]) + __popc(wv & (bit - 1u));
+          }
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < kCompactPerThread; ++k)
+        if (dst[k] >= 0) rec[k].y = compact_remap(rec[k].y, g0, fb, new_fb, mark, prefix);
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < kCompactPerThread; ++k)
+        if (dst[k] >= 0) bp[dst[k]] = rec[k];
+    }
+    __syncthreads();
+    // ... then the current frame's records, in the same way
+    for (int base = 0; base < n_cur; base += kTile) {
+      int2 rec[kCompactPerThread];
+#pragma unroll
+      for (int k = 0; k < kCompactPerThread; ++k) {
+        const int i = base + k * kCompactBlock + tid;
+        rec[k] = make_int2(0, 0);
+        if (i < n_cur) {
+          rec[k] = bp[fb + i];
+          rec[k].y = compact_remap(rec[k].y, g0, fb, new_fb, mark, prefix);
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < kCompactPerThread; ++k) {
+        const int i = base + k * kCompactBlock + tid;
+        if (i < n_cur) bp[new_fb + i] = rec[k];
+      }
+    }
+  }
+  __syncthreads();   // every wave is done with the channel's old numbers
+  if (tid == 0) {
+    cs->frame_base = new_fb;
+    cs->n_rec = new_fb + n_cur;
+    cs->gc_base = g0 + n_fixed;
+    cs->gc_runs += 1;
+    cs->gc_dropped += young - n_keep;
+  }
 }
 
 }  // namespace cbd

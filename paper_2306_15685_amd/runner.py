@@ -50,8 +50,11 @@ class Session:
 
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
-                 context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0):
-        """context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
+                 context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0,
+                 compact_records_above: int = 0, record_frames: int = 0):
+        """compact_records_above / record_frames: automatic compaction of the back-pointer records, and the number
+        of frames the record buffer is sized for (0: the whole utterance).
+        context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
         segments' lists once with cbd_contexts_create and switches by id (Sec. 4.3)."""
         import torch
         self.torch = torch
@@ -64,10 +67,10 @@ class Session:
             g.num_states, g.num_pdfs, g.start_state, g.row_offsets, g.dst, g.ilabel, g.olabel, g.weight, g.final_cost)
         self.stream = torch.cuda.current_stream()
         self.dh = B.cbd_decoder_create(
-            self.gh, w.channels, w.beam, w.max_active, w.frames, max(w.ctx_max, 1), w.lookup_mode,
+            self.gh, w.channels, w.beam, w.max_active, record_frames or w.frames, max(w.ctx_max, 1), w.lookup_mode,
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
             records_per_frame or default_records_per_frame(w), table_location, lds_token_cap,
-            w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu,
+            w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu, compact_records_above,
             hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode
         self.async_partials = async_partials   # partial results through cbd_best_paths_begin / _finish
