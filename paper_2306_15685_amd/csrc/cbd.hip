@@ -1027,7 +1027,7 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   rc = size_out_slot(d, o, n, capacity);
   if (rc != CBD_OK) return rc;
   cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
-  hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
+  hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(cbd::kWalkThreads), 0, d->stream, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(d->ids.release(slot, d->stream));
   return fetch_results(d, o, d->stream, n, capacity, words, arcs, n_words, n_arcs, cost, status);
@@ -1073,7 +1073,7 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
   HIPCHK(hipEventRecord(d->snap_ev, d->stream));
   // side stream: the walk reads only records that are already final, so it runs beside later decoding
   HIPCHK(hipStreamWaitEvent(d->side, d->snap_ev, 0));
-  hipLaunchKernelGGL(cbd::best_walk_kernel, dim3((unsigned)n), dim3(64), 0, d->side, bp);
+  hipLaunchKernelGGL(cbd::best_walk_kernel, dim3((unsigned)n), dim3(cbd::kWalkThreads), 0, d->side, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(hipEventRecord(o.done, d->side));
   o.pending = true; o.n = n; o.req_capacity = capacity; o.want_arcs = want_arcs != 0;

@@ -1476,10 +1476,53 @@ __device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanS
   return besti < 0 ? -1 : base + besti;
 }
 
+// The walk below is one lane's chain of dependent reads, a round trip to device memory each.  Records lie in the
+// order of the frames that wrote them, and a step of the walk leads about one frame's records back.  A second wave
+// therefore reads ahead of it: it looks where the walk is (walk_pos, in LDS) and asks for the lines a few frames
+// further down (64 bytes = 8 records each), so that the walk finds its records in the L2 cache.  It reads only and
+// ends when the walk says so.
+constexpr int kWalkDone = -2;
+constexpr int kWalkChunk = 128;   // arcs the walk notes in LDS before the wave writes them out
+
+__device__ __forceinline__ void walk_read_ahead(const BestParams &p, int i, int c, int lane, const int *walk_pos) {
+  const int2 *bp = p.bp + (size_t)c * p.bp_cap;
+  int sink = 0;
+  int prev_r = -1, low = -1;   // where the walk was a moment ago; the lowest record asked for so far
+  for (;;) {
+    const int r = __hip_atomic_load(walk_pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (r == kWalkDone) break;
+    if (low < 0 || r < low) low = r;   // (first pass, or the walk has overtaken the reads)
+    // how far the walk came since the last look tells how far it will be when these reads are back:
+    // stay three such stretches and one span of the wave ahead of it, at most four spans per pass
+    int moved = prev_r < 0 ? 64 : prev_r - r;
+    moved = moved < 64 ? 64 : moved;
+    prev_r = r;
+    const int target = r - 3 * moved - 512;
+    int spans = (low - target + 511) >> 9;
+    spans = spans > 4 ? 4 : spans;
+    if (spans <= 0) {   // far enough ahead: look again shortly
+      __builtin_amdgcn_s_sleep(8);
+      continue;
+    }
+    // (always four reads, all under way together; spans not wanted yet repeat the first one's addresses)
+    int v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int q = low - 8 - lane * 8 - (k < spans ? k : 0) * 512;
+      v[k] = bp[q < 0 ? 0 : q].x;
+    }
+    sink ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    low -= spans * 512;
+    if (low < 0) low = 0;
+  }
+  // (keeps the reads: the value is never this one)
+  if (sink == 0x5A17C0DE && lane == 0) p.out_meta[(size_t)i * 4 + 3] = sink;
+}
+
 // Back-pointer walk from record `rec` and labels in time order.  One wave.  Only records below
 // n_rec are touched (they never change once written), so this may run beside later decoding.
 __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int rec, int n_rec, uint32_t cost_ord,
-                                          int lane) {
+                                          int lane, int *walk_pos, int *walk_arcs) {
   int32_t *meta = p.out_meta + (size_t)i * 4;
   int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
   int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
@@ -1490,17 +1533,33 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
   // cycles can form.
   const int max_steps = n_rec;
   int na = 0;
-  if (lane == 0) {
+  {
+    // Lane 0 follows the predecessors and notes the arcs in LDS; every kWalkChunk steps the wave writes them out
+    // together.  (A store to device memory per step would sit in the chain: the wait for the next record also
+    // waits for the store before it.)
     int r = rec;
-    while (r >= 0 && na <= max_steps) {
-      int2 e = bp[r];
-      if ((uint32_t)e.x == kArcNone) break;
-      if (na < p.capacity) oarcs[na] = e.x;
-      na++;
-      r = e.y;
+    while (r >= 0 && na <= max_steps) {   // uniform
+      int n_chunk = 0;
+      if (lane == 0) {
+        while (r >= 0 && na + n_chunk <= max_steps && n_chunk < kWalkChunk) {
+          int2 e = bp[r];
+          // where the walk is, for the wave that reads ahead of it (an atomic store: a plain one is dropped)
+          __hip_atomic_store(walk_pos, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+          if ((uint32_t)e.x == kArcNone) { r = -1; break; }
+          walk_arcs[n_chunk++] = e.x;
+          r = e.y;
+        }
+      }
+      n_chunk = __shfl(n_chunk, 0, 64);
+      r = __shfl(r, 0, 64);
+      __threadfence_block();
+      for (int j = lane; j < n_chunk; j += 64)
+        if (na + j < p.capacity) oarcs[na + j] = walk_arcs[j];
+      __threadfence_block();
+      na += n_chunk;
     }
+    if (lane == 0) __hip_atomic_store(walk_pos, kWalkDone, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   }
-  na = __shfl(na, 0, 64);
   __threadfence_block();
   if (na > max_steps) {
     if (lane == 0) { meta[0] = kStatusEpsDiverged; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
@@ -1547,24 +1606,37 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
   }
 }
 
-// One wave per channel: best token, then its path.
-__global__ __launch_bounds__(64) void best_path_kernel(BestParams p) {
-  const int lane = threadIdx.x, i = blockIdx.x;
+constexpr int kWalkThreads = 128;   // per channel: the wave that walks and the wave that reads ahead of it
+
+// One workgroup per channel: best token, then its path.
+__global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
+  __shared__ int s_walk_pos;
+  __shared__ int s_walk_arcs[kWalkChunk];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = blockIdx.x;
   const int c = p.chan_ids[i];
   const ChanState *cs = p.chan + c;
   int32_t *meta = p.out_meta + (size_t)i * 4;
   const int inf_bits = (int)__float_as_uint(__builtin_inff());
-  if (cs->status != kStatusOk) {
-    if (lane == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
+  if (cs->status != kStatusOk) {   // (uniform)
+    if (threadIdx.x == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
-  uint64_t key;
-  int rec = find_best(p, c, cs, key, lane);
+  uint64_t key = kEmptyVal;
+  int rec = -1;
+  if (wave == 0) {
+    rec = find_best(p, c, cs, key, lane);
+    if (lane == 0) s_walk_pos = rec < 0 ? kWalkDone : rec;
+  }
+  __syncthreads();
+  if (wave == 1) {
+    walk_read_ahead(p, i, c, lane, &s_walk_pos);
+    return;
+  }
   if (rec < 0) {
     if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
-  walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane);
+  walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane, &s_walk_pos, s_walk_arcs);
 }
 
 // Two-stage form for results delivered beside later decoding.  Stage 1 (decode stream): pick the
@@ -1586,15 +1658,23 @@ __global__ __launch_bounds__(64) void best_snapshot_kernel(BestParams p) {
 }
 
 // Stage 2 (side stream): the walk, from the snapshot only.
-__global__ __launch_bounds__(64) void best_walk_kernel(BestParams p) {
-  const int lane = threadIdx.x, i = blockIdx.x;
+__global__ __launch_bounds__(kWalkThreads) void best_walk_kernel(BestParams p) {
+  __shared__ int s_walk_pos;
+  __shared__ int s_walk_arcs[kWalkChunk];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = blockIdx.x;
   const int32_t *snap = p.snap + (size_t)i * kSnapInts;
   int32_t *meta = p.out_meta + (size_t)i * 4;
-  if (snap[0] != kStatusOk) {
-    if (lane == 0) { meta[0] = snap[0]; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
+  if (snap[0] != kStatusOk) {   // (uniform)
+    if (threadIdx.x == 0) { meta[0] = snap[0]; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
     return;
   }
-  walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane);
+  if (threadIdx.x == 0) s_walk_pos = snap[1];
+  __syncthreads();
+  if (wave == 1) {
+    walk_read_ahead(p, i, snap[4], lane, &s_walk_pos);
+    return;
+  }
+  walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane, &s_walk_pos, s_walk_arcs);
 }
 
 // ---- compaction of the back-pointer records ------------------------------------------
