@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--chunk", type=int, default=0, help="override the frames per advance call")
     ap.add_argument("--compact-records-above", type=int, default=0,
                     help="compact a channel's back-pointer records once it holds more than this many new ones")
+    ap.add_argument("--tail-partials", action="store_true",
+                    help="partial results through cbd_best_tails_* (the part of the path above what compactions fixed)")
     ap.add_argument("--record-frames", type=int, default=0,
                     help="size the back-pointer buffer for this many frames (default: the utterance)")
     ap.add_argument("--hash-log2", type=int, default=0)
@@ -143,7 +145,8 @@ def main():
     sess = runner.Session(inp, hash_log2=args.hash_log2 or None, table_location=args.table_location,
                           biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
                           async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu,
-                          compact_records_above=args.compact_records_above, record_frames=args.record_frames)
+                          compact_records_above=args.compact_records_above, record_frames=args.record_frames,
+                          tail_partials=args.tail_partials)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -181,7 +184,7 @@ def main():
     default_cfg = (not args.unbiased and args.context_mode == "upload" and not args.channels and not args.hash_log2
                    and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu
                    and args.lookup_mode < 0 and not args.sync_partials and not args.frames and not args.chunk
-                   and not args.compact_records_above and not args.record_frames)
+                   and not args.compact_records_above and not args.record_frames and not args.tail_partials)
     traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name) if default_cfg else None
 
     out = {
@@ -195,7 +198,7 @@ def main():
                    "context_mode": args.context_mode, "async_partials": not args.sync_partials,
                    "lookup_mode": w.lookup_mode, "lds_token_cap": info["lds_token_cap"],
                    "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"],
-                   "compact_records_above": args.compact_records_above, "device_bytes": info["device_bytes"]},
+                   "compact_records_above": args.compact_records_above, "tail_partials": args.tail_partials, "device_bytes": info["device_bytes"]},
         "arcs_per_s": arcs / (wall / args.steps),
         "frames_per_s": w.channels * w.segments * w.frames / (wall / args.steps),
         "tokens_per_frame": st["tokens"] / max(st["frames"], 1),
@@ -206,6 +209,7 @@ def main():
                      "avg_launch_ms": avg_launch_ms, "algorithmic_bytes_per_launch": alg_bytes_step / launches_per_step,
                      "kernel_time_share": sum(kms) / (wall * 1e3)},
     }
+    out["config"]["device_bytes"] = B.cbd_decoder_info(sess.dh)["device_bytes"]   # (buffers allocated on first use included)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp, min(args.cpu_channels, w.channels), w.frames)
     sess.close()

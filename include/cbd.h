@@ -117,10 +117,12 @@ typedef struct cbd_config {
   int32_t workgroups_per_cu;  /* channels decoded side by side on one compute unit (they share its LDS, so each
                                  gets a smaller table): 1, 2 or 4; 0 = chosen by the library (1 while the decoder has
                                  no more channels than the device has compute units, else 2) */
-  int32_t compact_records_above; /* 0 = records are only compacted on request (cbd_compact_records); N > 0 = every
-                                 cbd_advance call first compacts those of its channels that hold more than N records
-                                 above the part their paths share, and with them (so that the call is held up once,
-                                 not once per channel) those that hold more than N / 2 */
+  int32_t compact_records_above; /* 0 = records are only compacted on request (cbd_compact_records); N > 0 = a
+                                 cbd_advance call first compacts its channels once one of them holds more than N
+                                 records above the part its paths share, and with it (so that a call is held up
+                                 once, not once per channel) those that hold more than N / 2.  The counts are the
+                                 ones finished launches have reported, so the mark may be overshot by the records
+                                 of the calls still in flight: size the buffer with that room */
 } cbd_config;
 
 /*
@@ -233,6 +235,37 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
                              int32_t want_arcs, int32_t *ticket);
 int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
                               int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status);
+
+/*
+ * Results in two parts, for long utterances.  All paths of a channel's current tokens share their beginning,
+ * and the part of it that the compactions (cbd_compact_records) have found so far can no longer change: it is
+ * what an online recogniser may show as final while the utterance goes on (Sec. 1, Sec. 3.2: intermediate
+ * results are the best current token sequence).  The library keeps that part per channel, in time order.
+ *
+ * cbd_best_tails / _begin / _finish work like cbd_best_paths / _begin / _finish, but follow each best path only
+ * down to that fixed part: words / arcs receive the rest of the path, and n_fixed_words[i] / n_fixed_arcs[i]
+ * (HOST [n]) say how many words and arcs of the fixed part precede it.  The whole result is the first
+ * n_fixed_words[i] words of the fixed part followed by the returned words (likewise for arcs); cost is the
+ * whole path's.  A walk then costs the frames since the paths merged, not the utterance so far.  Without
+ * compactions the fixed part is empty and the calls return whole paths.  A request begun by cbd_best_tails_begin
+ * is finished by cbd_best_tails_finish (and one begun by cbd_best_paths_begin by cbd_best_paths_finish).
+ *
+ * cbd_get_fixed copies the fixed part of one channel from word from_word and arc from_arc on (it only ever
+ * grows within an utterance, so a caller keeps what it has and asks for the rest): words, arcs HOST [capacity]
+ * or NULL; *n_words, *n_arcs receive the counts beyond from_word / from_arc; CBD_E_BUFFER if a wanted array is
+ * too small.  Synchronises.  The fixed part is cleared by cbd_reset_channels; its room is that of the
+ * back-pointer buffer (when it is full, nothing more is declared fixed).
+ */
+int32_t cbd_best_tails(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                       int32_t *status, int32_t *n_fixed_words, int32_t *n_fixed_arcs);
+int32_t cbd_best_tails_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
+                             int32_t want_arcs, int32_t *ticket);
+int32_t cbd_best_tails_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status,
+                              int32_t *n_fixed_words, int32_t *n_fixed_arcs);
+int32_t cbd_get_fixed(cbd_decoder *d, int32_t channel, int32_t from_word, int32_t from_arc, int32_t *words,
+                      int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs);
 
 /*
  * The channel's current token table (any order): state, cost, arc (caller's

@@ -21,7 +21,8 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_context_from_words", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
-    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_compact_records", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_get_tokens",
+    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_compact_records", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_best_tails", "cbd_best_tails_begin", "cbd_best_tails_finish",
+    "cbd_get_fixed", "cbd_get_tokens",
     "cbd_get_records", "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
 
@@ -100,6 +101,14 @@ def lib():
     L.cbd_best_paths_begin.argtypes = [vp, vp, i32, i32, i32, i32, vp]
     L.cbd_best_paths_finish.restype = i32
     L.cbd_best_paths_finish.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
+    L.cbd_best_tails.restype = i32
+    L.cbd_best_tails.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    L.cbd_best_tails_begin.restype = i32
+    L.cbd_best_tails_begin.argtypes = [vp, vp, i32, i32, i32, i32, vp]
+    L.cbd_best_tails_finish.restype = i32
+    L.cbd_best_tails_finish.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    L.cbd_get_fixed.restype = i32
+    L.cbd_get_fixed.argtypes = [vp, i32, i32, i32, vp, vp, i32, vp, vp]
     L.cbd_get_tokens.restype = i32
     L.cbd_get_tokens.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.cbd_get_records.restype = i32
@@ -277,6 +286,8 @@ class BestPathBuffers:
         self.n_arcs = np.zeros(n, np.int32)
         self.cost = np.zeros(n, np.float32)
         self.status = np.zeros(n, np.int32)
+        self.n_fixed_words = np.zeros(n, np.int32)   # (cbd_best_tails* only)
+        self.n_fixed_arcs = np.zeros(n, np.int32)
 
 
 def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, buffers: Optional[BestPathBuffers] = None,
@@ -325,6 +336,65 @@ def cbd_best_paths_finish(d, ticket, buffers: Optional[BestPathBuffers] = None, 
     if want_arcs:
         al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
     return st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()
+
+
+def _tails_result(b, n, want_arcs, as_lists):
+    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
+    if not as_lists:
+        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw, b.n_fixed_words[:n], b.n_fixed_arcs[:n]
+    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    al = None
+    if want_arcs:
+        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    return (st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy(), b.n_fixed_words[:n].copy(),
+            b.n_fixed_arcs[:n].copy())
+
+
+def cbd_best_tails(d, channels, use_final=False, capacity=4096, want_arcs=True,
+                   buffers: Optional[BestPathBuffers] = None, as_lists=True):
+    """Like cbd_best_paths for the part of each path above the fixed part
+    -> (status, words, arcs or None, cost, n_arcs, n_words, n_fixed_words, n_fixed_arcs)."""
+    ch = _i32(channels)
+    n = int(ch.size)
+    b = buffers if buffers is not None else BestPathBuffers(n, capacity, want_arcs)
+    assert b.n >= n and b.capacity == capacity
+    _check(lib().cbd_best_tails(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
+                                int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status),
+                                _p(b.n_fixed_words), _p(b.n_fixed_arcs)), "cbd_best_tails")
+    return _tails_result(b, n, want_arcs, as_lists)
+
+
+def cbd_best_tails_begin(d, channels, use_final=False, capacity=4096, want_arcs=True):
+    ch = _i32(channels)
+    t = C.c_int32(0)
+    _check(lib().cbd_best_tails_begin(d, _p(ch), int(ch.size), int(bool(use_final)), int(capacity), int(bool(want_arcs)),
+                                      C.byref(t)), "cbd_best_tails_begin")
+    return (t.value, int(ch.size), int(capacity), bool(want_arcs))
+
+
+def cbd_best_tails_finish(d, ticket, buffers: Optional[BestPathBuffers] = None, as_lists=True):
+    t, n, capacity, want_arcs = ticket
+    b = buffers if buffers is not None else BestPathBuffers(n, capacity, want_arcs)
+    assert b.n >= n and b.capacity == capacity
+    _check(lib().cbd_best_tails_finish(d, t, _p(b.words), _p(b.arcs) if want_arcs else None, int(capacity),
+                                       _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status), _p(b.n_fixed_words),
+                                       _p(b.n_fixed_arcs)), "cbd_best_tails_finish")
+    return _tails_result(b, n, want_arcs, as_lists)
+
+
+def cbd_get_fixed(d, channel, from_word=0, from_arc=0):
+    """-> (words, arcs) of the channel's fixed part from the given positions on."""
+    nw, na = C.c_int32(0), C.c_int32(0)
+    _check(lib().cbd_get_fixed(d, int(channel), int(from_word), int(from_arc), None, None, 0, C.byref(nw), C.byref(na)),
+           "cbd_get_fixed")
+    words = np.zeros(max(nw.value, 1), np.int32)
+    arcs = np.zeros(max(na.value, 1), np.int32)
+    cap = int(max(words.size, arcs.size))
+    words = np.zeros(cap, np.int32)
+    arcs = np.zeros(cap, np.int32)
+    _check(lib().cbd_get_fixed(d, int(channel), int(from_word), int(from_arc), _p(words), _p(arcs), cap, C.byref(nw),
+                               C.byref(na)), "cbd_get_fixed")
+    return words[:nw.value].copy(), arcs[:na.value].copy()
 
 
 def cbd_get_tokens(d, channel):

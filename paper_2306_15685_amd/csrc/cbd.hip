@@ -137,7 +137,13 @@ struct cbd_decoder {
   uint32_t *d_hidx = nullptr;
   // record compaction: one bit per back-pointer record, and two counts per bitmap word (allocated on first use)
   uint32_t *d_gc_mark = nullptr, *d_gc_prefix = nullptr;
-  int32_t *d_gc_cross = nullptr, *d_gc_due = nullptr;
+  int32_t *d_gc_cross = nullptr;
+  // automatic compaction: each decoding launch leaves (records above gc_base, call number) per channel here (pinned
+  // host memory the kernel writes to), so cbd_advance can tell when a compaction is due without synchronising
+  int2 *h_new = nullptr, *dv_new = nullptr;
+  int64_t last_compact_call = -1;
+  // the shared beginning of each channel's paths in time order, as the compactions find it ([C][bp_cap] each)
+  int32_t *d_fixed_arcs = nullptr, *d_fixed_words = nullptr;
   int32_t gc_words = 0;
   // best-path results: slot 0 serves the synchronous calls, the others asynchronous requests
   static constexpr int kOutSlots = 5;
@@ -149,7 +155,7 @@ struct cbd_decoder {
     int32_t *dv_words = nullptr, *dv_meta = nullptr;
     int32_t rows = 0, capacity = 0;
     int32_t n = 0, req_capacity = 0;
-    bool want_arcs = false, pending = false;
+    bool want_arcs = false, pending = false, tail_only = false;
     int snap_slot = -1;   // ring slot of d_auto_snap the request reads (-1: its own snapshot)
     hipEvent_t done = nullptr;
   } out[kOutSlots];
@@ -230,7 +236,7 @@ int32_t size_out_slot(cbd_decoder *d, cbd_decoder::OutSlot &o, int32_t n, int32_
   HIPCHK(dmalloc(&o.d_snap, (size_t)rows * cbd::kSnapInts, nullptr));
   HIPCHK(hipHostMalloc((void **)&o.h_arcs, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
   HIPCHK(hipHostMalloc((void **)&o.h_words, sizeof(int32_t) * (size_t)rows * cap, hipHostMallocDefault));
-  HIPCHK(hipHostMalloc((void **)&o.h_meta, sizeof(int32_t) * (size_t)rows * 4, hipHostMallocDefault));
+  HIPCHK(hipHostMalloc((void **)&o.h_meta, sizeof(int32_t) * (size_t)rows * cbd::kMetaInts, hipHostMallocDefault));
   HIPCHK(hipHostGetDevicePointer((void **)&o.dv_words, o.h_words, 0));
   HIPCHK(hipHostGetDevicePointer((void **)&o.dv_meta, o.h_meta, 0));
   o.rows = rows; o.capacity = cap;
@@ -238,12 +244,13 @@ int32_t size_out_slot(cbd_decoder *d, cbd_decoder::OutSlot &o, int32_t n, int32_
 }
 
 cbd::BestParams best_params(const cbd_decoder *d, const cbd_decoder::OutSlot &o, const int32_t *chan_ids,
-                            int32_t use_final, int32_t capacity) {
+                            int32_t use_final, int32_t capacity, bool tail_only) {
   cbd::BestParams bp{};
   bp.chan = d->d_chan; bp.chan_ids = chan_ids; bp.tok_state = d->d_tok_state; bp.tok_cost = d->d_tok_cost;
   bp.bp = d->d_bp; bp.olabel = d->g->d_olabel; bp.int2pub = d->g->d_int2pub; bp.final_cost = d->g->d_final;
   bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
   bp.row_pitch = o.capacity;
+  bp.tail_only = tail_only ? 1 : 0;
   bp.out_arcs = o.d_arcs; bp.out_words = o.dv_words; bp.out_meta = o.dv_meta; bp.snap = o.d_snap;
   return bp;
 }
@@ -252,13 +259,14 @@ cbd::BestParams best_params(const cbd_decoder *d, const cbd_decoder::OutSlot &o,
 // many columns of the arc rows as the longest path needs if arcs are wanted, and hands the rows to the caller.
 int32_t fetch_results(cbd_decoder *d, cbd_decoder::OutSlot &o, hipStream_t st, int32_t n, int32_t capacity,
                       int32_t *words, int32_t *arcs, int32_t *n_words, int32_t *n_arcs, float *cost,
-                      int32_t *status) {
+                      int32_t *status, int32_t *n_fixed_words = nullptr, int32_t *n_fixed_arcs = nullptr) {
+  constexpr size_t M = cbd::kMetaInts;
   int32_t *meta = o.h_meta;
   HIPCHK(hipStreamSynchronize(st));   // the kernel has written headers and words into host memory
   if (arcs) {
     int32_t max_na = 0;
     for (int32_t i = 0; i < n; ++i)
-      if (meta[(size_t)i * 4] == CBD_OK) max_na = std::max(max_na, meta[(size_t)i * 4 + 1]);
+      if (meta[(size_t)i * M] == CBD_OK) max_na = std::max(max_na, meta[(size_t)i * M + 1]);
     const size_t pitch = sizeof(int32_t) * (size_t)o.capacity;
     if (max_na > 0) {
       HIPCHK(hipMemcpy2DAsync(o.h_arcs, pitch, o.d_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
@@ -267,10 +275,12 @@ int32_t fetch_results(cbd_decoder *d, cbd_decoder::OutSlot &o, hipStream_t st, i
     }
   }
   for (int32_t i = 0; i < n; ++i) {
-    status[i] = meta[(size_t)i * 4 + 0];
-    n_arcs[i] = meta[(size_t)i * 4 + 1];
-    n_words[i] = meta[(size_t)i * 4 + 2];
-    uint32_t bits = (uint32_t)meta[(size_t)i * 4 + 3];
+    status[i] = meta[(size_t)i * M + 0];
+    n_arcs[i] = meta[(size_t)i * M + 1];
+    n_words[i] = meta[(size_t)i * M + 2];
+    if (n_fixed_arcs) n_fixed_arcs[i] = meta[(size_t)i * M + 4];
+    if (n_fixed_words) n_fixed_words[i] = meta[(size_t)i * M + 5];
+    uint32_t bits = (uint32_t)meta[(size_t)i * M + 3];
     memcpy(&cost[i], &bits, 4);
     if (status[i] != CBD_OK) continue;
     memcpy(words + (size_t)i * capacity, o.h_words + (size_t)i * o.capacity, sizeof(int32_t) * (size_t)n_words[i]);
@@ -311,13 +321,13 @@ int32_t stage_channels(cbd_decoder *d, const int32_t *channels, int32_t n, const
 
 // Enqueues the record compaction for the channels in `dev` (a staged list of n).  It renumbers records, so the
 // stream first waits for every unfinished asynchronous walk, and snapshots left by earlier calls are retired.
-// together: a channel half-way to min_new joins in when another channel of the list is due.
-int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_t min_new, bool together) {
+int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_t min_new) {
   d->gc_words = (d->bp_cap + 31) / 32;
   if (!d->d_gc_mark) HIPCHK(dmalloc(&d->d_gc_mark, (size_t)d->C * d->gc_words, &d->bytes));
   if (!d->d_gc_prefix) HIPCHK(dmalloc(&d->d_gc_prefix, (size_t)d->C * d->gc_words, &d->bytes));
   if (!d->d_gc_cross) HIPCHK(dmalloc(&d->d_gc_cross, (size_t)d->C * (d->gc_words + 2), &d->bytes));
-  if (!d->d_gc_due) HIPCHK(dmalloc(&d->d_gc_due, 1, &d->bytes));
+  if (!d->d_fixed_arcs) HIPCHK(dmalloc(&d->d_fixed_arcs, (size_t)d->C * d->bp_cap, &d->bytes));
+  if (!d->d_fixed_words) HIPCHK(dmalloc(&d->d_fixed_words, (size_t)d->C * d->bp_cap, &d->bytes));
   for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
     if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
   d->last_list.clear();
@@ -325,12 +335,8 @@ int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_
   cp.chan = d->d_chan; cp.chan_ids = dev; cp.bp = d->d_bp; cp.tok_cost = d->d_tok_cost;
   cp.mark = d->d_gc_mark; cp.prefix = d->d_gc_prefix; cp.cross = d->d_gc_cross;
   cp.bp_cap = d->bp_cap; cp.tok_cap = d->g_tok_cap; cp.mark_words = d->gc_words; cp.min_new = min_new;
-  if (together) {
-    hipLaunchKernelGGL(cbd::compact_due_kernel, dim3(1), dim3(256), 0, d->stream, d->d_chan, dev, n, min_new,
-                       d->d_gc_due);
-    HIPCHK(hipGetLastError());
-    cp.any_due = d->d_gc_due;
-  }
+  cp.fixed_arcs = d->d_fixed_arcs; cp.fixed_words = d->d_fixed_words; cp.fixed_cap = d->bp_cap;
+  cp.olabel = d->g->d_olabel; cp.int2pub = d->g->d_int2pub;
   hipLaunchKernelGGL(cbd::compact_records_kernel, dim3((unsigned)n), dim3(cbd::kCompactBlock), 0, d->stream, cp);
   HIPCHK(hipGetLastError());
   return CBD_OK;
@@ -670,6 +676,11 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   hipLaunchKernelGGL(cbd::init_chan_kernel, dim3((unsigned)((C + 255) / 256)), dim3(256), 0, d->stream, d->d_chan,
                      d->C);
   DCHK(hipGetLastError());
+  if (cfg->compact_records_above > 0) {
+    DCHK(hipHostMalloc((void **)&d->h_new, sizeof(int2) * C, hipHostMallocDefault));
+    memset(d->h_new, 0, sizeof(int2) * C);
+    DCHK(hipHostGetDevicePointer((void **)&d->dv_new, d->h_new, 0));
+  }
   DCHK(d->ids.init(sizeof(int32_t) * C));
   // context staging: [channels n][list offsets n+1][offsets n][lists ...]
   DCHK(d->ctxs.init(sizeof(int32_t) * (C * 4 + 1 + C * (size_t)d->max_ctx)));
@@ -684,10 +695,11 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
-                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_gc_due};
+                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->side) (void)hipStreamSynchronize(d->side);
+  if (d->h_new) (void)hipHostFree(d->h_new);
   for (auto &o : d->out) {
     free_out_slot(o);
     if (o.done) (void)hipEventDestroy(o.done);
@@ -721,6 +733,7 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
     if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = nullptr; p.channel_stride = 0; p.n_frames = 0; p.do_reset = 1;
+  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls;
   rc = claim_snapshot_slot(d, channels, n, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n));
@@ -989,11 +1002,26 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   int32_t rc = stage_channels(d, channels, n_channels, &dev, &slot);
   if (rc != CBD_OK) return rc;
   if (d->cfg.compact_records_above > 0) {
-    rc = enqueue_compaction(d, dev, n_channels, d->cfg.compact_records_above, true);
-    if (rc != CBD_OK) return rc;
+    // Each finished launch has left its channels' record counts in host memory.  When one of this call's channels is
+    // over the mark, all of them that are half-way there are compacted now: a compaction holds up the call for one
+    // lane's walk however many channels take part, so they had better take part together.  Counts written before
+    // the last compaction say nothing (their launch ran before it) and are skipped.
+    const int32_t mark = d->cfg.compact_records_above;
+    bool due = false;
+    for (int32_t i = 0; i < n_channels && !due; ++i) {
+      const volatile int2 *e = d->h_new + channels[i];
+      const int32_t count = e->x, call = e->y;
+      due = count > mark && (int32_t)((uint32_t)call - (uint32_t)d->last_compact_call) >= 0;   // (call numbers wrap)
+    }
+    if (due) {
+      rc = enqueue_compaction(d, dev, n_channels, mark / 2);
+      if (rc != CBD_OK) return rc;
+      d->last_compact_call = d->adv_calls;   // (the number this call is about to take)
+    }
   }
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
+  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls;
   rc = claim_snapshot_slot(d, channels, n_channels, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n_channels));
@@ -1008,17 +1036,25 @@ int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, 
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n, &dev, &slot);
   if (rc != CBD_OK) return rc;
-  rc = enqueue_compaction(d, dev, n, min_new_records, false);
+  rc = enqueue_compaction(d, dev, n, min_new_records);
   if (rc != CBD_OK) return rc;
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
 }
 
-int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
-                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
-                       int32_t *status) {
-  if (!d || !words || !n_words || !n_arcs || !cost || !status) return fail(CBD_E_INVALID, "best_paths: null argument");
-  if (capacity < 1) return fail(CBD_E_INVALID, "best_paths: capacity < 1");
+}  // extern "C"
+
+namespace {
+
+// tail_only: follow each path down to the beginning that all of the channel's paths share (as the compactions
+// have found it) and report how many words and arcs of it precede (n_fixed_*); else whole paths.
+int32_t best_paths_impl(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                        int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                        int32_t *status, bool tail_only, int32_t *n_fixed_words, int32_t *n_fixed_arcs,
+                        const char *who) {
+  if (!d || !words || !n_words || !n_arcs || !cost || !status || (tail_only && (!n_fixed_words || !n_fixed_arcs)))
+    return fail(CBD_E_INVALID, std::string(who) + ": null argument");
+  if (capacity < 1) return fail(CBD_E_INVALID, std::string(who) + ": capacity < 1");
   const int32_t *dev = nullptr;
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n, &dev, &slot);
@@ -1026,21 +1062,22 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   cbd_decoder::OutSlot &o = d->out[0];
   rc = size_out_slot(d, o, n, capacity);
   if (rc != CBD_OK) return rc;
-  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
+  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity, tail_only);
   hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(cbd::kWalkThreads), 0, d->stream, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(d->ids.release(slot, d->stream));
-  return fetch_results(d, o, d->stream, n, capacity, words, arcs, n_words, n_arcs, cost, status);
+  return fetch_results(d, o, d->stream, n, capacity, words, arcs, n_words, n_arcs, cost, status, n_fixed_words,
+                       n_fixed_arcs);
 }
 
-int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
-                             int32_t want_arcs, int32_t *ticket) {
-  if (!d || !ticket) return fail(CBD_E_INVALID, "best_paths_begin: null argument");
-  if (capacity < 1) return fail(CBD_E_INVALID, "best_paths_begin: capacity < 1");
+int32_t best_paths_begin_impl(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final,
+                              int32_t capacity, int32_t want_arcs, int32_t *ticket, bool tail_only, const char *who) {
+  if (!d || !ticket) return fail(CBD_E_INVALID, std::string(who) + ": null argument");
+  if (capacity < 1) return fail(CBD_E_INVALID, std::string(who) + ": capacity < 1");
   int t = -1;
   for (int k = 1; k < cbd_decoder::kOutSlots; ++k)
     if (!d->out[k].pending) { t = k; break; }
-  if (t < 0) return fail(CBD_E_CAPACITY, "best_paths_begin: too many requests in flight (finish one first)");
+  if (t < 0) return fail(CBD_E_CAPACITY, std::string(who) + ": too many requests in flight (finish one first)");
   // The decoding kernel leaves each channel's best token behind when it finishes.  A request for the channels
   // of the latest advance / reset call, in the same order and without final costs, walks from those; any other
   // request takes its own snapshot on the decode stream first.
@@ -1059,7 +1096,7 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
   if (!d->side) HIPCHK(hipStreamCreateWithFlags(&d->side, hipStreamNonBlocking));
   if (!d->snap_ev) HIPCHK(hipEventCreateWithFlags(&d->snap_ev, hipEventDisableTiming));
   if (!o.done) HIPCHK(hipEventCreateWithFlags(&o.done, hipEventDisableTiming));
-  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity);
+  cbd::BestParams bp = best_params(d, o, dev, use_final, capacity, tail_only);
   if (reuse) {
     o.snap_slot = (int)((d->adv_calls - 1) % cbd_decoder::kSnapRing);
     bp.snap = d->d_auto_snap + (size_t)o.snap_slot * d->C * cbd::kSnapInts;
@@ -1076,23 +1113,87 @@ int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n,
   hipLaunchKernelGGL(cbd::best_walk_kernel, dim3((unsigned)n), dim3(cbd::kWalkThreads), 0, d->side, bp);
   HIPCHK(hipGetLastError());
   HIPCHK(hipEventRecord(o.done, d->side));
-  o.pending = true; o.n = n; o.req_capacity = capacity; o.want_arcs = want_arcs != 0;
+  o.pending = true; o.n = n; o.req_capacity = capacity; o.want_arcs = want_arcs != 0; o.tail_only = tail_only;
   *ticket = t;
   return CBD_OK;
 }
 
-int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
-                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status) {
-  if (!d || !words || !n_words || !n_arcs || !cost || !status)
-    return fail(CBD_E_INVALID, "best_paths_finish: null argument");
+int32_t best_paths_finish_impl(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                               int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status, bool tail_only,
+                               int32_t *n_fixed_words, int32_t *n_fixed_arcs, const char *who) {
+  if (!d || !words || !n_words || !n_arcs || !cost || !status || (tail_only && (!n_fixed_words || !n_fixed_arcs)))
+    return fail(CBD_E_INVALID, std::string(who) + ": null argument");
   if (ticket < 1 || ticket >= cbd_decoder::kOutSlots || !d->out[ticket].pending)
-    return fail(CBD_E_INVALID, "best_paths_finish: no such request");
+    return fail(CBD_E_INVALID, std::string(who) + ": no such request");
   cbd_decoder::OutSlot &o = d->out[ticket];
-  if (capacity != o.req_capacity) return fail(CBD_E_INVALID, "best_paths_finish: capacity differs from the request");
-  if (arcs && !o.want_arcs) return fail(CBD_E_INVALID, "best_paths_finish: arcs were not requested");
-  int32_t rc = fetch_results(d, o, d->side, o.n, capacity, words, arcs, n_words, n_arcs, cost, status);
+  if (o.tail_only != tail_only) return fail(CBD_E_INVALID, std::string(who) + ": the request was begun by the other kind of call");
+  if (capacity != o.req_capacity) return fail(CBD_E_INVALID, std::string(who) + ": capacity differs from the request");
+  if (arcs && !o.want_arcs) return fail(CBD_E_INVALID, std::string(who) + ": arcs were not requested");
+  int32_t rc = fetch_results(d, o, d->side, o.n, capacity, words, arcs, n_words, n_arcs, cost, status, n_fixed_words,
+                             n_fixed_arcs);
   o.pending = false;
   return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                       int32_t *status) {
+  return best_paths_impl(d, channels, n, use_final, words, arcs, capacity, n_words, n_arcs, cost, status, false,
+                         nullptr, nullptr, "best_paths");
+}
+
+int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
+                             int32_t want_arcs, int32_t *ticket) {
+  return best_paths_begin_impl(d, channels, n, use_final, capacity, want_arcs, ticket, false, "best_paths_begin");
+}
+
+int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status) {
+  return best_paths_finish_impl(d, ticket, words, arcs, capacity, n_words, n_arcs, cost, status, false, nullptr,
+                                nullptr, "best_paths_finish");
+}
+
+int32_t cbd_best_tails(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                       int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                       int32_t *status, int32_t *n_fixed_words, int32_t *n_fixed_arcs) {
+  return best_paths_impl(d, channels, n, use_final, words, arcs, capacity, n_words, n_arcs, cost, status, true,
+                         n_fixed_words, n_fixed_arcs, "best_tails");
+}
+
+int32_t cbd_best_tails_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
+                             int32_t want_arcs, int32_t *ticket) {
+  return best_paths_begin_impl(d, channels, n, use_final, capacity, want_arcs, ticket, true, "best_tails_begin");
+}
+
+int32_t cbd_best_tails_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status,
+                              int32_t *n_fixed_words, int32_t *n_fixed_arcs) {
+  return best_paths_finish_impl(d, ticket, words, arcs, capacity, n_words, n_arcs, cost, status, true, n_fixed_words,
+                                n_fixed_arcs, "best_tails_finish");
+}
+
+int32_t cbd_get_fixed(cbd_decoder *d, int32_t channel, int32_t from_word, int32_t from_arc, int32_t *words,
+                      int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs) {
+  if (!d || !n_words || !n_arcs) return fail(CBD_E_INVALID, "get_fixed: null argument");
+  if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_fixed: channel out of range");
+  if (from_word < 0 || from_arc < 0 || capacity < 0) return fail(CBD_E_INVALID, "get_fixed: negative argument");
+  HIPCHK(hipStreamSynchronize(d->stream));
+  cbd::ChanState cs;
+  HIPCHK(hipMemcpy(&cs, d->d_chan + channel, sizeof(cs), hipMemcpyDeviceToHost));
+  const int32_t nw = std::max(cs.n_fixed_words - from_word, 0), na = std::max(cs.n_fixed_arcs - from_arc, 0);
+  *n_words = nw; *n_arcs = na;
+  if ((words && nw > capacity) || (arcs && na > capacity)) return CBD_E_BUFFER;
+  if (words && nw > 0)
+    HIPCHK(hipMemcpy(words, d->d_fixed_words + (size_t)channel * d->bp_cap + from_word, sizeof(int32_t) * (size_t)nw,
+                     hipMemcpyDeviceToHost));
+  if (arcs && na > 0)
+    HIPCHK(hipMemcpy(arcs, d->d_fixed_arcs + (size_t)channel * d->bp_cap + from_arc, sizeof(int32_t) * (size_t)na,
+                     hipMemcpyDeviceToHost));
+  return CBD_OK;
 }
 
 int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_t *words, int32_t *arcs,

@@ -89,7 +89,8 @@ struct __attribute__((aligned(128))) ChanState {
   int32_t gc_base;      // records below this one survived the last compaction and are never examined again
   int32_t gc_runs;      // compactions since reset
   long long gc_dropped; // records they removed
-  int32_t pad[2];
+  int32_t n_fixed_arcs;  // arcs / words of the paths' shared beginning written out so far (in time order, to the
+  int32_t n_fixed_words; // channel's fixed_arcs / fixed_words rows)
 };
 static_assert(sizeof(ChanState) == 128, "one channel's state fills one 128-byte line");
 
@@ -131,9 +132,13 @@ struct AdvanceParams {
   uint64_t *g_hval;
   uint32_t *g_hidx;
   int32_t *auto_snap;      // [grid][kSnapInts] or null: where each workgroup leaves its channel's best token when done
+  int2 *new_records;       // [C] or null (pinned host memory): x = the channel's records above gc_base after this
+  int32_t call_seq;        //     call, y = call_seq: lets the host decide when to compact without waiting for anything
 };
 
-constexpr int kSnapInts = 8;   // a best-token snapshot: status, best record, cost bits, records in use, channel
+constexpr int kSnapInts = 8;   // a best-token snapshot: status, best record, cost bits, records in use, channel,
+                               // gc_base, fixed arcs, fixed words
+constexpr int kMetaInts = 8;   // a result's header: status, arcs, words, cost bits, fixed arcs, fixed words
 
 constexpr int kBigRows = 32;      // slots for such rows per frame
 constexpr int kBigRowArcs = 512;  // a row with more arcs than this is shared out over all waves
@@ -1182,9 +1187,11 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   }
   __syncthreads();
   if (sh->status != kStatusOk) {  // uniform: the channel is parked until reset
+    if (p.new_records && tid == 0) p.new_records[c] = make_int2(0, p.call_seq);
     if (p.auto_snap && tid == 0) {
       int32_t *snap = p.auto_snap + (size_t)blockIdx.x * kSnapInts;
       snap[0] = sh->status; snap[1] = -1; snap[2] = (int)0xFFFFFFFFu; snap[3] = cs->n_rec; snap[4] = c;
+      snap[5] = 0; snap[6] = 0; snap[7] = 0;
     }
     return;
   }
@@ -1278,13 +1285,14 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     if (p.do_reset) {
       cs->frames = 0; cs->active_tokens = 0; cs->emit_arcs = 0; cs->eps_arcs = 0; cs->candidates = 0;
       cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0; cs->slow_frames = 0;
-      cs->gc_base = 0; cs->gc_runs = 0; cs->gc_dropped = 0;
+      cs->gc_base = 0; cs->gc_runs = 0; cs->gc_dropped = 0; cs->n_fixed_arcs = 0; cs->n_fixed_words = 0;
     }
     cs->frames += sh->a_frames; cs->active_tokens += sh->a_active; cs->emit_arcs += sh->a_emit;
     cs->eps_arcs += sh->a_eps; cs->candidates += sh->a_cand; cs->improvements += sh->a_impr;
     cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
     if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
     cs->slow_frames += sh->a_slow;
+    if (p.new_records) p.new_records[c] = make_int2(sh->n_rec - (p.do_reset ? 0 : cs->gc_base), p.call_seq);
   }
   // Sec. 1 / 3.2: the partial result is the best current token's sequence.  The workgroup leaves that token
   // here (arg-min of (cost, arc) over its final table, as the stand-alone snapshot kernel would find it), so a
@@ -1318,6 +1326,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         snap[1] = besti < 0 ? -1 : sh->frame_base + besti;
         snap[2] = (int)(uint32_t)(bestk >> 32);
         snap[3] = sh->n_rec; snap[4] = c;
+        snap[5] = cs->gc_base; snap[6] = cs->n_fixed_arcs; snap[7] = cs->n_fixed_words;
       }
     }
   }
@@ -1445,7 +1454,8 @@ struct BestParams {
   int32_t row_pitch;        // entries between consecutive output rows (>= capacity)
   int32_t *out_arcs;        // [n][row_pitch]
   int32_t *out_words;       // [n][row_pitch]
-  int32_t *out_meta;        // [n][4]: status, n_arcs, n_words, cost bits
+  int32_t *out_meta;        // [n][kMetaInts]: status, n_arcs, n_words, cost bits, fixed arcs, fixed words
+  int32_t tail_only;        // 1: the path is followed down to the paths' shared beginning only (see the compaction)
   int32_t *snap;            // [n][kSnapInts] snapshot taken on the decode stream (two-stage form only)
 };
 
@@ -1516,14 +1526,15 @@ __device__ __forceinline__ void walk_read_ahead(const BestParams &p, int i, int 
     if (low < 0) low = 0;
   }
   // (keeps the reads: the value is never this one)
-  if (sink == 0x5A17C0DE && lane == 0) p.out_meta[(size_t)i * 4 + 3] = sink;
+  if (sink == 0x5A17C0DE && lane == 0) p.out_meta[(size_t)i * kMetaInts + 3] = sink;
 }
 
 // Back-pointer walk from record `rec` and labels in time order.  One wave.  Only records below
 // n_rec are touched (they never change once written), so this may run beside later decoding.
 __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int rec, int n_rec, uint32_t cost_ord,
-                                          int lane, int *walk_pos, int *walk_arcs) {
-  int32_t *meta = p.out_meta + (size_t)i * 4;
+                                          int lane, int *walk_pos, int *walk_arcs, int stop_below) {
+  // stop_below: records below this one are not followed (0: the whole path)
+  int32_t *meta = p.out_meta + (size_t)i * kMetaInts;
   int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
   int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
   const int2 *bp = p.bp + (size_t)c * p.bp_cap;
@@ -1538,10 +1549,10 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
     // together.  (A store to device memory per step would sit in the chain: the wait for the next record also
     // waits for the store before it.)
     int r = rec;
-    while (r >= 0 && na <= max_steps) {   // uniform
+    while (r >= stop_below && na <= max_steps) {   // uniform
       int n_chunk = 0;
       if (lane == 0) {
-        while (r >= 0 && na + n_chunk <= max_steps && n_chunk < kWalkChunk) {
+        while (r >= stop_below && na + n_chunk <= max_steps && n_chunk < kWalkChunk) {
           int2 e = bp[r];
           // where the walk is, for the wave that reads ahead of it (an atomic store: a plain one is dropped)
           __hip_atomic_store(walk_pos, r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -1615,8 +1626,12 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = blockIdx.x;
   const int c = p.chan_ids[i];
   const ChanState *cs = p.chan + c;
-  int32_t *meta = p.out_meta + (size_t)i * 4;
+  int32_t *meta = p.out_meta + (size_t)i * kMetaInts;
   const int inf_bits = (int)__float_as_uint(__builtin_inff());
+  if (threadIdx.x == 0) {
+    meta[4] = p.tail_only ? cs->n_fixed_arcs : 0;
+    meta[5] = p.tail_only ? cs->n_fixed_words : 0;
+  }
   if (cs->status != kStatusOk) {   // (uniform)
     if (threadIdx.x == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
@@ -1636,7 +1651,8 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
     if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
-  walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane, &s_walk_pos, s_walk_arcs);
+  walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane, &s_walk_pos, s_walk_arcs,
+            p.tail_only ? cs->gc_base : 0);
 }
 
 // Two-stage form for results delivered beside later decoding.  Stage 1 (decode stream): pick the
@@ -1654,6 +1670,7 @@ __global__ __launch_bounds__(64) void best_snapshot_kernel(BestParams p) {
   }
   if (lane == 0) {
     snap[0] = status; snap[1] = rec; snap[2] = (int)(uint32_t)(key >> 32); snap[3] = cs->n_rec; snap[4] = c;
+    snap[5] = cs->gc_base; snap[6] = cs->n_fixed_arcs; snap[7] = cs->n_fixed_words;
   }
 }
 
@@ -1663,7 +1680,11 @@ __global__ __launch_bounds__(kWalkThreads) void best_walk_kernel(BestParams p) {
   __shared__ int s_walk_arcs[kWalkChunk];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, i = blockIdx.x;
   const int32_t *snap = p.snap + (size_t)i * kSnapInts;
-  int32_t *meta = p.out_meta + (size_t)i * 4;
+  int32_t *meta = p.out_meta + (size_t)i * kMetaInts;
+  if (threadIdx.x == 0) {
+    meta[4] = p.tail_only ? snap[6] : 0;
+    meta[5] = p.tail_only ? snap[7] : 0;
+  }
   if (snap[0] != kStatusOk) {   // (uniform)
     if (threadIdx.x == 0) { meta[0] = snap[0]; meta[1] = 0; meta[2] = 0; meta[3] = (int)__float_as_uint(__builtin_inff()); }
     return;
@@ -1674,7 +1695,8 @@ __global__ __launch_bounds__(kWalkThreads) void best_walk_kernel(BestParams p) {
     walk_read_ahead(p, i, snap[4], lane, &s_walk_pos);
     return;
   }
-  walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane, &s_walk_pos, s_walk_arcs);
+  walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane, &s_walk_pos, s_walk_arcs,
+            p.tail_only ? snap[5] : 0);
 }
 
 // ---- compaction of the back-pointer records ------------------------------------------
@@ -1702,8 +1724,13 @@ struct CompactParams {
   uint32_t *prefix;         // [C][mark_words] marked records before each bitmap word
   int32_t *cross;           // [C][mark_words + 2] marked links crossing the place before each bitmap word
   int32_t bp_cap, tok_cap, mark_words;
-  int32_t min_new;          // channels with at most this many records above gc_base are left alone ...
-  const int32_t *any_due;   // ... or, where this is given and reads non-zero, with at most half as many
+  int32_t min_new;          // channels with at most this many records above gc_base are left alone
+  // the shared beginning of the paths, written out in time order as it is found (append-only per utterance)
+  int32_t *fixed_arcs;      // [C][fixed_cap] arcs, caller's numbering
+  int32_t *fixed_words;     // [C][fixed_cap] their word labels
+  int32_t fixed_cap;
+  const int32_t *olabel;    // library arc order
+  const int32_t *int2pub;   // library arc order -> caller's numbering
 };
 
 constexpr int kCompactBlock = 1024;
@@ -1752,28 +1779,9 @@ __device__ __forceinline__ int compact_block_scan(int v, int &excl, int *s_tot, 
   return total;
 }
 
-// A compaction holds up its call for as long as one lane needs to walk the frames since the last one, however
-// many channels take part.  So when one channel of a call is due, those that are half-way there join in: the
-// channels of a call then compact in the same calls rather than each delaying a call of its own.
-// One workgroup: *any_due = some listed channel has more than min_new records above its gc_base.
-__global__ __launch_bounds__(256) void compact_due_kernel(const ChanState *chan, const int32_t *chan_ids, int n,
-                                                          int32_t min_new, int32_t *any_due) {
-  __shared__ int s_due;
-  if (threadIdx.x == 0) s_due = 0;
-  __syncthreads();
-  int due = 0;
-  for (int i = threadIdx.x; i < n; i += 256) {
-    const ChanState *cs = chan + chan_ids[i];
-    if (cs->status == kStatusOk && cs->n_rec - cs->gc_base > min_new) due = 1;
-  }
-  if (due) s_due = 1;
-  __syncthreads();
-  if (threadIdx.x == 0) *any_due = s_due;
-}
-
 __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactParams p) {
   __shared__ int s_tot[kCompactBlock / 64];
-  __shared__ int s_cut;
+  __shared__ int s_cut, s_top;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
@@ -1781,8 +1789,7 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
   const int n_tok = cs->n_tok, fb = cs->frame_base, n_rec = cs->n_rec, g0 = cs->gc_base;
   const int young = fb - g0;      // records examined
   const int n_cur = n_rec - fb;   // records of the current frame
-  const int min_new = (p.any_due && *p.any_due) ? p.min_new / 2 : p.min_new;
-  if (young <= 0 || n_rec - g0 <= min_new) return;
+  if (young <= 0 || n_rec - g0 <= p.min_new) return;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
   const float *tc = p.tok_cost + (size_t)c * p.tok_cap;
   uint32_t *mark = p.mark + (size_t)c * p.mark_words;
@@ -1793,7 +1800,7 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
 
   for (int i = tid; i < W; i += kCompactBlock) mark[i] = 0;
   for (int i = tid; i < B + 2; i += kCompactBlock) cross[i] = 0;
-  if (tid == 0) s_cut = -1;
+  if (tid == 0) { s_cut = -1; s_top = -1; }
   __syncthreads();
   // mark: from every live token's record, back to the first record that is already marked or lies below gc_base.
   // Links inside the current frame (epsilon-input arcs) are not followed: their targets are tokens with walks of
@@ -1849,7 +1856,31 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
   const int new_fb = g0 + n_keep;
   // marked records below the highest place that a single link crosses: the new part of the shared beginning
   const int cut = s_cut;
-  const int n_fixed = cut < 0 ? 0 : (cut < W ? (int)ld_agent_u32(&prefix[cut]) : n_keep);
+  int n_fixed = cut < 0 ? 0 : (cut < W ? (int)ld_agent_u32(&prefix[cut]) : n_keep);
+  // The new part of the shared beginning will be written out in time order: that takes its uppermost record, the
+  // lower end of the one link that crosses the cut.  (Record 0, the start token's, carries no arc.)
+  const int n_new_arcs = n_fixed - (g0 == 0 && n_fixed > 0 ? 1 : 0);
+  const int nf_arcs = cs->n_fixed_arcs, nf_words = cs->n_fixed_words;
+  if (nf_arcs + n_new_arcs > p.fixed_cap) n_fixed = 0;   // (uniform) no room to write it out: leave it for later
+  if (n_fixed > 0) {
+    const int edge = cut << 5;   // examined records below this one are the new part
+    for (int w = cut + tid; w < W; w += kCompactBlock) {
+      uint32_t m = ld_agent_u32(&mark[w]);
+      while (m) {
+        const int r = (w << 5) + __builtin_ctz(m);
+        m &= m - 1u;
+        const int u = bp[g0 + r].y;
+        if (u >= g0 && u - g0 < edge) s_top = u - g0;
+      }
+    }
+    for (int i = tid; i < n_tok && i < n_cur; i += kCompactBlock) {
+      if (!(tc[i] < __builtin_inff())) continue;
+      const int u = bp[fb + i].y;
+      if (u >= g0 && u < fb && u - g0 < edge) s_top = u - g0;
+    }
+    __syncthreads();
+    if (s_top < 0) n_fixed = 0;   // (uniform; cannot happen while the marked records below the cut are one chain)
+  }
   if (n_keep < young) {   // (uniform) something to drop
     // Move the kept records down, a tile at a time: a record never moves up, so a tile's destinations lie
     // below every record that a later tile reads; the barrier keeps them off the tile's own sources.
@@ -1901,12 +1932,51 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
     }
   }
   __syncthreads();   // every wave is done with the channel's old numbers
+  int nw_new = 0;
+  bool wrote = true;
+  if (n_fixed > 0 && n_new_arcs > 0 && tid < 64) {
+    // Lane 0 follows the new part down from its uppermost record (these records were written a moment ago and sit
+    // in L2) and writes the arcs where they belong in time order; the wave then adds the word labels and turns
+    // the arcs into the caller's numbers.
+    int32_t *fa = p.fixed_arcs + (size_t)c * p.fixed_cap + nf_arcs;
+    int32_t *fw = p.fixed_words + (size_t)c * p.fixed_cap + nf_words;
+    if (lane == 0) {
+      int r = compact_remap(g0 + s_top, g0, fb, new_fb, mark, prefix);
+      int k = 0;
+      while (r >= g0 && k < n_new_arcs) {
+        const unsigned long long e = __hip_atomic_load((const unsigned long long *)&bp[r], __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t arc = (uint32_t)e;
+        if (arc != kArcNone) fa[n_new_arcs - 1 - k++] = (int)arc;
+        r = (int)(uint32_t)(e >> 32);
+      }
+      wrote = k == n_new_arcs;   // else the records were not the chain they should be: nothing is declared fixed
+    }
+    wrote = __shfl((int)wrote, 0, 64) != 0;
+    __threadfence_block();
+    for (int j0 = 0; j0 < n_new_arcs; j0 += 64) {
+      const int j = j0 + lane;
+      int w = 0, a = 0;
+      if (j < n_new_arcs && wrote) {
+        a = fa[j];
+        w = p.olabel[a];
+      }
+      const unsigned long long wm = __ballot(w != 0);
+      if (w != 0) fw[nw_new + __popcll(wm & ((1ull << lane) - 1ull))] = w;
+      nw_new += __popcll(wm);
+      if (j < n_new_arcs && wrote) fa[j] = p.int2pub[a];
+    }
+  }
   if (tid == 0) {
     cs->frame_base = new_fb;
     cs->n_rec = new_fb + n_cur;
-    cs->gc_base = g0 + n_fixed;
     cs->gc_runs += 1;
     cs->gc_dropped += young - n_keep;
+    if (n_fixed > 0 && wrote) {
+      cs->gc_base = g0 + n_fixed;
+      cs->n_fixed_arcs = nf_arcs + n_new_arcs;
+      cs->n_fixed_words = nf_words + nw_new;
+    }
   }
 }
 

@@ -51,9 +51,10 @@ class Session:
     def __init__(self, inp: Inputs, hash_log2: Optional[int] = None, table_location: int = 0,
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
                  context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0,
-                 compact_records_above: int = 0, record_frames: int = 0):
+                 compact_records_above: int = 0, record_frames: int = 0, tail_partials: bool = False):
         """compact_records_above / record_frames: automatic compaction of the back-pointer records, and the number
-        of frames the record buffer is sized for (0: the whole utterance).
+        of frames the record buffer is sized for (0: the whole utterance).  tail_partials: partial results through
+        cbd_best_tails_begin / _finish (only the part of the path above what the compactions have fixed).
         context_mode: "upload" sends every segment's lists with cbd_set_contexts; "pool" loads all
         segments' lists once with cbd_contexts_create and switches by id (Sec. 4.3)."""
         import torch
@@ -74,6 +75,9 @@ class Session:
             hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode
         self.async_partials = async_partials   # partial results through cbd_best_paths_begin / _finish
+        self.begin_partial = B.cbd_best_tails_begin if tail_partials else B.cbd_best_paths_begin
+        self.finish_partial = B.cbd_best_tails_finish if tail_partials else B.cbd_best_paths_finish
+        self.sync_partial = B.cbd_best_tails if tail_partials else B.cbd_best_paths
         # contexts packed once: per segment (arc_idx, list_offsets)
         self.packed = [B.pack_lists(lists) for lists, _ in inp.contexts]
         self.pool_ids = None
@@ -138,18 +142,18 @@ class Session:
                         # The previous request is collected first: its copies are queued on the side stream and
                         # must not end up behind the walk that is about to be queued there.
                         if pending is not None:
-                            r = B.cbd_best_paths_finish(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
+                            r = self.finish_partial(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
                             if keep_results:
                                 self.partials.append((s, pending[1], r))
-                        tk = B.cbd_best_paths_begin(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
+                        tk = self.begin_partial(self.dh, self.all, False, self.capacity, want_arcs=keep_results)
                         pending = (tk, t)
                     else:
-                        r = B.cbd_best_paths(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
-                                             buffers=self.buffers, as_lists=keep_results)
+                        r = self.sync_partial(self.dh, self.all, False, self.capacity, want_arcs=keep_results,
+                                              buffers=self.buffers, as_lists=keep_results)
                         if keep_results:
                             self.partials.append((s, t, r))
             if pending is not None:
-                r = B.cbd_best_paths_finish(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
+                r = self.finish_partial(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
                 if keep_results:
                     self.partials.append((s, pending[1], r))
             r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results,

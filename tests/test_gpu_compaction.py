@@ -256,3 +256,66 @@ def test_compaction_beside_asynchronous_requests_and_parked_channels(torch_cuda)
         assert small.best(0)[0] == B.CBD_E_CAPACITY
     finally:
         small.close()
+
+
+def test_tails_plus_fixed_part_are_the_whole_results(torch_cuda):
+    """Results in two parts (Sec. 1 / 3.2: the intermediate result is the best current token's sequence): what the
+    compactions have found to be common to all paths, kept by the library in time order, and the rest of the best
+    path.  Put together they must be the checker's partial result at every chunk, for channels that are compacted
+    every chunk, sometimes, or never; the fixed part only ever grows; requests begun before a compaction are put
+    together with the fixed part as it was then."""
+    torch = torch_cuda
+    C, T, chunk = 4, 400, 10
+    g, L, ctxs, offs = inputs(C, T, seed=34, finals=True)
+    Lh = L.cpu().numpy()
+    dec = GH.GpuDecoder(g, C, 12.0, 250, max_frames=T)
+    try:
+        og = OracleGraph.from_graph(g)
+        orcs = GH.oracle_channels(g, C, 12.0, 250, og=og)
+        dec.set_contexts(ctxs, offs)
+        dec.reset()
+        for c in range(C):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset()
+        fixed = [(np.zeros(0, np.int32), np.zeros(0, np.int32)) for _ in range(C)]
+
+        def whole(c, res, i=None):
+            st, wl, al, cost, na, nw, nfw, nfa = res
+            i = c if i is None else i
+            fw, fa = fixed[c]
+            assert nfw[i] <= fw.size and nfa[i] <= fa.size
+            return (int(st[i]), np.concatenate([fw[:nfw[i]], wl[i]]), np.concatenate([fa[:nfa[i]], al[i]]), float(cost[i]))
+
+        for k, t in enumerate(range(0, T, chunk)):
+            dec.advance(L, t, t + chunk)
+            for c in range(C):
+                orcs[c].advance(Lh[c, t:t + chunk])
+            ticket = B.cbd_best_tails_begin(dec.dh, dec.all, False, capacity=4 * T)   # before this chunk's compaction
+            dec.compact(np.array([0], np.int32))
+            if k % 7 == 3:
+                dec.compact(np.array([2, 3], np.int32))
+            for c in range(C):     # the fixed part only grows
+                fw, fa = B.cbd_get_fixed(dec.dh, c)
+                assert np.array_equal(fw[:fixed[c][0].size], fixed[c][0]) and np.array_equal(fa[:fixed[c][1].size], fixed[c][1])
+                more_w, more_a = B.cbd_get_fixed(dec.dh, c, fixed[c][0].size, fixed[c][1].size)   # asking for the rest only
+                assert np.array_equal(np.concatenate([fixed[c][0], more_w]), fw)
+                assert np.array_equal(np.concatenate([fixed[c][1], more_a]), fa)
+                fixed[c] = (fw, fa)
+            before = B.cbd_best_tails_finish(dec.dh, ticket)
+            after = B.cbd_best_tails(dec.dh, dec.all, False, capacity=4 * T)
+            for c in range(C):
+                want = orcs[c].best_path(False)
+                GH.assert_best_equal(whole(c, before), want, f"t={t + chunk} ch={c} begun before the compaction")
+                GH.assert_best_equal(whole(c, after), want, f"t={t + chunk} ch={c} after the compaction")
+        final = B.cbd_best_tails(dec.dh, dec.all, True, capacity=4 * T)
+        for c in range(C):
+            GH.assert_best_equal(whole(c, final), orcs[c].best_path(True), f"final ch={c}")
+            GH.assert_best_equal(dec.best(c, True), orcs[c].best_path(True), f"final ch={c}, whole path")
+        st, wl, al, cost, na, nw, nfw, nfa = final
+        assert nfa[1] == 0 and na[1] >= T                # never compacted: nothing fixed, the tail is the path
+        assert nfa[0] > 0.9 * (nfa[0] + na[0])           # compacted every chunk: the tail is what is still open
+        assert 0 < nfa[2] and nfa[3] > 0
+        # a new utterance starts with an empty fixed part
+        dec.reset(np.array([0], np.int32))
+        assert B.cbd_get_fixed(dec.dh, 0)[1].size == 0 and B.cbd_get_fixed(dec.dh, 2)[1].size == nfa[2]
+    finally:
+        dec.close()
