@@ -118,11 +118,12 @@ typedef struct cbd_config {
                                  gets a smaller table): 1, 2 or 4; 0 = chosen by the library (1 while the decoder has
                                  no more channels than the device has compute units, else 2) */
   int32_t compact_records_above; /* 0 = records are only compacted on request (cbd_compact_records); N > 0 = a
-                                 cbd_advance call first compacts its channels once one of them holds more than N
-                                 records above the part its paths share, and with it (so that a call is held up
-                                 once, not once per channel) those that hold more than N / 2.  The counts are the
-                                 ones finished launches have reported, so the mark may be overshot by the records
-                                 of the calls still in flight: size the buffer with that room */
+                                 cbd_advance call first compacts those of its channels that hold more than N records
+                                 above the part their paths share, and with them (so that a call is held up once,
+                                 not once per channel) those that hold more than N / 2.  While the counts that
+                                 recent launches have reported show nothing due, the call does not even look (and
+                                 asynchronous result walks keep running beside the decoding); N may therefore be
+                                 overshot by the records of a few calls: size the buffer with that room */
 } cbd_config;
 
 /*

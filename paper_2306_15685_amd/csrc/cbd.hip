@@ -141,6 +141,7 @@ struct cbd_decoder {
   // automatic compaction: each decoding launch leaves (records above gc_base, call number) per channel here (pinned
   // host memory the kernel writes to), so cbd_advance can tell when a compaction is due without synchronising
   int2 *h_new = nullptr, *dv_new = nullptr;
+  unsigned long long *d_due_max = nullptr;   // the same for the device: (call number, largest count of that call)
   int64_t last_compact_call = -1;
   // the shared beginning of each channel's paths in time order, as the compactions find it ([C][bp_cap] each)
   int32_t *d_fixed_arcs = nullptr, *d_fixed_words = nullptr;
@@ -321,7 +322,8 @@ int32_t stage_channels(cbd_decoder *d, const int32_t *channels, int32_t n, const
 
 // Enqueues the record compaction for the channels in `dev` (a staged list of n).  It renumbers records, so the
 // stream first waits for every unfinished asynchronous walk, and snapshots left by earlier calls are retired.
-int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_t min_new) {
+// due_seq >= 0: channels half-way to min_new join in if call due_seq left a count above min_new (automatic mode).
+int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_t min_new, int64_t due_seq = -1) {
   d->gc_words = (d->bp_cap + 31) / 32;
   if (!d->d_gc_mark) HIPCHK(dmalloc(&d->d_gc_mark, (size_t)d->C * d->gc_words, &d->bytes));
   if (!d->d_gc_prefix) HIPCHK(dmalloc(&d->d_gc_prefix, (size_t)d->C * d->gc_words, &d->bytes));
@@ -337,6 +339,7 @@ int32_t enqueue_compaction(cbd_decoder *d, const int32_t *dev, int32_t n, int32_
   cp.bp_cap = d->bp_cap; cp.tok_cap = d->g_tok_cap; cp.mark_words = d->gc_words; cp.min_new = min_new;
   cp.fixed_arcs = d->d_fixed_arcs; cp.fixed_words = d->d_fixed_words; cp.fixed_cap = d->bp_cap;
   cp.olabel = d->g->d_olabel; cp.int2pub = d->g->d_int2pub;
+  if (due_seq >= 0) { cp.due_max = d->d_due_max; cp.due_seq = (int32_t)due_seq; }
   hipLaunchKernelGGL(cbd::compact_records_kernel, dim3((unsigned)n), dim3(cbd::kCompactBlock), 0, d->stream, cp);
   HIPCHK(hipGetLastError());
   return CBD_OK;
@@ -680,6 +683,8 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     DCHK(hipHostMalloc((void **)&d->h_new, sizeof(int2) * C, hipHostMallocDefault));
     memset(d->h_new, 0, sizeof(int2) * C);
     DCHK(hipHostGetDevicePointer((void **)&d->dv_new, d->h_new, 0));
+    DCHK(dmalloc(&d->d_due_max, 1, &d->bytes));
+    DCHK(hipMemsetAsync(d->d_due_max, 0, sizeof(unsigned long long), d->stream));
   }
   DCHK(d->ids.init(sizeof(int32_t) * C));
   // context staging: [channels n][list offsets n+1][offsets n][lists ...]
@@ -695,7 +700,7 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   (void)hipStreamSynchronize(d->stream);
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
-                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words};
+                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words, d->d_due_max};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->side) (void)hipStreamSynchronize(d->side);
@@ -733,7 +738,7 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
     if (d->out[k].pending) HIPCHK(hipStreamWaitEvent(d->stream, d->out[k].done, 0));
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = nullptr; p.channel_stride = 0; p.n_frames = 0; p.do_reset = 1;
-  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls;
+  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls; p.due_max = d->d_due_max;
   rc = claim_snapshot_slot(d, channels, n, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n));
@@ -1001,27 +1006,33 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   int slot = 0;
   int32_t rc = stage_channels(d, channels, n_channels, &dev, &slot);
   if (rc != CBD_OK) return rc;
-  if (d->cfg.compact_records_above > 0) {
-    // Each finished launch has left its channels' record counts in host memory.  When one of this call's channels is
-    // over the mark, all of them that are half-way there are compacted now: a compaction holds up the call for one
-    // lane's walk however many channels take part, so they had better take part together.  Counts written before
-    // the last compaction say nothing (their launch ran before it) and are skipped.
+  if (d->cfg.compact_records_above > 0 && d->adv_calls > 0) {
+    // Whether a channel is due is decided on the device, from the counts the previous launch left there: the
+    // compaction kernel is enqueued and its workgroups return at once where nothing is to do.  But enqueueing it
+    // makes the stream wait for unfinished partial-result walks, which otherwise run beside the decoding.  So each
+    // launch also leaves its channels' counts in host memory, and while the counts of one of the last two calls
+    // are in and none is over the mark, the kernel is not enqueued at all (the mark may then be overshot by the
+    // records of a few calls).  Counts written before the last compaction are recognised by their call number.
     const int32_t mark = d->cfg.compact_records_above;
-    bool due = false;
-    for (int32_t i = 0; i < n_channels && !due; ++i) {
+    // (right after the kernel was enqueued the counts in host memory are still the old ones: nothing can be due)
+    bool skip = d->last_compact_call >= 0 && d->adv_calls - d->last_compact_call <= 2;
+    for (int32_t i = 0; i < n_channels && !skip; ++i) {
       const volatile int2 *e = d->h_new + channels[i];
       const int32_t count = e->x, call = e->y;
-      due = count > mark && (int32_t)((uint32_t)call - (uint32_t)d->last_compact_call) >= 0;   // (call numbers wrap)
+      const int32_t age = (int32_t)((uint32_t)d->adv_calls - (uint32_t)call);   // (call numbers wrap)
+      const bool since_compaction = (int32_t)((uint32_t)call - (uint32_t)d->last_compact_call) >= 0;
+      if (!(age >= 1 && age <= 2 && since_compaction && count <= mark)) break;
+      if (i == n_channels - 1) skip = true;
     }
-    if (due) {
-      rc = enqueue_compaction(d, dev, n_channels, mark / 2);
+    if (!skip) {
+      rc = enqueue_compaction(d, dev, n_channels, mark, d->adv_calls - 1);
       if (rc != CBD_OK) return rc;
       d->last_compact_call = d->adv_calls;   // (the number this call is about to take)
     }
   }
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
-  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls;
+  p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls; p.due_max = d->d_due_max;
   rc = claim_snapshot_slot(d, channels, n_channels, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n_channels));

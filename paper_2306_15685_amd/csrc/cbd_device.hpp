@@ -133,7 +133,8 @@ struct AdvanceParams {
   uint32_t *g_hidx;
   int32_t *auto_snap;      // [grid][kSnapInts] or null: where each workgroup leaves its channel's best token when done
   int2 *new_records;       // [C] or null (pinned host memory): x = the channel's records above gc_base after this
-  int32_t call_seq;        //     call, y = call_seq: lets the host decide when to compact without waiting for anything
+  int32_t call_seq;        //     call, y = call_seq: lets the host see when no compaction is due without waiting
+  unsigned long long *due_max;  // or null: (call_seq << 32 | largest such count among the call's channels)
 };
 
 constexpr int kSnapInts = 8;   // a best-token snapshot: status, best record, cost bits, records in use, channel,
@@ -1292,7 +1293,9 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
     if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
     cs->slow_frames += sh->a_slow;
-    if (p.new_records) p.new_records[c] = make_int2(sh->n_rec - (p.do_reset ? 0 : cs->gc_base), p.call_seq);
+    const int n_new = sh->n_rec - (p.do_reset ? 0 : cs->gc_base);
+    if (p.new_records) p.new_records[c] = make_int2(n_new, p.call_seq);
+    if (p.due_max) atomicMax(p.due_max, ((unsigned long long)(uint32_t)p.call_seq << 32) | (uint32_t)n_new);
   }
   // Sec. 1 / 3.2: the partial result is the best current token's sequence.  The workgroup leaves that token
   // here (arg-min of (cost, arc) over its final table, as the stand-alone snapshot kernel would find it), so a
@@ -1724,7 +1727,9 @@ struct CompactParams {
   uint32_t *prefix;         // [C][mark_words] marked records before each bitmap word
   int32_t *cross;           // [C][mark_words + 2] marked links crossing the place before each bitmap word
   int32_t bp_cap, tok_cap, mark_words;
-  int32_t min_new;          // channels with at most this many records above gc_base are left alone
+  int32_t min_new;          // channels with at most this many records above gc_base are left alone ...
+  const unsigned long long *due_max;  // ... or with at most half as many, if this (see AdvanceParams; null: not used)
+  int32_t due_seq;                    //     comes from call due_seq and shows a channel above min_new
   // the shared beginning of the paths, written out in time order as it is found (append-only per utterance)
   int32_t *fixed_arcs;      // [C][fixed_cap] arcs, caller's numbering
   int32_t *fixed_words;     // [C][fixed_cap] their word labels
@@ -1789,7 +1794,14 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
   const int n_tok = cs->n_tok, fb = cs->frame_base, n_rec = cs->n_rec, g0 = cs->gc_base;
   const int young = fb - g0;      // records examined
   const int n_cur = n_rec - fb;   // records of the current frame
-  if (young <= 0 || n_rec - g0 <= p.min_new) return;
+  // A compaction holds up its call for as long as one lane needs to walk the frames since the last one, however
+  // many channels take part: so when one channel of the call is due, those half-way there join in.
+  int min_new = p.min_new;
+  if (p.due_max) {
+    const unsigned long long dm = *p.due_max;
+    if ((int32_t)(dm >> 32) == p.due_seq && (int32_t)(uint32_t)dm > p.min_new) min_new = p.min_new / 2;
+  }
+  if (young <= 0 || n_rec - g0 <= min_new) return;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
   const float *tc = p.tok_cost + (size_t)c * p.tok_cap;
   uint32_t *mark = p.mark + (size_t)c * p.mark_words;
