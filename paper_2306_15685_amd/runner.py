@@ -118,6 +118,7 @@ class Session:
         segments into self.step_stats (adds a synchronisation per segment)."""
         w = self.w
         finals = []
+        pending_final = None   # ticket of the previous utterance's final result, still in flight
         self.step_stats = None
         for s in range(w.segments):
             lists, offs = self.inp.contexts[s]
@@ -136,6 +137,13 @@ class Session:
                 n = min(w.chunk, w.frames - t)
                 self._advance(L, t, n)
                 t += n
+                if pending_final is not None:
+                    # the previous utterance's final result: collected now that this utterance's first chunk is
+                    # queued behind it, so the GPU is not left idle while the host reads results
+                    r = B.cbd_best_paths_finish(self.dh, pending_final, buffers=self.buffers, as_lists=keep_results)
+                    pending_final = None
+                    if keep_results:
+                        finals.append(r)
                 if w.partial_every_chunk and t < w.frames:
                     if self.async_partials:
                         # one request in flight: the walk and copy of chunk k overlap the decoding of chunk k+1.
@@ -156,10 +164,14 @@ class Session:
                 r = self.finish_partial(self.dh, pending[0], buffers=self.buffers, as_lists=keep_results)
                 if keep_results:
                     self.partials.append((s, pending[1], r))
-            r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results,
-                                 buffers=self.buffers, as_lists=keep_results)
-            if keep_results:
-                finals.append(r)
+            if self.async_partials and s + 1 < w.segments and not collect_stats:
+                # (the next utterance's reset waits on the device for this walk: it reuses the record buffer)
+                pending_final = B.cbd_best_paths_begin(self.dh, self.all, True, self.capacity, want_arcs=keep_results)
+            else:
+                r = B.cbd_best_paths(self.dh, self.all, True, self.capacity, want_arcs=keep_results,
+                                     buffers=self.buffers, as_lists=keep_results)
+                if keep_results:
+                    finals.append(r)
             if collect_stats:
                 st = self.stats(-1)
                 if self.step_stats is None:
