@@ -1497,39 +1497,42 @@ __device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanS
 constexpr int kWalkDone = -2;
 constexpr int kWalkChunk = 128;   // arcs the walk notes in LDS before the wave writes them out
 
-__device__ __forceinline__ void walk_read_ahead(const BestParams &p, int i, int c, int lane, const int *walk_pos) {
+// One pass of the wave that reads ahead of a walk at record r: asks for the 64-byte lines below `low` (the lowest
+// record asked for so far) that the walk will reach next, never below `floor`.  Returns false when it is far
+// enough ahead.  prev_r: where the walk was at the last pass.
+__device__ __forceinline__ bool read_ahead_pass(const int2 *bp, int r, int floor, int lane, int &prev_r, int &low) {
+  if (low < 0 || r < low) low = r;   // (first pass, or the walk has overtaken the reads)
+  // how far the walk came since the last look tells how far it will be when these reads are back:
+  // stay three such stretches and one span of the wave ahead of it, at most four spans per pass
+  int moved = prev_r < 0 ? 64 : prev_r - r;
+  moved = moved < 64 ? 64 : moved;
+  prev_r = r;
+  int target = r - 3 * moved - 512;
+  target = target < floor ? floor : target;
+  int spans = (low - target + 511) >> 9;
+  spans = spans > 4 ? 4 : spans;
+  if (spans <= 0) return false;
+  // (always four reads, all under way together; spans not wanted yet repeat the first one's addresses)
+  int v[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int q = low - 8 - lane * 8 - (k < spans ? k : 0) * 512;
+    v[k] = bp[q < floor ? floor : q].x;
+  }
+  asm volatile("" ::"v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]));   // (the values are not used: this keeps the reads)
+  low -= spans * 512;
+  if (low < floor) low = floor;
+  return true;
+}
+
+__device__ __forceinline__ void walk_read_ahead(const BestParams &p, int c, int lane, const int *walk_pos) {
   const int2 *bp = p.bp + (size_t)c * p.bp_cap;
-  int sink = 0;
-  int prev_r = -1, low = -1;   // where the walk was a moment ago; the lowest record asked for so far
+  int prev_r = -1, low = -1;
   for (;;) {
     const int r = __hip_atomic_load(walk_pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     if (r == kWalkDone) break;
-    if (low < 0 || r < low) low = r;   // (first pass, or the walk has overtaken the reads)
-    // how far the walk came since the last look tells how far it will be when these reads are back:
-    // stay three such stretches and one span of the wave ahead of it, at most four spans per pass
-    int moved = prev_r < 0 ? 64 : prev_r - r;
-    moved = moved < 64 ? 64 : moved;
-    prev_r = r;
-    const int target = r - 3 * moved - 512;
-    int spans = (low - target + 511) >> 9;
-    spans = spans > 4 ? 4 : spans;
-    if (spans <= 0) {   // far enough ahead: look again shortly
-      __builtin_amdgcn_s_sleep(8);
-      continue;
-    }
-    // (always four reads, all under way together; spans not wanted yet repeat the first one's addresses)
-    int v[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int q = low - 8 - lane * 8 - (k < spans ? k : 0) * 512;
-      v[k] = bp[q < 0 ? 0 : q].x;
-    }
-    sink ^= v[0] ^ v[1] ^ v[2] ^ v[3];
-    low -= spans * 512;
-    if (low < 0) low = 0;
+    if (!read_ahead_pass(bp, r, 0, lane, prev_r, low)) __builtin_amdgcn_s_sleep(8);   // look again shortly
   }
-  // (keeps the reads: the value is never this one)
-  if (sink == 0x5A17C0DE && lane == 0) p.out_meta[(size_t)i * kMetaInts + 3] = sink;
 }
 
 // Back-pointer walk from record `rec` and labels in time order.  One wave.  Only records below
@@ -1647,7 +1650,7 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
   }
   __syncthreads();
   if (wave == 1) {
-    walk_read_ahead(p, i, c, lane, &s_walk_pos);
+    walk_read_ahead(p, c, lane, &s_walk_pos);
     return;
   }
   if (rec < 0) {
@@ -1695,7 +1698,7 @@ __global__ __launch_bounds__(kWalkThreads) void best_walk_kernel(BestParams p) {
   if (threadIdx.x == 0) s_walk_pos = snap[1];
   __syncthreads();
   if (wave == 1) {
-    walk_read_ahead(p, i, snap[4], lane, &s_walk_pos);
+    walk_read_ahead(p, snap[4], lane, &s_walk_pos);
     return;
   }
   walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane, &s_walk_pos, s_walk_arcs,
@@ -1740,6 +1743,8 @@ struct CompactParams {
 
 constexpr int kCompactBlock = 1024;
 constexpr int kCompactPerThread = 4;
+constexpr int kCompactStage = 4096;   // records the workgroup stages in LDS
+constexpr int kCompactLdsWords = 16384;   // bitmap words (32 records each) the marking keeps in LDS
 
 __device__ __forceinline__ uint32_t ld_agent_u32(const uint32_t *p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1786,7 +1791,9 @@ __device__ __forceinline__ int compact_block_scan(int v, int &excl, int *s_tot, 
 
 __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactParams p) {
   __shared__ int s_tot[kCompactBlock / 64];
-  __shared__ int s_cut, s_top;
+  __shared__ int s_cut, s_top, s_pos, s_done;
+  __shared__ int2 s_stage[kCompactStage];
+  __shared__ uint32_t s_mark[kCompactLdsWords];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
@@ -1810,25 +1817,64 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
   const int W = (young + 31) >> 5;   // bitmap words in use (<= mark_words: the host sizes them for bp_cap records)
   const int B = young >> 5;          // places 0..B: place b lies before examined record 32 b
 
-  for (int i = tid; i < W; i += kCompactBlock) mark[i] = 0;
+  // While the walks run, the bitmap is in LDS if it fits (a walk's step then waits for a record from L2 and an LDS
+  // atomic, not for an atomic's trip to device memory); it is copied out afterwards for the passes that follow.
+  const bool lds_marks = W <= kCompactLdsWords;
+  if (lds_marks) {
+    for (int i = tid; i < W; i += kCompactBlock) s_mark[i] = 0;
+  } else {
+    for (int i = tid; i < W; i += kCompactBlock) mark[i] = 0;
+  }
   for (int i = tid; i < B + 2; i += kCompactBlock) cross[i] = 0;
-  if (tid == 0) { s_cut = -1; s_top = -1; }
+  if (tid == 0) { s_cut = -1; s_top = -1; s_pos = fb; s_done = 0; }
   __syncthreads();
   // mark: from every live token's record, back to the first record that is already marked or lies below gc_base.
   // Links inside the current frame (epsilon-input arcs) are not followed: their targets are tokens with walks of
   // their own.  A walk that runs into a loop of predecessors stops at its first marked record like any other.
-  for (int i = tid; i < n_tok && i < n_cur; i += kCompactBlock) {
-    if (!(tc[i] < __builtin_inff())) continue;   // dropped by the frame cutoff
-    int q = bp[fb + i].y;
-    if (q < fb) compact_note_link(cross, q < g0 ? -1 : q - g0, young);
-    while (q >= g0 && q < fb) {
-      const uint32_t r = (uint32_t)(q - g0), bit = 1u << (r & 31);
-      const int nxt = bp[q].y;   // asked for before the mark's answer is in: one round trip per step, not two
-      if (atomicOr(&mark[r >> 5], bit) & bit) break;
-      q = nxt;
+  // The walks soon merge into one lane's chain of dependent reads, a trip to device memory each; as for the
+  // result walks, the last wave reads ahead of the lowest position any walk has reached (s_pos).
+  constexpr int kWalkWaves = kCompactBlock / 64 - 1;
+  if (wave == kWalkWaves) {
+    int prev_r = -1, low = -1;
+    while (__hip_atomic_load(&s_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < kWalkWaves) {
+      const int r = __hip_atomic_load(&s_pos, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (!read_ahead_pass(bp, r, g0, lane, prev_r, low)) __builtin_amdgcn_s_sleep(8);
     }
+  } else {
+    if (lds_marks) {
+      for (int i = tid; i < n_tok && i < n_cur; i += kWalkWaves * 64) {
+        if (!(tc[i] < __builtin_inff())) continue;   // dropped by the frame cutoff
+        int q = bp[fb + i].y;
+        if (q < fb) compact_note_link(cross, q < g0 ? -1 : q - g0, young);
+        while (q >= g0 && q < fb) {
+          const uint32_t r = (uint32_t)(q - g0), bit = 1u << (r & 31);
+          const int nxt = bp[q].y;   // asked for before the mark's answer is in
+          atomicMin(&s_pos, q);
+          if (atomicOr(&s_mark[r >> 5], bit) & bit) break;
+          q = nxt;
+        }
+      }
+    } else {
+      for (int i = tid; i < n_tok && i < n_cur; i += kWalkWaves * 64) {
+        if (!(tc[i] < __builtin_inff())) continue;
+        int q = bp[fb + i].y;
+        if (q < fb) compact_note_link(cross, q < g0 ? -1 : q - g0, young);
+        while (q >= g0 && q < fb) {
+          const uint32_t r = (uint32_t)(q - g0), bit = 1u << (r & 31);
+          const int nxt = bp[q].y;   // asked for before the mark's answer is in: one round trip per step, not two
+          atomicMin(&s_pos, q);
+          if (atomicOr(&mark[r >> 5], bit) & bit) break;
+          q = nxt;
+        }
+      }
+    }
+    if (lane == 0) atomicAdd(&s_done, 1);   // (the wave is through with its tokens)
   }
   __syncthreads();
+  if (lds_marks) {
+    for (int i = tid; i < W; i += kCompactBlock) mark[i] = s_mark[i];
+    __syncthreads();
+  }
   // the links of the marked records (noted here, by all threads, rather than by the walks: the long walk is one
   // lane's chain of dependent loads and should wait for nothing else).  One bitmap word per thread: few bits
   // are set, and a word's records are asked for four at a time.
@@ -1894,34 +1940,37 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
     if (s_top < 0) n_fixed = 0;   // (uniform; cannot happen while the marked records below the cut are one chain)
   }
   if (n_keep < young) {   // (uniform) something to drop
-    // Move the kept records down, a tile at a time: a record never moves up, so a tile's destinations lie
-    // below every record that a later tile reads; the barrier keeps them off the tile's own sources.
-    constexpr int kTile = kCompactBlock * kCompactPerThread;
-    for (int base = 0; base < young; base += kTile) {
-      int2 rec[kCompactPerThread];
-      int dst[kCompactPerThread];
-#pragma unroll
-      for (int k = 0; k < kCompactPerThread; ++k) {
-        const int r = base + k * kCompactBlock + tid;
-        dst[k] = -1;
-        rec[k] = make_int2(0, 0);
-        if (r < young) {
-          const uint32_t bit = 1u << (r & 31);
-          const uint32_t wv = ld_agent_u32(&mark[r >> 5]);
-          if (wv & bit) {
-            rec[k] = bp[g0 + r];
-            dst[k] = g0 + (int)ld_agent_u32(&prefix[r >> 5]) + __popc(wv & (bit - 1u));
+    // Move the kept records down.  Few records are kept, so the bitmap is taken a word per thread, 1024 words at
+    // a time; each thread brings its word's records (with their predecessors renumbered) to LDS, in the order
+    // they will have, and the workgroup writes them out together.  A record never moves up: what is written lies
+    // below every record that is still to be read.  (More than kCompactStage kept records in one stretch of 1024
+    // words take several passes over it.)
+    for (int w0 = 0; w0 < W; w0 += kCompactBlock) {
+      const int w = w0 + tid;
+      const uint32_t m0 = w < W ? ld_agent_u32(&mark[w]) : 0u;
+      const int first = w < W ? (int)ld_agent_u32(&prefix[w]) : 0;   // the new place (above g0) of the word's first record
+      const int t_lo = (int)ld_agent_u32(&prefix[w0]);
+      const int t_hi = w0 + kCompactBlock < W ? (int)ld_agent_u32(&prefix[w0 + kCompactBlock]) : n_keep;
+      for (int lo = t_lo; lo < t_hi; lo += kCompactStage) {   // (uniform)
+        uint32_t m = m0;
+        int k = first;
+        while (m) {
+          const int r = (w << 5) + __builtin_ctz(m);
+          m &= m - 1u;
+          if (k >= lo && k < lo + kCompactStage) {
+            int2 rec = bp[g0 + r];
+            rec.y = compact_remap(rec.y, g0, fb, new_fb, mark, prefix);
+            s_stage[k - lo] = rec;
           }
+          ++k;
         }
+        __syncthreads();
+        const int n_out = t_hi - lo < kCompactStage ? t_hi - lo : kCompactStage;
+        for (int j = tid; j < n_out; j += kCompactBlock) bp[g0 + lo + j] = s_stage[j];
+        __syncthreads();
       }
-#pragma unroll
-      for (int k = 0; k < kCompactPerThread; ++k)
-        if (dst[k] >= 0) rec[k].y = compact_remap(rec[k].y, g0, fb, new_fb, mark, prefix);
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < kCompactPerThread; ++k)
-        if (dst[k] >= 0) bp[dst[k]] = rec[k];
     }
+    constexpr int kTile = kCompactBlock * kCompactPerThread;
     __syncthreads();
     // ... then the current frame's records, in the same way
     for (int base = 0; base < n_cur; base += kTile) {
@@ -1946,21 +1995,37 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
   __syncthreads();   // every wave is done with the channel's old numbers
   int nw_new = 0;
   bool wrote = true;
+  // The new part of the shared beginning now lies in records [g0, g0 + n_fixed).  Lane 0 follows it down from its
+  // uppermost record and writes the arcs where they belong in time order; the wave then adds the word labels and
+  // turns the arcs into the caller's numbers.  The walk runs in LDS where the stretch fits there.
+  const bool staged = n_fixed > 0 && n_fixed <= kCompactStage;
+  if (staged && n_new_arcs > 0) {
+    for (int j = tid; j < n_fixed; j += kCompactBlock) {
+      const unsigned long long e = __hip_atomic_load((const unsigned long long *)&bp[g0 + j], __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+      s_stage[j] = make_int2((int)(uint32_t)e, (int)(uint32_t)(e >> 32));
+    }
+    __syncthreads();
+  }
   if (n_fixed > 0 && n_new_arcs > 0 && tid < 64) {
-    // Lane 0 follows the new part down from its uppermost record (these records were written a moment ago and sit
-    // in L2) and writes the arcs where they belong in time order; the wave then adds the word labels and turns
-    // the arcs into the caller's numbers.
     int32_t *fa = p.fixed_arcs + (size_t)c * p.fixed_cap + nf_arcs;
     int32_t *fw = p.fixed_words + (size_t)c * p.fixed_cap + nf_words;
     if (lane == 0) {
       int r = compact_remap(g0 + s_top, g0, fb, new_fb, mark, prefix);
       int k = 0;
-      while (r >= g0 && k < n_new_arcs) {
-        const unsigned long long e = __hip_atomic_load((const unsigned long long *)&bp[r], __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t arc = (uint32_t)e;
-        if (arc != kArcNone) fa[n_new_arcs - 1 - k++] = (int)arc;
-        r = (int)(uint32_t)(e >> 32);
+      if (staged) {   // (two loops: the one in LDS should not inherit the other's waits for device memory)
+        while (r >= g0 && r < g0 + n_fixed && k < n_new_arcs) {
+          const int2 e = s_stage[r - g0];
+          if ((uint32_t)e.x != kArcNone) fa[n_new_arcs - 1 - k++] = e.x;
+          r = e.y;
+        }
+      } else {
+        while (r >= g0 && r < g0 + n_fixed && k < n_new_arcs) {
+          const unsigned long long v = __hip_atomic_load((const unsigned long long *)&bp[r], __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+          if ((uint32_t)v != kArcNone) fa[n_new_arcs - 1 - k++] = (int)(uint32_t)v;
+          r = (int)(uint32_t)(v >> 32);
+        }
       }
       wrote = k == n_new_arcs;   // else the records were not the chain they should be: nothing is declared fixed
     }

@@ -37,7 +37,7 @@ def mark_and_renumber(arcs, prev, fb, kept_base, live):
     the current frame's (from fb on) stay; of the others, those on a predecessor chain from a live current token.
     Kept records keep their order.  kept_base then moves up past the marked records below the highest place, a
     multiple of 32 records above the old kept_base, that exactly one marked link crosses.
-    -> (arcs, prev, frame_base, n_records, kept_base) after the compaction."""
+    -> (arcs, prev, frame_base, n_records, kept_base) after the compaction, and which records were kept."""
     n = arcs.size
     young = fb - kept_base
     keep = np.zeros(n, bool)
@@ -61,7 +61,7 @@ def mark_and_renumber(arcs, prev, fb, kept_base, live):
         if sum(1 for lo, hi in links if lo < 32 * b <= hi) == 1:
             new_kept = kept_base + int(keep[kept_base:kept_base + 32 * b].sum())
             break
-    return arcs[keep], new_prev, int(new[fb]), int(keep.sum()), new_kept
+    return arcs[keep], new_prev, int(new[fb]), int(keep.sum()), new_kept, keep
 
 
 def top_of_chain(prev, kb):
@@ -317,5 +317,78 @@ def test_tails_plus_fixed_part_are_the_whole_results(torch_cuda):
         # a new utterance starts with an empty fixed part
         dec.reset(np.array([0], np.int32))
         assert B.cbd_get_fixed(dec.dh, 0)[1].size == 0 and B.cbd_get_fixed(dec.dh, 2)[1].size == nfa[2]
+    finally:
+        dec.close()
+
+
+def check_one_compaction(dec, c, where):
+    arcs, prev, fb, kb = dec.records(c)
+    want = mark_and_renumber(arcs, prev, fb, kb, live_mask(dec, c, arcs, fb))
+    dec.compact(np.array([c], np.int32))
+    arcs2, prev2, fb2, kb2 = dec.records(c)
+    assert np.array_equal(arcs2, want[0]) and np.array_equal(prev2, want[1]), where
+    assert fb2 == want[2] and arcs2.size == want[3] and kb2 == want[4], where
+    # (also: the most records kept within one stretch of 32,768 examined records, the unit the kernel moves by)
+    per_stretch = np.add.reduceat(want[5][kb:fb].astype(np.int64), np.arange(0, fb - kb, 32768)) if fb > kb else np.zeros(1)
+    return arcs.size, arcs2.size, kb2 - kb, int(per_stretch.max())
+
+
+def test_compaction_of_a_long_stretch(torch_cuda):
+    """One compaction after 4,500 frames: more records than the bitmap the kernel keeps in LDS covers (524,288), and
+    a shared beginning longer than what it stages in LDS (4,096 records); then results in two parts."""
+    torch = torch_cuda
+    T, C = 4500, 2
+    w = synth.scaled(synth.WORKLOADS["medium"], channels=C, frames=T, chunk=250, config_id=64)
+    g = synth.graph_for(synth.WORKLOADS["medium"])
+    og = OracleGraph.from_graph(g)
+    L = synth.make_loglikes(C, T, w.num_pdfs, w.sigma, seed_stream=(64,), device="cuda")
+    Lh = L.cpu().numpy()
+    ctxs, offs = synth.make_contexts(w, g)
+    dec = GH.GpuDecoder(g, C, w.beam, w.max_active, max_frames=T, records_per_frame=512,
+                        max_context_arcs=max(len(x) for x in ctxs))
+    try:
+        orcs = GH.oracle_channels(g, C, w.beam, w.max_active, og=og)
+        dec.set_contexts(ctxs, offs)
+        dec.reset()
+        for c in range(C):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset(); orcs[c].advance(Lh[c])
+        for t in range(0, T, w.chunk):
+            dec.advance(L, t, t + w.chunk)
+        for c in range(C):
+            before, after, fixed, _ = check_one_compaction(dec, c, f"ch {c}")
+            assert before > 524_288 + 1000 and fixed > 4096 and after < before // 50
+        st, wl, al, cost, na, nw, nfw, nfa = B.cbd_best_tails(dec.dh, dec.all, True, capacity=8 * T)
+        for c in range(C):
+            fw, fa = B.cbd_get_fixed(dec.dh, c)
+            assert fa.size == nfa[c] > 4096 and fw.size == nfw[c]
+            GH.assert_best_equal((int(st[c]), np.concatenate([fw, wl[c]]), np.concatenate([fa, al[c]]), float(cost[c])),
+                                 orcs[c].best_path(True), f"two parts ch {c}")
+            GH.assert_best_equal(dec.best(c, True), orcs[c].best_path(True), f"whole path ch {c}")
+    finally:
+        dec.close()
+
+
+def test_compaction_of_dense_records(torch_cuda):
+    """Flat log-likelihoods and a wide beam: thousands of tokens per frame, and after a dozen frames more records
+    of one stretch of the bitmap are still on some token's path than the kernel stages in LDS at a time (4,096)."""
+    torch = torch_cuda
+    T = 12
+    g = synth.make_graph(1_000_000, 500, 2000, 0.10, seed_stream=(41,))
+    L = synth.make_loglikes(1, T + 6, 500, 0.5, seed_stream=(41,), device="cuda")
+    Lh = L.cpu().numpy()
+    dec = GH.GpuDecoder(g, 1, 16.0, 5000, max_frames=T + 6, hash_log2=16, max_context_arcs=4)
+    try:
+        orc = GH.oracle_channels(g, 1, 16.0, 5000)[0]
+        dec.set_contexts([np.zeros(0, np.int32)], [0.0])
+        orc.set_context(np.zeros(0, np.int32), 0.0)
+        dec.reset(); orc.reset()
+        dec.advance(L, 0, T); orc.advance(Lh[0, :T])
+        before, after, _, densest = check_one_compaction(dec, 0, "first")
+        assert densest > 4096 and before > 2 * 32768
+        GH.assert_best_equal(dec.best(0), orc.best_path(False), "after the first compaction")
+        dec.advance(L, T, T + 6); orc.advance(Lh[0, T:])
+        check_one_compaction(dec, 0, "second")
+        GH.assert_best_equal(dec.best(0), orc.best_path(False), "after the second compaction")
+        GH.assert_tables_equal(dec.tokens(0), orc.tokens(), "final table")
     finally:
         dec.close()
