@@ -630,7 +630,8 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     // half the table capacity each (the log-likelihood row then stays in device memory / L2).
     int wgs = cfg->workgroups_per_cu;
     if (wgs == 0) wgs = d->C > n_cu ? 2 : 1;
-    const int budget = lds_limit / wgs;
+    // (a little LDS per compute unit is left for the partial-result walks, which run beside the decoding)
+    const int budget = (lds_limit - 1024) / wgs;
     auto best_cap = [&](int pdfs_staged) {
       if (cfg->table_location == 2) return 0;
       int want = cfg->lds_token_cap > 0 ? cfg->lds_token_cap : cbd::kLdsTokLimit;
