@@ -392,3 +392,72 @@ def test_compaction_of_dense_records(torch_cuda):
         GH.assert_tables_equal(dec.tokens(0), orc.tokens(), "final table")
     finally:
         dec.close()
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_schedules(torch_cuda, seed):
+    """Seeded random interleaving of everything that touches the records: chunks of 1-17 frames on changing channel
+    subsets, compactions of random subsets with random thresholds, new utterances and context changes on single
+    channels in between, results asked for whole, in two parts, synchronously and asynchronously.  Every result
+    must be the checker's."""
+    torch = torch_cuda
+    rng = np.random.default_rng(1000 + seed)
+    C, T = 6, 260
+    g, L, ctxs, offs = inputs(C, T, seed=40 + seed, finals=True)
+    Lh = L.cpu().numpy()
+    spare, spare_offs = inputs(C, 1, seed=50 + seed)[2:]
+    dec = GH.GpuDecoder(g, C, 12.0, 250, max_frames=T)
+    try:
+        og = OracleGraph.from_graph(g)
+        orcs = GH.oracle_channels(g, C, 12.0, 250, og=og)
+        dec.set_contexts(ctxs, offs)
+        dec.reset()
+        for c in range(C):
+            orcs[c].set_context(ctxs[c], offs[c]); orcs[c].reset()
+        pos = [0] * C        # frames of L each channel has consumed (its utterance may have restarted since)
+
+        def check(c, res, i, where):
+            st, wl, al, cost, na, nw, nfw, nfa = res
+            fw, fa = B.cbd_get_fixed(dec.dh, c)
+            got = (int(st[i]), np.concatenate([fw[:nfw[i]], wl[i]]), np.concatenate([fa[:nfa[i]], al[i]]), float(cost[i]))
+            GH.assert_best_equal(got, orcs[c].best_path(False), where)
+
+        for step in range(60):
+            subset = np.sort(rng.choice(C, size=rng.integers(1, C + 1), replace=False)).astype(np.int32)
+            n = int(rng.integers(1, 18))
+            subset = np.array([c for c in subset if pos[c] + n <= T], np.int32)
+            if subset.size == 0:
+                break
+            # the rows of a call are consecutive in memory: gather this call's frames of the chosen channels
+            rows = torch.stack([L[c, pos[c]:pos[c] + n] for c in subset]).contiguous()
+            B.cbd_advance(dec.dh, subset, rows.data_ptr(), n * rows.shape[2], n)
+            for c in subset:
+                orcs[c].advance(Lh[c, pos[c]:pos[c] + n]); pos[c] += n
+            ticket = None
+            if rng.random() < 0.5:
+                ticket = (B.cbd_best_tails_begin(dec.dh, subset, False, capacity=4 * T), subset.copy())
+            if rng.random() < 0.6:
+                who = np.sort(rng.choice(C, size=rng.integers(1, C + 1), replace=False)).astype(np.int32)
+                dec.compact(who, int(rng.choice([0, 0, 300, 3000])))
+            if ticket is not None:
+                res = B.cbd_best_tails_finish(dec.dh, ticket[0])
+                for i, c in enumerate(ticket[1]):
+                    check(int(c), res, i, f"seed {seed} step {step} ch {c} (begun before)")
+            res = B.cbd_best_tails(dec.dh, dec.all, False, capacity=4 * T)
+            for c in range(C):
+                check(c, res, c, f"seed {seed} step {step} ch {c}")
+            if rng.random() < 0.3:
+                c = int(rng.integers(C))
+                GH.assert_best_equal(dec.best(c, True), orcs[c].best_path(True), f"seed {seed} step {step} ch {c} whole, final")
+            if rng.random() < 0.15:      # a new utterance on one channel, with another context
+                c = int(rng.integers(C))
+                dec.set_contexts([spare[c]], [spare_offs[c]], np.array([c], np.int32))
+                orcs[c].set_context(spare[c], spare_offs[c])
+                dec.reset(np.array([c], np.int32)); orcs[c].reset()
+            elif rng.random() < 0.15:    # a context change in mid-utterance
+                c = int(rng.integers(C))
+                dec.set_contexts([ctxs[(c + 1) % C]], [offs[(c + 1) % C]], np.array([c], np.int32))
+                orcs[c].set_context(ctxs[(c + 1) % C], offs[(c + 1) % C])
+        assert dec.stats(-1)["status"] == 0 and dec.stats(-1)["compactions"] > 10
+    finally:
+        dec.close()
