@@ -405,7 +405,8 @@ def test_random_schedules(torch_cuda, seed):
     C, T = 6, 260
     g, L, ctxs, offs = inputs(C, T, seed=40 + seed, finals=True)
     Lh = L.cpu().numpy()
-    spare, spare_offs = inputs(C, 1, seed=50 + seed)[2:]
+    spare, spare_offs = synth.make_contexts(
+        synth.scaled(synth.WORKLOADS["large"], channels=C, ctx_min=30, ctx_max=60, config_id=90 + seed), g)
     dec = GH.GpuDecoder(g, C, 12.0, 250, max_frames=T)
     try:
         og = OracleGraph.from_graph(g)
