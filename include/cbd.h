@@ -256,6 +256,9 @@ int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, in
  * or NULL; *n_words, *n_arcs receive the counts beyond from_word / from_arc; CBD_E_BUFFER if a wanted array is
  * too small.  Synchronises.  The fixed part is cleared by cbd_reset_channels; its room is that of the
  * back-pointer buffer (when it is full, nothing more is declared fixed).
+ *
+ * (cbd_best_path* use the fixed part too: they walk down to it and copy it in front of the rest, so whole-path
+ * results stay cheap on long utterances once compactions run; what they return is the same either way.)
  */
 int32_t cbd_best_tails(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
                        int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,

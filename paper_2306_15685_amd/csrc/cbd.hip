@@ -257,6 +257,7 @@ cbd::BestParams best_params(const cbd_decoder *d, const cbd_decoder::OutSlot &o,
   bp.tok_cap = d->g_tok_cap; bp.bp_cap = d->bp_cap; bp.use_final = use_final; bp.capacity = capacity;
   bp.row_pitch = o.capacity;
   bp.tail_only = tail_only ? 1 : 0;
+  bp.fixed_arcs = d->d_fixed_arcs; bp.fixed_words = d->d_fixed_words; bp.fixed_cap = d->bp_cap;
   bp.out_arcs = o.d_arcs; bp.out_words = o.dv_words; bp.out_meta = o.dv_meta; bp.snap = o.d_snap;
   return bp;
 }

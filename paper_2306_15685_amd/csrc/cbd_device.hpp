@@ -1459,6 +1459,10 @@ struct BestParams {
   int32_t *out_words;       // [n][row_pitch]
   int32_t *out_meta;        // [n][kMetaInts]: status, n_arcs, n_words, cost bits, fixed arcs, fixed words
   int32_t tail_only;        // 1: the path is followed down to the paths' shared beginning only (see the compaction)
+  // that shared beginning in time order, or null if no compaction has run ([C][fixed_cap] each): whole-path
+  // requests copy it instead of walking it
+  const int32_t *fixed_arcs, *fixed_words;
+  int32_t fixed_cap;
   int32_t *snap;            // [n][kSnapInts] snapshot taken on the decode stream (two-stage form only)
 };
 
@@ -1538,8 +1542,12 @@ __device__ __forceinline__ void walk_read_ahead(const BestParams &p, int c, int 
 // Back-pointer walk from record `rec` and labels in time order.  One wave.  Only records below
 // n_rec are touched (they never change once written), so this may run beside later decoding.
 __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int rec, int n_rec, uint32_t cost_ord,
-                                          int lane, int *walk_pos, int *walk_arcs, int stop_below) {
-  // stop_below: records below this one are not followed (0: the whole path)
+                                          int lane, int *walk_pos, int *walk_arcs, int stop_below, int front_arcs,
+                                          int front_words) {
+  // stop_below: records below this one are not followed (0: the whole path).  front_arcs / front_words: that many
+  // arcs / words of the channel's fixed part are put in front of what the walk finds (a plain copy: the fixed
+  // part is kept in time order and in the caller's numbering).
+  const int Fa = front_arcs, Fw = front_words;
   int32_t *meta = p.out_meta + (size_t)i * kMetaInts;
   int32_t *oarcs = p.out_arcs + (size_t)i * p.row_pitch;
   int32_t *owords = p.out_words + (size_t)i * p.row_pitch;
@@ -1571,7 +1579,7 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
       r = __shfl(r, 0, 64);
       __threadfence_block();
       for (int j = lane; j < n_chunk; j += 64)
-        if (na + j < p.capacity) oarcs[na + j] = walk_arcs[j];
+        if (Fa + na + j < p.capacity) oarcs[Fa + na + j] = walk_arcs[j];
       __threadfence_block();
       na += n_chunk;
     }
@@ -1582,7 +1590,7 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
     if (lane == 0) { meta[0] = kStatusEpsDiverged; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
-  if (na > p.capacity) {
+  if (Fa + na > p.capacity) {
     // count the words too so the caller learns both sizes
     int nw = 0;
     if (lane == 0) {
@@ -1593,32 +1601,38 @@ __device__ __forceinline__ void walk_path(const BestParams &p, int i, int c, int
         if (p.olabel[e.x] != 0) nw++;
         r = e.y;
       }
-      meta[0] = kStatusBuffer; meta[1] = na; meta[2] = nw; meta[3] = (int)__float_as_uint(ord2f(cost_ord));
+      meta[0] = kStatusBuffer; meta[1] = Fa + na; meta[2] = Fw + nw; meta[3] = (int)__float_as_uint(ord2f(cost_ord));
     }
     return;
   }
   // reverse into time order, pick up word labels, translate to the caller's numbering
   int nw_total = 0;
+  int32_t *tail = oarcs + Fa;
   for (int j0 = 0; j0 < (na + 1) / 2; j0 += 64) {
     int j = j0 + lane;
     if (j < (na + 1) / 2) {
       int k = na - 1 - j;
-      int a = oarcs[j], b = oarcs[k];
-      oarcs[j] = b; oarcs[k] = a;
+      int a = tail[j], b = tail[k];
+      tail[j] = b; tail[k] = a;
     }
   }
   __threadfence_block();
   for (int j0 = 0; j0 < na; j0 += 64) {
     int j = j0 + lane;
     int w = 0, a = 0;
-    if (j < na) { a = oarcs[j]; w = p.olabel[a]; }
+    if (j < na) { a = tail[j]; w = p.olabel[a]; }
     unsigned long long wm = __ballot(w != 0);
-    if (w != 0) owords[nw_total + __popcll(wm & ((1ull << lane) - 1ull))] = w;
+    if (w != 0) owords[Fw + nw_total + __popcll(wm & ((1ull << lane) - 1ull))] = w;
     nw_total += __popcll(wm);
-    if (j < na) oarcs[j] = p.int2pub[a];
+    if (j < na) tail[j] = p.int2pub[a];
+  }
+  if (Fa > 0) {
+    const int32_t *fa = p.fixed_arcs + (size_t)c * p.fixed_cap, *fw = p.fixed_words + (size_t)c * p.fixed_cap;
+    for (int j = lane; j < Fa; j += 64) oarcs[j] = fa[j];
+    for (int j = lane; j < Fw; j += 64) owords[j] = fw[j];
   }
   if (lane == 0) {
-    meta[0] = kStatusOk; meta[1] = na; meta[2] = nw_total;
+    meta[0] = kStatusOk; meta[1] = Fa + na; meta[2] = Fw + nw_total;
     meta[3] = (int)__float_as_uint(ord2f(cost_ord));
   }
 }
@@ -1657,8 +1671,11 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
     if (lane == 0) { meta[0] = kStatusNoTokens; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
+  // (whole paths: what lies below gc_base is not walked but copied from the fixed part, where there is one)
+  const bool have_fixed = p.fixed_arcs != nullptr;
   walk_path(p, i, c, rec, cs->n_rec, (uint32_t)(key >> 32), lane, &s_walk_pos, s_walk_arcs,
-            p.tail_only ? cs->gc_base : 0);
+            (p.tail_only || have_fixed) ? cs->gc_base : 0, (!p.tail_only && have_fixed) ? cs->n_fixed_arcs : 0,
+            (!p.tail_only && have_fixed) ? cs->n_fixed_words : 0);
 }
 
 // Two-stage form for results delivered beside later decoding.  Stage 1 (decode stream): pick the
@@ -1701,8 +1718,10 @@ __global__ __launch_bounds__(kWalkThreads) void best_walk_kernel(BestParams p) {
     walk_read_ahead(p, snap[4], lane, &s_walk_pos);
     return;
   }
+  const bool have_fixed = p.fixed_arcs != nullptr;
   walk_path(p, i, snap[4], snap[1], snap[3], (uint32_t)snap[2], lane, &s_walk_pos, s_walk_arcs,
-            p.tail_only ? snap[5] : 0);
+            (p.tail_only || have_fixed) ? snap[5] : 0, (!p.tail_only && have_fixed) ? snap[6] : 0,
+            (!p.tail_only && have_fixed) ? snap[7] : 0);
 }
 
 // ---- compaction of the back-pointer records ------------------------------------------
