@@ -124,6 +124,8 @@ typedef struct cbd_config {
                                  recent launches have reported show nothing due, the call does not even look (and
                                  asynchronous result walks keep running beside the decoding); N may therefore be
                                  overshot by the records of a few calls: size the buffer with that room */
+  int32_t block_threads;      /* threads per workgroup of the decoding kernel: 256, 512, 960 or 1024; 0 = chosen by
+                                 the library from workgroups_per_cu (1024 / 512 / 256 for 1 / 2 / 4) */
 } cbd_config;
 
 /*

@@ -13,7 +13,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cbd_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# CBD_ORACLE_SANITIZE=1: the checker built with AddressSanitizer and UndefinedBehaviorSanitizer (host code only);
+# the process must then have been started with the sanitizer's runtime preloaded (tests/test_oracle_sanitized.py).
+SANITIZE = os.environ.get("CBD_ORACLE_SANITIZE") == "1"
+_LIB = os.path.join(_HERE, "liboracle_san.so" if SANITIZE else "liboracle.so")
 
 ORC_OK, ORC_NO_TOKENS, ORC_EPS_DIVERGED, ORC_BUFFER, ORC_INVALID = 0, 1, 2, 3, 4
 
@@ -25,6 +28,9 @@ def build_oracle(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast-math",
                "-Wall", "-Wextra", "-o", _LIB + ".tmp", _SRC, "-lm"]
+        if SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                        "-fno-omit-frame-pointer"]
         subprocess.run(cmd, check=True)
         os.replace(_LIB + ".tmp", _LIB)
     return _LIB

@@ -40,7 +40,7 @@ class cbd_config(C.Structure):
                 ("hash_capacity_log2", C.c_int32), ("max_eps_iters", C.c_int32),
                 ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32),
                 ("max_pool_contexts", C.c_int32), ("workgroups_per_cu", C.c_int32),
-                ("compact_records_above", C.c_int32)]
+                ("compact_records_above", C.c_int32), ("block_threads", C.c_int32)]
 
 
 class cbd_stats(C.Structure):
@@ -186,11 +186,11 @@ def cbd_context_from_words(g, sequences) -> np.ndarray:
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,
                        hash_capacity_log2=14, max_eps_iters=0, records_per_frame=0, table_location=0,
                        lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, compact_records_above=0,
-                       hip_stream=0):
+                       block_threads=0, hip_stream=0):
     cfg = cbd_config(int(num_channels), float(beam), int(max_active), int(max_frames), int(max_context_arcs),
                      int(lookup_mode), int(hash_capacity_log2), int(max_eps_iters), int(records_per_frame),
                      int(table_location), int(lds_token_cap), int(max_pool_contexts), int(workgroups_per_cu),
-                     int(compact_records_above))
+                     int(compact_records_above), int(block_threads))
     h = C.c_void_p()
     _check(lib().cbd_decoder_create(g, C.byref(cfg), C.c_void_p(int(hip_stream)), C.byref(h)), "cbd_decoder_create")
     return h
@@ -290,6 +290,21 @@ class BestPathBuffers:
         self.n_fixed_arcs = np.zeros(n, np.int32)
 
 
+def _result(b: BestPathBuffers, n: int, want_arcs: bool, as_lists: bool, fixed: bool = False):
+    """What the cbd_best_paths* / cbd_best_tails* calls left in `b`, as their common return value:
+    (status[n], words, arcs or None, cost[n], n_arcs[n], n_words[n]) and, with `fixed`, n_fixed_words[n] and
+    n_fixed_arcs[n] behind them.  as_lists: one array per channel (copies); else the [n, capacity] matrices."""
+    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
+    extra = (b.n_fixed_words[:n], b.n_fixed_arcs[:n]) if fixed else ()
+    if not as_lists:
+        return (st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw) + extra
+    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    al = None
+    if want_arcs:
+        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
+    return (st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()) + tuple(x.copy() for x in extra)
+
+
 def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, buffers: Optional[BestPathBuffers] = None,
                    as_lists=True):
     """-> (status[n], words, arcs or None, cost[n], n_arcs[n], n_words[n]).
@@ -302,14 +317,7 @@ def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, 
     assert b.n >= n and b.capacity == capacity
     _check(lib().cbd_best_paths(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
                                 int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths")
-    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
-    if not as_lists:
-        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw
-    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    al = None
-    if want_arcs:
-        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    return st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()
+    return _result(b, n, want_arcs, as_lists)
 
 
 def cbd_best_paths_begin(d, channels, use_final=False, capacity=4096, want_arcs=True) -> int:
@@ -328,26 +336,7 @@ def cbd_best_paths_finish(d, ticket, buffers: Optional[BestPathBuffers] = None, 
     assert b.n >= n and b.capacity == capacity
     _check(lib().cbd_best_paths_finish(d, t, _p(b.words), _p(b.arcs) if want_arcs else None, int(capacity),
                                        _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths_finish")
-    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
-    if not as_lists:
-        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw
-    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    al = None
-    if want_arcs:
-        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    return st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy()
-
-
-def _tails_result(b, n, want_arcs, as_lists):
-    st, nw, na = b.status[:n], b.n_words[:n], b.n_arcs[:n]
-    if not as_lists:
-        return st, b.words, b.arcs if want_arcs else None, b.cost[:n], na, nw, b.n_fixed_words[:n], b.n_fixed_arcs[:n]
-    wl = [b.words[i, :nw[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    al = None
-    if want_arcs:
-        al = [b.arcs[i, :na[i]].copy() if st[i] == CBD_OK else np.zeros(0, np.int32) for i in range(n)]
-    return (st.copy(), wl, al, b.cost[:n].copy(), na.copy(), nw.copy(), b.n_fixed_words[:n].copy(),
-            b.n_fixed_arcs[:n].copy())
+    return _result(b, n, want_arcs, as_lists)
 
 
 def cbd_best_tails(d, channels, use_final=False, capacity=4096, want_arcs=True,
@@ -361,7 +350,7 @@ def cbd_best_tails(d, channels, use_final=False, capacity=4096, want_arcs=True,
     _check(lib().cbd_best_tails(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
                                 int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status),
                                 _p(b.n_fixed_words), _p(b.n_fixed_arcs)), "cbd_best_tails")
-    return _tails_result(b, n, want_arcs, as_lists)
+    return _result(b, n, want_arcs, as_lists, fixed=True)
 
 
 def cbd_best_tails_begin(d, channels, use_final=False, capacity=4096, want_arcs=True):
@@ -379,7 +368,7 @@ def cbd_best_tails_finish(d, ticket, buffers: Optional[BestPathBuffers] = None, 
     _check(lib().cbd_best_tails_finish(d, t, _p(b.words), _p(b.arcs) if want_arcs else None, int(capacity),
                                        _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status), _p(b.n_fixed_words),
                                        _p(b.n_fixed_arcs)), "cbd_best_tails_finish")
-    return _tails_result(b, n, want_arcs, as_lists)
+    return _result(b, n, want_arcs, as_lists, fixed=True)
 
 
 def cbd_get_fixed(d, channel, from_word=0, from_arc=0):

@@ -9,6 +9,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <new>
+#include <stdexcept>
 #include <string>
 #include <vector>
 
@@ -384,7 +386,7 @@ const char *cbd_strerror(int32_t status) {
 
 const char *cbd_last_error(void) { return g_last_error.c_str(); }
 
-int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
+int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) try {
   if (!desc || !out) return fail(CBD_E_INVALID, "graph: null argument");
   const int32_t S = desc->num_states, A = desc->num_arcs, P = desc->num_pdfs;
   if (S <= 0 || A < 0 || P <= 0 || desc->start_state < 0 || desc->start_state >= S)
@@ -402,13 +404,21 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
     if (desc->olabel[a] < 0) return fail(CBD_E_INVALID, "graph: negative olabel");
     if (!std::isfinite(desc->weight[a])) return fail(CBD_E_INVALID, "graph: non-finite weight");
   }
+  if (desc->final_cost)
+    for (int32_t s = 0; s < S; ++s)   // +inf marks a state that is not final
+      if (std::isnan(desc->final_cost[s]) || desc->final_cost[s] == -INFINITY)
+        return fail(CBD_E_INVALID, "graph: final_cost must be finite or +inf");
   cbd_graph *g = new (std::nothrow) cbd_graph();
   if (!g) return fail(CBD_E_NOMEM, "graph: host allocation");
+  struct Guard {   // frees the half-built graph if anything below throws
+    cbd_graph *g;
+    ~Guard() { if (g) cbd_graph_free(g); }
+  } guard{g};
   g->S = S; g->A = A; g->P = P; g->start = desc->start_state;
   g->h_row.assign(row, row + S + 1);
   g->h_dst.assign(desc->dst, desc->dst + A);
   g->h_olabel.assign(desc->olabel, desc->olabel + A);
-  if (hipGetDevice(&g->device) != hipSuccess) { delete g; return fail(CBD_E_HIP, "hipGetDevice failed"); }
+  if (hipGetDevice(&g->device) != hipSuccess) return fail(CBD_E_HIP, "hipGetDevice failed");
   // library order: per state, emitting arcs first, then epsilon-input arcs, each in the caller's order
   std::vector<int2> off2((size_t)S + 1);
   std::vector<cbd::ArcRec> arcs((size_t)std::max(A, 1));
@@ -442,7 +452,6 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
   do {                                                                                 \
     hipError_t e_ = (expr);                                                            \
     if (e_ != hipSuccess) {                                                            \
-      cbd_graph_free(g);                                                               \
       return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));       \
     }                                                                                  \
   } while (0)
@@ -463,8 +472,13 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) {
     GCHK(hipMemcpy(g->d_final, desc->final_cost, sizeof(float) * (size_t)S, hipMemcpyHostToDevice));
   }
 #undef GCHK
+  guard.g = nullptr;
   *out = g;
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "graph_load: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("graph_load: ") + e.what());
 }
 
 namespace {
@@ -549,7 +563,7 @@ void arcs_for_sequence(cbd_graph *g, const int32_t *words, int32_t k, std::vecto
 }  // namespace
 
 int32_t cbd_context_from_words(cbd_graph *g, const int32_t *words, const int32_t *seq_offsets, int32_t n_seq,
-                               int32_t *arcs, int32_t capacity, int32_t *n_arcs) {
+                               int32_t *arcs, int32_t capacity, int32_t *n_arcs) try {
   if (!g || !seq_offsets || !n_arcs) return fail(CBD_E_INVALID, "context_from_words: null argument");
   if (n_seq < 0 || seq_offsets[0] != 0) return fail(CBD_E_INVALID, "context_from_words: bad sequence offsets");
   for (int32_t i = 0; i < n_seq; ++i)
@@ -568,6 +582,10 @@ int32_t cbd_context_from_words(cbd_graph *g, const int32_t *words, const int32_t
     memcpy(arcs, out.data(), sizeof(int32_t) * out.size());
   }
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "context_from_words: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("context_from_words: ") + e.what());
 }
 
 int32_t cbd_graph_free(cbd_graph *g) {
@@ -582,7 +600,7 @@ int32_t cbd_graph_free(cbd_graph *g) {
   return CBD_OK;
 }
 
-int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_stream, cbd_decoder **out) {
+int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_stream, cbd_decoder **out) try {
   if (!g || !cfg || !out) return fail(CBD_E_INVALID, "decoder: null argument");
   if (cfg->num_channels < 1) return fail(CBD_E_INVALID, "decoder: num_channels < 1");
   if (!(cfg->beam >= 0.0f)) return fail(CBD_E_INVALID, "decoder: beam must be >= 0");
@@ -596,8 +614,15 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->max_pool_contexts < 0) return fail(CBD_E_INVALID, "decoder: max_pool_contexts");
   if (cfg->workgroups_per_cu < 0 || cfg->workgroups_per_cu > 4) return fail(CBD_E_INVALID, "decoder: workgroups_per_cu");
   if (cfg->compact_records_above < 0) return fail(CBD_E_INVALID, "decoder: compact_records_above");
+  if (cfg->block_threads != 0 && cfg->block_threads != 256 && cfg->block_threads != 512 && cfg->block_threads != 960 &&
+      cfg->block_threads != 1024)
+    return fail(CBD_E_INVALID, "decoder: block_threads must be 0, 256, 512, 960 or 1024");
   cbd_decoder *d = new (std::nothrow) cbd_decoder();
   if (!d) return fail(CBD_E_NOMEM, "decoder: host allocation");
+  struct Guard {   // frees the half-built decoder on every early return and if anything below throws
+    cbd_decoder *d;
+    ~Guard() { if (d) cbd_decoder_free(d); }
+  } guard{d};
   d->g = g; d->cfg = *cfg; d->stream = (hipStream_t)hip_stream;
   if (d->cfg.max_eps_iters <= 0) d->cfg.max_eps_iters = 64;
   d->C = cfg->num_channels;
@@ -606,7 +631,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   d->g_log_cap = d->g_slots;
   int64_t rpf = cfg->records_per_frame > 0 ? cfg->records_per_frame : d->g_tok_cap;
   int64_t bp = rpf * ((int64_t)cfg->max_frames + 1) + d->g_tok_cap;
-  if (bp > 0x7FFFFFF0) { delete d; return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel"); }
+  if (bp > 0x7FFFFFF0) return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel");
   d->bp_cap = (int32_t)bp;
   d->max_ctx = std::max(cfg->max_context_arcs, 1);
   d->ctx_lds_cap = std::min((d->max_ctx + 15) / 16 * 16, 2048);
@@ -615,7 +640,6 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   do {                                                                                 \
     hipError_t e_ = (expr);                                                            \
     if (e_ != hipSuccess) {                                                            \
-      cbd_decoder_free(d);                                                             \
       return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));       \
     }                                                                                  \
   } while (0)
@@ -637,6 +661,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
       if (cfg->table_location == 2) return 0;
       int want = cfg->lds_token_cap > 0 ? cfg->lds_token_cap : cbd::kLdsTokLimit;
       want = std::min(want, std::min<int>(d->g_tok_cap, cbd::kLdsTokLimit));
+      want = std::min(want, (int)(cbd::LogT<true>::kSrcMask * 2 / 3));   // the LDS change log keeps a table slot in 14 bits
       for (int t = want / 64 * 64; t >= 64; t -= 64) {
         cbd::LdsLayout l = cbd::make_layout(pdfs_staged, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t));
         if ((int64_t)l.total <= budget) return t;
@@ -651,11 +676,9 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
       cap = best_cap(0);
     }
     if ((int64_t)cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, 0, 0, 0).total > lds_limit) {
-      delete d;
       return fail(CBD_E_INVALID, "decoder: context list does not fit LDS");
     }
     if (cap == 0 && cfg->table_location == 1) {
-      delete d;
       return fail(CBD_E_INVALID, "decoder: no room for token tables in LDS");
     }
     d->lds_tok_cap = cap;
@@ -664,10 +687,10 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     d->lds_bytes = cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap).total;
     // workgroup size: the more channels share a compute unit, the smaller the groups
     d->block = wgs >= 4 ? 256 : (wgs >= 2 ? 512 : 1024);
-    const char *env = getenv("CBD_BLOCK");
-    if (env) {
-      int b = atoi(env);
-      if (b == 256 || b == 512 || b == 960 || b == 1024) d->block = b;
+    if (cfg->block_threads != 0) d->block = cfg->block_threads;
+    // (the LDS change log keeps a table slot in 14 bits)
+    if (d->lds_slots > (int32_t)cbd::LogT<true>::kSrcMask) {
+      return fail(CBD_E_INVALID, "decoder: LDS table too large for the change log's slot field");
     }
   }
   DCHK(set_attr(d->block, d->lds_bytes));
@@ -706,25 +729,31 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     DCHK(dmalloc(&d->d_due_max, 1, &d->bytes));
     DCHK(hipMemsetAsync(d->d_due_max, 0, sizeof(unsigned long long), d->stream));
   }
+  d->h_tmp.reserve(C); d->last_list.reserve(C); d->kept_ids.reserve(C); d->last_ids.reserve(C);
   DCHK(d->ids.init(sizeof(int32_t) * C));
   DCHK(dmalloc(&d->d_ids_kept, C, &d->bytes));
   // context staging: [channels n][list offsets n+1][offsets n][lists ...]
   DCHK(d->ctxs.init(sizeof(int32_t) * (C * 4 + 1 + C * (size_t)d->max_ctx)));
   DCHK(hipStreamSynchronize(d->stream));
 #undef DCHK
+  guard.d = nullptr;
   *out = d;
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "decoder_create: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("decoder_create: ") + e.what());
 }
 
 int32_t cbd_decoder_free(cbd_decoder *d) {
   if (!d) return CBD_OK;
   (void)hipStreamSynchronize(d->stream);
+  if (d->side) (void)hipStreamSynchronize(d->side);   // its walks read the records and snapshots freed below
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
                   d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words, d->d_due_max, d->d_ids_kept};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
-  if (d->side) (void)hipStreamSynchronize(d->side);
   if (d->h_new) (void)hipHostFree(d->h_new);
   for (auto &o : d->out) {
     free_out_slot(o);
@@ -748,7 +777,7 @@ int32_t cbd_decoder_info(const cbd_decoder *d, int64_t *device_bytes, int32_t *l
   return CBD_OK;
 }
 
-int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
+int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) try {
   if (!d) return fail(CBD_E_INVALID, "reset: null decoder");
   const int32_t *dev = nullptr;
   int slot = 0;
@@ -765,6 +794,10 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) {
   HIPCHK(launch_advance(d, p, n));
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "reset_channels: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("reset_channels: ") + e.what());
 }
 
 namespace {
@@ -927,7 +960,7 @@ int32_t check_channel_list(cbd_decoder *d, const int32_t *channels, int32_t n, c
 }  // namespace
 
 int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const int32_t *arc_idx,
-                         const int32_t *list_offsets, const float *offsets) {
+                         const int32_t *list_offsets, const float *offsets) try {
   if (!d || !channels || !list_offsets || !offsets) return fail(CBD_E_INVALID, "set_contexts: null argument");
   // validate everything before anything changes
   int32_t rc = check_channel_list(d, channels, n_channels, "set_contexts");
@@ -943,10 +976,14 @@ int32_t cbd_set_contexts(cbd_decoder *d, const int32_t *channels, int32_t n_chan
   rc = prepare_lists(d, n_channels, arc_idx, list_offsets, offsets, packed, off, "set_contexts");
   if (rc != CBD_OK) return rc;
   return upload_lists(d, n_channels, channels, channels, offsets, packed, off);
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "set_contexts: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("set_contexts: ") + e.what());
 }
 
 int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *arc_idx, const int32_t *list_offsets,
-                            const float *offsets, int32_t *context_ids) {
+                            const float *offsets, int32_t *context_ids) try {
   if (!d || !list_offsets || !offsets || !context_ids) return fail(CBD_E_INVALID, "contexts_create: null argument");
   if (n_contexts <= 0) return fail(CBD_E_INVALID, "contexts_create: bad count");
   int32_t free_ids = 0;
@@ -974,6 +1011,10 @@ int32_t cbd_contexts_create(cbd_decoder *d, int32_t n_contexts, const int32_t *a
   if (rc != CBD_OK)
     for (int32_t i = 0; i < n_contexts; ++i) d->pool_used[(size_t)context_ids[i]] = 0;
   return rc;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "contexts_create: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("contexts_create: ") + e.what());
 }
 
 int32_t cbd_context_destroy(cbd_decoder *d, int32_t context_id) {
@@ -984,7 +1025,7 @@ int32_t cbd_context_destroy(cbd_decoder *d, int32_t context_id) {
   return CBD_OK;
 }
 
-int32_t cbd_use_contexts(cbd_decoder *d, const int32_t *channels, const int32_t *context_ids, int32_t n) {
+int32_t cbd_use_contexts(cbd_decoder *d, const int32_t *channels, const int32_t *context_ids, int32_t n) try {
   if (!d || !context_ids) return fail(CBD_E_INVALID, "use_contexts: null argument");
   int32_t rc = check_channel_list(d, channels, n, "use_contexts");
   if (rc != CBD_OK) return rc;
@@ -1007,6 +1048,10 @@ int32_t cbd_use_contexts(cbd_decoder *d, const int32_t *channels, const int32_t 
   HIPCHK(hipGetLastError());
   HIPCHK(d->ctxs.release(slot, d->stream));
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "use_contexts: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("use_contexts: ") + e.what());
 }
 
 int32_t cbd_set_context(cbd_decoder *d, int32_t channel, const int32_t *arc_idx, int32_t n, float offset) {
@@ -1016,7 +1061,7 @@ int32_t cbd_set_context(cbd_decoder *d, int32_t channel, const int32_t *arc_idx,
 }
 
 int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels, const float *loglikes,
-                    int64_t channel_stride, int32_t n_frames) {
+                    int64_t channel_stride, int32_t n_frames) try {
   if (!d) return fail(CBD_E_INVALID, "advance: null decoder");
   if (n_frames < 0) return fail(CBD_E_INVALID, "advance: negative frame count");
   if (n_frames == 0) return CBD_OK;
@@ -1038,8 +1083,10 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
     // (right after the kernel was enqueued the counts in host memory are still the old ones: nothing can be due)
     bool skip = d->last_compact_call >= 0 && d->adv_calls - d->last_compact_call <= 2;
     for (int32_t i = 0; i < n_channels && !skip; ++i) {
-      const volatile int2 *e = d->h_new + channels[i];
-      const int32_t count = e->x, call = e->y;
+      // (count, call number) as the kernel stored the pair: one 64-bit load, so that a running launch cannot
+      // leave an old count beside a new call number
+      const uint64_t pair = __atomic_load_n((const uint64_t *)(d->h_new + channels[i]), __ATOMIC_RELAXED);
+      const int32_t count = (int32_t)(uint32_t)pair, call = (int32_t)(uint32_t)(pair >> 32);
       const int32_t age = (int32_t)((uint32_t)d->adv_calls - (uint32_t)call);   // (call numbers wrap)
       const bool since_compaction = (int32_t)((uint32_t)call - (uint32_t)d->last_compact_call) >= 0;
       if (!(age >= 1 && age <= 2 && since_compaction && count <= mark)) break;
@@ -1059,9 +1106,13 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   HIPCHK(launch_advance(d, p, n_channels));
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "advance: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("advance: ") + e.what());
 }
 
-int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t min_new_records) {
+int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t min_new_records) try {
   if (!d) return fail(CBD_E_INVALID, "compact_records: null decoder");
   if (min_new_records < 0) return fail(CBD_E_INVALID, "compact_records: negative threshold");
   const int32_t *dev = nullptr;
@@ -1072,6 +1123,10 @@ int32_t cbd_compact_records(cbd_decoder *d, const int32_t *channels, int32_t n, 
   if (rc != CBD_OK) return rc;
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "compact_records: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("compact_records: ") + e.what());
 }
 
 }  // extern "C"
@@ -1173,43 +1228,67 @@ extern "C" {
 
 int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
                        int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
-                       int32_t *status) {
+                       int32_t *status) try {
   return best_paths_impl(d, channels, n, use_final, words, arcs, capacity, n_words, n_arcs, cost, status, false,
                          nullptr, nullptr, "best_paths");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_paths: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_paths: ") + e.what());
 }
 
 int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
-                             int32_t want_arcs, int32_t *ticket) {
+                             int32_t want_arcs, int32_t *ticket) try {
   return best_paths_begin_impl(d, channels, n, use_final, capacity, want_arcs, ticket, false, "best_paths_begin");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_paths_begin: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_paths_begin: ") + e.what());
 }
 
 int32_t cbd_best_paths_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
-                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status) {
+                              int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status) try {
   return best_paths_finish_impl(d, ticket, words, arcs, capacity, n_words, n_arcs, cost, status, false, nullptr,
                                 nullptr, "best_paths_finish");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_paths_finish: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_paths_finish: ") + e.what());
 }
 
 int32_t cbd_best_tails(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
                        int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
-                       int32_t *status, int32_t *n_fixed_words, int32_t *n_fixed_arcs) {
+                       int32_t *status, int32_t *n_fixed_words, int32_t *n_fixed_arcs) try {
   return best_paths_impl(d, channels, n, use_final, words, arcs, capacity, n_words, n_arcs, cost, status, true,
                          n_fixed_words, n_fixed_arcs, "best_tails");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_tails: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_tails: ") + e.what());
 }
 
 int32_t cbd_best_tails_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
-                             int32_t want_arcs, int32_t *ticket) {
+                             int32_t want_arcs, int32_t *ticket) try {
   return best_paths_begin_impl(d, channels, n, use_final, capacity, want_arcs, ticket, true, "best_tails_begin");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_tails_begin: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_tails_begin: ") + e.what());
 }
 
 int32_t cbd_best_tails_finish(cbd_decoder *d, int32_t ticket, int32_t *words, int32_t *arcs, int32_t capacity,
                               int32_t *n_words, int32_t *n_arcs, float *cost, int32_t *status,
-                              int32_t *n_fixed_words, int32_t *n_fixed_arcs) {
+                              int32_t *n_fixed_words, int32_t *n_fixed_arcs) try {
   return best_paths_finish_impl(d, ticket, words, arcs, capacity, n_words, n_arcs, cost, status, true, n_fixed_words,
                                 n_fixed_arcs, "best_tails_finish");
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_tails_finish: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_tails_finish: ") + e.what());
 }
 
 int32_t cbd_get_fixed(cbd_decoder *d, int32_t channel, int32_t from_word, int32_t from_arc, int32_t *words,
-                      int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs) {
+                      int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs) try {
   if (!d || !n_words || !n_arcs) return fail(CBD_E_INVALID, "get_fixed: null argument");
   if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_fixed: channel out of range");
   if (from_word < 0 || from_arc < 0 || capacity < 0) return fail(CBD_E_INVALID, "get_fixed: negative argument");
@@ -1226,6 +1305,10 @@ int32_t cbd_get_fixed(cbd_decoder *d, int32_t channel, int32_t from_word, int32_
     HIPCHK(hipMemcpy(arcs, d->d_fixed_arcs + (size_t)channel * d->bp_cap + from_arc, sizeof(int32_t) * (size_t)na,
                      hipMemcpyDeviceToHost));
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "get_fixed: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("get_fixed: ") + e.what());
 }
 
 int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_t *words, int32_t *arcs,
@@ -1240,7 +1323,7 @@ int32_t cbd_best_path(cbd_decoder *d, int32_t channel, int32_t use_final, int32_
 }
 
 int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *costs, int32_t *arcs,
-                       int32_t capacity, int32_t *n) {
+                       int32_t capacity, int32_t *n) try {
   if (!d || !n) return fail(CBD_E_INVALID, "get_tokens: null argument");
   if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_tokens: channel out of range");
   HIPCHK(hipStreamSynchronize(d->stream));
@@ -1271,10 +1354,14 @@ int32_t cbd_get_tokens(cbd_decoder *d, int32_t channel, int32_t *states, float *
   }
   *n = k;
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "get_tokens: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("get_tokens: ") + e.what());
 }
 
 int32_t cbd_get_records(cbd_decoder *d, int32_t channel, int32_t *arcs, int32_t *prev, int32_t capacity,
-                        int32_t *n_records, int32_t *frame_base, int32_t *kept_base) {
+                        int32_t *n_records, int32_t *frame_base, int32_t *kept_base) try {
   if (!d || !n_records) return fail(CBD_E_INVALID, "get_records: null argument");
   if (channel < 0 || channel >= d->C) return fail(CBD_E_INVALID, "get_records: channel out of range");
   HIPCHK(hipStreamSynchronize(d->stream));
@@ -1293,9 +1380,13 @@ int32_t cbd_get_records(cbd_decoder *d, int32_t channel, int32_t *arcs, int32_t 
     prev[i] = rec[i].y;
   }
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "get_records: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("get_records: ") + e.what());
 }
 
-int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
+int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) try {
   if (!d || !out) return fail(CBD_E_INVALID, "get_stats: null argument");
   if (channel < -1 || channel >= d->C) return fail(CBD_E_INVALID, "get_stats: channel out of range");
   HIPCHK(hipStreamSynchronize(d->stream));
@@ -1313,6 +1404,10 @@ int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) {
   }
   *out = s;
   return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "get_stats: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("get_stats: ") + e.what());
 }
 
 int32_t cbd_selftest(void) {

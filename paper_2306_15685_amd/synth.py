@@ -48,6 +48,7 @@ class Workload:
     mean_degree: float = 3.0
     word_frac: float = 0.25
     config_id: int = 0
+    graph_id: int = -1  # seed stream of the decoding graph (-1: config_id); workloads that share a graph share it
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -58,9 +59,9 @@ WORKLOADS: Dict[str, Workload] = {
     "large": Workload("large", 10_000_000, 6_000, 200_000, 0.10, 256, 500, 50, 15.0, 10_000, 4.0,
                       100, 500, -5.0, -5.0, partial_every_chunk=True, lookup_mode=1, config_id=2),
     "dynamic": Workload("dynamic", 10_000_000, 6_000, 200_000, 0.10, 512, 100, 100, 15.0, 10_000, 4.0,
-                        10, 1_000, -8.0, -2.0, segments=20, lookup_mode=1, config_id=3),
+                        10, 1_000, -8.0, -2.0, segments=20, lookup_mode=1, config_id=3, graph_id=2),
     "stress": Workload("stress", 10_000_000, 6_000, 200_000, 0.10, 2_048, 300, 50, 16.0, 20_000, 4.0,
-                       1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4),
+                       1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4, graph_id=2),
     # second workload: lexicon loop over end-to-end units (dense token activity, a 20,000-arc hub row,
     # max-active pruning engaged); contexts are word-end arcs (unigram boosting)
     "e2e": Workload("e2e", 0, 96, 20_000, 0.0, 64, 200, 50, 10.0, 2_500, 2.0,
@@ -195,10 +196,12 @@ def make_lexicon_graph(num_units: int, num_words: int, seed_stream: Tuple[int, .
 
 
 def graph_for(w: Workload, with_finals: bool = False) -> Graph:
+    """The workload's decoding graph.  Dynamic and Stress decode over Large's 10M-state graph (same seed stream)."""
+    gid = w.graph_id if w.graph_id >= 0 else w.config_id
     if w.name.startswith("e2e"):
-        return make_lexicon_graph(w.num_pdfs, w.num_words, seed_stream=(w.config_id,))
+        return make_lexicon_graph(w.num_pdfs, w.num_words, seed_stream=(gid,))
     return make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob,
-                      seed_stream=(w.config_id,), mean_degree=w.mean_degree,
+                      seed_stream=(gid,), mean_degree=w.mean_degree,
                       word_frac=w.word_frac, with_finals=with_finals)
 
 

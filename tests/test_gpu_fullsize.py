@@ -1,9 +1,13 @@
-"""Full-size parity: the five benchmark workloads in the launch configuration bench.py times
-(runner.Session.step), checked against the CPU checker on sampled channels (every partial and
-final result, counters) and, on many more channels, by properties that need no checker:
-the returned arc path is connected from the start state, consumes exactly the decoded frames,
-re-accumulating its cost in fp32 in path order gives the returned cost bit for bit, and the
-words are the path's output labels."""
+"""Full-size parity: the benchmark workloads in the launch configuration bench.py times
+(runner.Session.step), on the graphs bench.py builds, with EVERY channel of every segment checked
+against the CPU checker (each partial result, the final result, the counters).  On some channels the
+results are also checked by properties that need no checker: the returned arc path is connected from
+the start state, consumes exactly the decoded frames, re-accumulating its cost in fp32 in path order
+gives the returned cost bit for bit, and the words are the path's output labels."""
+import os
+import threading
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -27,45 +31,68 @@ def torch_cuda():
 
 @pytest.fixture(scope="module")
 def big_graph():
-    """The 10M-state graph shared by the large, dynamic and stress workloads (same seed stream)."""
+    """The 10M-state graph that the large, dynamic and stress workloads share (bench.py builds the same one)."""
     w = synth.WORKLOADS["large"]
-    g = synth.make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob, seed_stream=(w.config_id,),
-                         mean_degree=w.mean_degree, word_frac=w.word_frac)
+    g = synth.graph_for(w)
+    for other in ("dynamic", "stress"):
+        assert synth.WORKLOADS[other].graph_id == w.config_id
     return g, OracleGraph.from_graph(g)
 
 
-def check_workload(torch, w, g, og, sample, prop_channels, graph_handle=None):
+def oracle_workers():
+    return max(1, min(16, len(os.sched_getaffinity(0))))
+
+
+def check_workload(torch, w, g, og, prop_channels, graph_handle=None):
+    """Every channel of every segment against the checker: each chunk's partial result, the final result and (for
+    the last segment) the counters.  The checker's channels run on a pool of host threads, one checker object per
+    thread, reused from channel to channel (ctypes releases the interpreter lock during the calls)."""
     inp = runner.make_inputs(w, g)
     sess = runner.Session(inp, graph_handle=graph_handle)
     try:
         finals = sess.step(keep_results=True, collect_stats=False)
-        partials = sess.partials
+        partials = {(ss, tt): r for (ss, tt, r) in sess.partials}
         n_seg = w.segments
         assert len(finals) == n_seg
-        # --- sampled channels against the checker: every chunk's partial result, the final one, counters
-        for c in sample:
-            ch = OracleChannel(og, w.beam, w.max_active)
+        tls = threading.local()
+        last_counters = {}
+
+        def one_channel(s, c, Lh, lists, offs):
+            ch = getattr(tls, "ch", None)
+            if ch is None:
+                ch = tls.ch = OracleChannel(og, w.beam, w.max_active)
+            ch.set_context(lists[c], offs[c])
+            ch.reset()
+            t = 0
+            while t < w.frames:
+                n = min(w.chunk, w.frames - t)
+                ch.advance(Lh[c, t:t + n])
+                t += n
+                if w.partial_every_chunk and t < w.frames:
+                    st, wl, al, cost, na, nw = partials[(s, t)]
+                    GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(False),
+                                         f"{w.name} seg {s} ch {c} partial t={t}")
+            st, wl, al, cost, na, nw = finals[s]
+            GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(True),
+                                 f"{w.name} seg {s} ch {c} final")
+            if s == n_seg - 1:
+                last_counters[c] = (ch.emit_arcs, ch.stat(1), ch.stat(2), ch.stat(3))
+            return c
+
+        with ThreadPoolExecutor(max_workers=oracle_workers()) as ex:
             for s in range(n_seg):
                 lists, offs = inp.contexts[s]
-                ch.set_context(lists[c], offs[c])
-                ch.reset()
-                Lh = inp.loglikes[s][c].cpu().numpy()
-                t = 0
-                while t < w.frames:
-                    n = min(w.chunk, w.frames - t)
-                    ch.advance(Lh[t:t + n])
-                    t += n
-                    if w.partial_every_chunk and t < w.frames:
-                        st, wl, al, cost, na, nw = next(r for (ss, tt, r) in partials if ss == s and tt == t)
-                        GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(False),
-                                             f"{w.name} seg {s} ch {c} partial t={t}")
-                st, wl, al, cost, na, nw = finals[s]
-                GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), ch.best_path(True),
-                                     f"{w.name} seg {s} ch {c} final")
-            stc = sess.stats(c)   # counters of the last segment
-            assert stc["emit_arcs"] == ch.emit_arcs and stc["tokens"] == ch.stat(1), f"{w.name} ch {c} counters"
-            assert stc["active_tokens"] == ch.stat(2) and stc["max_tokens"] == ch.stat(3)
-        # --- properties on many channels
+                Lh = inp.loglikes[s].cpu().numpy()
+                done = list(ex.map(lambda c: one_channel(s, c, Lh, lists, offs), range(w.channels)))
+                assert len(done) == w.channels
+                del Lh
+                print(f"{w.name}: segment {s + 1}/{n_seg}: {w.channels} channels equal to the checker", flush=True)
+        for c in range(w.channels):   # counters of the last segment
+            stc = sess.stats(c)
+            emit, toks, act, mx = last_counters[c]
+            assert stc["emit_arcs"] == emit and stc["tokens"] == toks, f"{w.name} ch {c} counters"
+            assert stc["active_tokens"] == act and stc["max_tokens"] == mx, f"{w.name} ch {c} counters"
+        # --- extra, on some channels: properties that need no checker
         for s in range(n_seg if n_seg <= 2 else 2):
             lists, offs = inp.contexts[s]
             st, wl, al, cost, na, nw = finals[s]
@@ -87,7 +114,7 @@ def test_medium_all_channels(torch_cuda):
     w = synth.WORKLOADS["medium"]
     g = synth.graph_for(w)
     og = OracleGraph.from_graph(g)
-    check_workload(torch_cuda, w, g, og, sample=range(w.channels), prop_channels=range(w.channels))
+    check_workload(torch_cuda, w, g, og, prop_channels=range(w.channels))
 
 
 def test_e2e_units_lexicon_loop(torch_cuda):
@@ -95,7 +122,7 @@ def test_e2e_units_lexicon_loop(torch_cuda):
     w = synth.WORKLOADS["e2e"]
     g = synth.graph_for(w)
     og = OracleGraph.from_graph(g)
-    total = check_workload(torch_cuda, w, g, og, sample=[0, 31, 63], prop_channels=range(0, w.channels, 8))
+    total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 8))
     assert total["max_tokens"] > 2500   # far denser token activity than the HCLG-style workloads
 
 
@@ -103,28 +130,23 @@ def test_e2e_units_lexicon_loop(torch_cuda):
 def test_large_online(torch_cuda, big_graph):
     g, og = big_graph
     w = synth.WORKLOADS["large"]
-    rng = np.random.default_rng(1)
-    sample = [0, w.channels - 1] + rng.choice(w.channels, 6, replace=False).tolist()
-    total = check_workload(torch_cuda, w, g, og, sample=sample, prop_channels=range(0, w.channels, 4))
+    total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 16))
     assert total["slow_frames"] < total["frames"] // 100   # LDS tables carry the workload, the fallback is rare
 
 
 @pytest.mark.timeout(900)
 def test_dynamic_context_switching(torch_cuda, big_graph):
-    """512 channels, 20 utterances each with a fresh context per channel (fewer channels are
-    sampled for the checker because each costs 20 utterances)."""
+    """512 channels, 20 utterances each with a fresh context per channel."""
     g, og = big_graph
     w = synth.WORKLOADS["dynamic"]
-    check_workload(torch_cuda, w, g, og, sample=[0, 257, w.channels - 1], prop_channels=range(0, w.channels, 16))
+    check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 64))
 
 
 @pytest.mark.timeout(900)
 def test_throughput_stress(torch_cuda, big_graph):
     g, og = big_graph
     w = synth.WORKLOADS["stress"]
-    rng = np.random.default_rng(2)
-    sample = [0, w.channels - 1] + rng.choice(w.channels, 4, replace=False).tolist()
-    check_workload(torch_cuda, w, g, og, sample=sample, prop_channels=range(0, w.channels, 64))
+    check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 256))
 
 
 @pytest.mark.timeout(600)

@@ -38,20 +38,19 @@ def tiny_inputs(torch, T=100, seed=(0,)):
     return w, g, L, ctxs, offs
 
 
-@pytest.mark.parametrize("table_location,block,lds_cap", [(1, "1024", 0), (2, "1024", 0), (1, "256", 0), (2, "512", 0),
-                                                          (1, "1024", 192), (1, "512", 64)])
-def test_tiny_frame_by_frame(torch_cuda, monkeypatch, table_location, block, lds_cap):
+@pytest.mark.parametrize("table_location,block,lds_cap", [(1, 1024, 0), (2, 1024, 0), (1, 256, 0), (2, 512, 0),
+                                                          (1, 1024, 192), (1, 512, 64), (1, 960, 0)])
+def test_tiny_frame_by_frame(torch_cuda, table_location, block, lds_cap):
     """Config Tiny: every frame's token table, then words / path / cost / arc counter.  With a small
     LDS capacity most frames outgrow the LDS tables and are redone in device memory, and decoding
     moves back to LDS whenever the token list fits again."""
     torch = torch_cuda
-    monkeypatch.setenv("CBD_BLOCK", block)
     w, g, L, ctxs, offs = tiny_inputs(torch)
     Lh = L.cpu().numpy()
     dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location,
-                        lds_token_cap=lds_cap)
+                        lds_token_cap=lds_cap, block_threads=block)
     info = B.cbd_decoder_info(dec.dh)
-    assert info["tables_in_lds"] == (table_location == 1) and info["block_threads"] == int(block)
+    assert info["tables_in_lds"] == (table_location == 1) and info["block_threads"] == block
     if lds_cap:
         assert info["lds_token_cap"] == lds_cap
     try:
@@ -616,19 +615,19 @@ def test_error_states(torch_cuda):
         dec.close()
 
 
-@pytest.mark.parametrize("table_location,block", [(1, "1024"), (2, "1024"), (1, "256")])
-def test_repeated_decodes_match_checker(torch_cuda, monkeypatch, table_location, block):
+@pytest.mark.parametrize("table_location,block", [(1, 1024), (2, 1024), (1, 256)])
+def test_repeated_decodes_match_checker(torch_cuda, table_location, block):
     """The same utterance many times over, one frame per call: counters and the final table must
     match the checker every time (lanes of different waves race for the same states; a lane can
     create a state's entry and still lose the minimum to another wave)."""
     torch = torch_cuda
-    monkeypatch.setenv("CBD_BLOCK", block)
     w, g, L, ctxs, offs = tiny_inputs(torch)
     Lh = L.cpu().numpy()
     orc = GH.oracle_channels(g, 1, w.beam, w.max_active)[0]
     orc.set_context(ctxs[0], offs[0]); orc.reset(); orc.advance(Lh[0])
     want = orc.tokens()
-    dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location)
+    dec = GH.GpuDecoder(g, 1, w.beam, w.max_active, max_frames=w.frames, table_location=table_location,
+                        block_threads=block)
     try:
         dec.set_contexts(ctxs, offs)
         for rep in range(60):
