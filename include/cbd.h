@@ -225,6 +225,21 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
                        int32_t *status);
 
 /*
+ * cbd_best_paths for callers that cannot allocate device memory while they run (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments, same results in the
+ * caller's arrays (entries of a row beyond its count are unspecified), but the kernel's device-side result
+ * rows live in a fixed 8 MiB array that is part of the library's code object instead of buffers the library
+ * sizes on demand: the call allocates and frees nothing, on the device or in pinned memory.  The fixed
+ * array bounds the request: CBD_E_CAPACITY unless n * (2 * capacity + 8) <= 2,097,152.  Every GPU the
+ * library runs on holds one such array until the process ends, and every call on that GPU shares it:
+ * calls that overlap on one GPU (two decoders driven from two threads) race and must be serialised by
+ * the caller.  Synchronises the stream.
+ */
+int32_t cbd_best_paths_static(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                              int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                              int32_t *status);
+
+/*
  * The same in two steps, so that intermediate results leave the GPU without interrupting the
  * decoding (Sec. 2.2).  cbd_best_paths_begin notes the best tokens on the decoder's stream (for the
  * channel list of the latest cbd_advance / cbd_reset_channels call and use_final = 0 the decoding

@@ -21,7 +21,7 @@ CBD_E_NO_TOKENS, CBD_E_BUFFER, CBD_E_HIP, CBD_E_NOMEM = -4, -5, -6, -7
 
 EXPORTS = [
     "cbd_graph_load", "cbd_graph_free", "cbd_context_from_words", "cbd_decoder_create", "cbd_decoder_free", "cbd_reset_channels",
-    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_compact_records", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_best_tails", "cbd_best_tails_begin", "cbd_best_tails_finish",
+    "cbd_set_context", "cbd_set_contexts", "cbd_contexts_create", "cbd_context_destroy", "cbd_use_contexts", "cbd_advance", "cbd_compact_records", "cbd_best_path", "cbd_best_paths", "cbd_best_paths_static", "cbd_best_paths_begin", "cbd_best_paths_finish", "cbd_best_tails", "cbd_best_tails_begin", "cbd_best_tails_finish",
     "cbd_get_fixed", "cbd_get_tokens",
     "cbd_get_records", "cbd_get_stats", "cbd_decoder_info", "cbd_synchronize", "cbd_selftest", "cbd_strerror", "cbd_last_error",
 ]
@@ -97,6 +97,8 @@ def lib():
     L.cbd_best_path.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, vp]
     L.cbd_best_paths.restype = i32
     L.cbd_best_paths.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
+    L.cbd_best_paths_static.restype = i32
+    L.cbd_best_paths_static.argtypes = [vp, vp, i32, i32, vp, vp, i32, vp, vp, vp, vp]
     L.cbd_best_paths_begin.restype = i32
     L.cbd_best_paths_begin.argtypes = [vp, vp, i32, i32, i32, i32, vp]
     L.cbd_best_paths_finish.restype = i32
@@ -317,6 +319,19 @@ def cbd_best_paths(d, channels, use_final=False, capacity=4096, want_arcs=True, 
     assert b.n >= n and b.capacity == capacity
     _check(lib().cbd_best_paths(d, _p(ch), n, int(bool(use_final)), _p(b.words), _p(b.arcs) if want_arcs else None,
                                 int(capacity), _p(b.n_words), _p(b.n_arcs), _p(b.cost), _p(b.status)), "cbd_best_paths")
+    return _result(b, n, want_arcs, as_lists)
+
+
+def cbd_best_paths_static(d, channels, use_final=False, capacity=4096, want_arcs=True,
+                          buffers: Optional[BestPathBuffers] = None, as_lists=True):
+    """cbd_best_paths through the entry point that allocates nothing; same return value."""
+    ch = _i32(channels)
+    n = int(ch.size)
+    b = buffers if buffers is not None else BestPathBuffers(n, capacity, want_arcs)
+    assert b.n >= n and b.capacity == capacity
+    _check(lib().cbd_best_paths_static(d, _p(ch), n, int(bool(use_final)), _p(b.words),
+                                       _p(b.arcs) if want_arcs else None, int(capacity), _p(b.n_words), _p(b.n_arcs),
+                                       _p(b.cost), _p(b.status)), "cbd_best_paths_static")
     return _result(b, n, want_arcs, as_lists)
 
 

@@ -16,9 +16,32 @@
 
 #include "cbd_device.hpp"
 
+// Device-side result rows of cbd_best_paths_static (headers, words, arcs): a fixed array in the code object instead
+// of buffers from hipMalloc, for callers that must not allocate.  Every GPU the library runs on holds its own copy
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress: kernels and copies get
+// the device address it returns (static_scratch()).
+constexpr size_t kStaticScratchInts = (size_t)2 << 20;   // 8 MiB
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
 namespace {
 
 thread_local std::string g_last_error;
+
+constexpr int kMaxDevices = 64;
+int32_t *g_scratch_ptr[kMaxDevices] = {};   // per device: where `scratch` lives there
+
+// The address of `scratch` on `device` (made current by the caller), looked up once per device.
+hipError_t static_scratch(int device, int32_t **out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[device]) {
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = (int32_t *)p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 int32_t fail(int32_t code, const std::string &msg) {
   g_last_error = msg;
@@ -177,6 +200,7 @@ struct cbd_decoder {
   std::vector<int32_t> kept_ids, last_ids;
   StageRing ctxs;  // context uploads
   std::vector<int32_t> h_tmp;
+  std::vector<int32_t> h_static_meta;   // result headers of cbd_best_paths_static on their way to the caller
   size_t bytes = 0;
 };
 
@@ -644,6 +668,10 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     }                                                                                  \
   } while (0)
   DCHK(hipSetDevice(g->device));
+  {
+    int32_t *sp = nullptr;   // cbd_best_paths_static's array on this device: resolved here, once
+    DCHK(static_scratch(g->device, &sp));
+  }
   int lds_limit = 0, n_cu = 0;
   DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
   DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
@@ -730,6 +758,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     DCHK(hipMemsetAsync(d->d_due_max, 0, sizeof(unsigned long long), d->stream));
   }
   d->h_tmp.reserve(C); d->last_list.reserve(C); d->kept_ids.reserve(C); d->last_ids.reserve(C);
+  d->h_static_meta.assign(C * cbd::kMetaInts, 0);
   DCHK(d->ids.init(sizeof(int32_t) * C));
   DCHK(dmalloc(&d->d_ids_kept, C, &d->bytes));
   // context staging: [channels n][list offsets n+1][offsets n][lists ...]
@@ -1235,6 +1264,66 @@ int32_t cbd_best_paths(cbd_decoder *d, const int32_t *channels, int32_t n, int32
   return fail(CBD_E_NOMEM, "best_paths: host allocation failed");
 } catch (const std::exception &e) {
   return fail(CBD_E_HIP, std::string("best_paths: ") + e.what());
+}
+
+int32_t cbd_best_paths_static(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t *words,
+                              int32_t *arcs, int32_t capacity, int32_t *n_words, int32_t *n_arcs, float *cost,
+                              int32_t *status) try {
+  if (!d || !words || !n_words || !n_arcs || !cost || !status)
+    return fail(CBD_E_INVALID, "best_paths_static: null argument");
+  if (capacity < 1) return fail(CBD_E_INVALID, "best_paths_static: capacity < 1");
+  if (n < 1 || n > d->C) return fail(CBD_E_INVALID, "best_paths_static: bad channel count");
+  // rows in the fixed array: [n] headers, [n][capacity] words, [n][capacity] arcs
+  constexpr size_t M = cbd::kMetaInts;
+  const size_t need = (size_t)n * (M + 2 * (size_t)capacity);
+  if (need > kStaticScratchInts)
+    return fail(CBD_E_CAPACITY, "best_paths_static: n * (2 * capacity + 8) exceeds the fixed result area of " +
+                                    std::to_string(kStaticScratchInts) + " entries");
+  // (looked up when the decoder was created, with its device current; never the array's name itself)
+  int32_t *sp = d->g->device >= 0 && d->g->device < kMaxDevices ? g_scratch_ptr[d->g->device] : nullptr;
+  if (!sp) return fail(CBD_E_HIP, "best_paths_static: the fixed result area was not set up on this device");
+  const int32_t *dev = nullptr;
+  int slot = 0;
+  int32_t rc = stage_channels(d, channels, n, &dev, &slot);
+  if (rc != CBD_OK) return rc;
+  cbd_decoder::OutSlot rows;   // (describes the rows only; owns nothing)
+  rows.capacity = capacity;
+  cbd::BestParams bp = best_params(d, rows, dev, use_final, capacity, false);
+  bp.out_meta = sp;
+  bp.out_words = sp + (size_t)n * M;
+  bp.out_arcs = bp.out_words + (size_t)n * capacity;
+  bp.snap = nullptr;
+  hipLaunchKernelGGL(cbd::best_path_kernel, dim3((unsigned)n), dim3(cbd::kWalkThreads), 0, d->stream, bp);
+  HIPCHK(hipGetLastError());
+  HIPCHK(d->ids.release(slot, d->stream));
+  int32_t *meta = d->h_static_meta.data();
+  HIPCHK(hipMemcpyAsync(meta, bp.out_meta, sizeof(int32_t) * (size_t)n * M, hipMemcpyDeviceToHost, d->stream));
+  HIPCHK(hipStreamSynchronize(d->stream));
+  int32_t max_na = 0, max_nw = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    status[i] = meta[(size_t)i * M + 0];
+    n_arcs[i] = meta[(size_t)i * M + 1];
+    n_words[i] = meta[(size_t)i * M + 2];
+    const uint32_t bits = (uint32_t)meta[(size_t)i * M + 3];
+    memcpy(&cost[i], &bits, 4);
+    if (status[i] != CBD_OK) continue;
+    max_na = std::max(max_na, n_arcs[i]);
+    max_nw = std::max(max_nw, n_words[i]);
+  }
+  // as many columns of the rows as the longest result needs, straight into the caller's arrays
+  const size_t pitch = sizeof(int32_t) * (size_t)capacity;
+  if (max_nw > 0)
+    HIPCHK(hipMemcpy2DAsync(words, pitch, bp.out_words, pitch, sizeof(int32_t) * (size_t)max_nw, (size_t)n,
+                            hipMemcpyDeviceToHost, d->stream));
+  if (arcs && max_na > 0)
+    HIPCHK(hipMemcpy2DAsync(arcs, pitch, bp.out_arcs, pitch, sizeof(int32_t) * (size_t)max_na, (size_t)n,
+                            hipMemcpyDeviceToHost, d->stream));
+  HIPCHK(hipStreamSynchronize(d->stream));
+  return CBD_OK;
+} catch (const std::bad_alloc &) {
+  return fail(CBD_E_NOMEM, "best_paths_static: host allocation failed");
+} catch (const std::exception &e) {
+  return fail(CBD_E_HIP, std::string("best_paths_static: ") + e.what());
 }
 
 int32_t cbd_best_paths_begin(cbd_decoder *d, const int32_t *channels, int32_t n, int32_t use_final, int32_t capacity,
