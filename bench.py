@@ -99,6 +99,7 @@ def main():
     ap.add_argument("--lds-token-cap", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=0)
     ap.add_argument("--block-threads", type=int, default=0)
+    ap.add_argument("--frame-code", type=int, default=0, help="0: lean frame code where it applies; 1: general code only")
     ap.add_argument("--lookup-mode", type=int, default=-1, help="0 binary search, 1 Bloom filter + search; default: the workload's")
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
     ap.add_argument("--sync-partials", action="store_true",
@@ -147,7 +148,7 @@ def main():
                           biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
                           async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu,
                           compact_records_above=args.compact_records_above, record_frames=args.record_frames,
-                          tail_partials=args.tail_partials, block_threads=args.block_threads)
+                          tail_partials=args.tail_partials, block_threads=args.block_threads, frame_code=args.frame_code)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -188,7 +189,7 @@ def main():
     achieved = alg_bytes_step / launches_per_step / (avg_launch_ms * 1e-3) / 1e9
 
     default_cfg = (not args.unbiased and args.context_mode == "upload" and not args.channels and not args.hash_log2
-                   and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu and not args.block_threads
+                   and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu and not args.block_threads and not args.frame_code
                    and args.lookup_mode < 0 and not args.sync_partials and not args.frames and not args.chunk
                    and not args.compact_records_above and not args.record_frames and not args.tail_partials)
     traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(w.name) if default_cfg else None

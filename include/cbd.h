@@ -126,6 +126,9 @@ typedef struct cbd_config {
                                  overshot by the records of a few calls: size the buffer with that room */
   int32_t block_threads;      /* threads per workgroup of the decoding kernel: 256, 512, 960 or 1024; 0 = chosen by
                                  the library from workgroups_per_cu (1024 / 512 / 256 for 1 / 2 / 4) */
+  int32_t frame_code;         /* 0 = frames that qualify (tables in LDS, at most one token per thread, stored closure
+                                 lists) are decoded by the lean frame code, the rest by the general code; 1 = general
+                                 code only.  Results are the same either way. */
 } cbd_config;
 
 /*
@@ -308,6 +311,7 @@ typedef struct cbd_stats {
   int64_t records;        /* back-pointer records in use */
   int64_t slow_frames;    /* frames decoded with the device-memory tables */
   int64_t records_dropped; /* back-pointer records removed by compactions */
+  int64_t lean_frames;    /* frames decoded by the lean frame code */
   int32_t compactions;    /* compactions that ran */
   int32_t status;         /* sticky cbd_status of the channel */
   int32_t max_tokens;     /* largest table so far */

@@ -120,8 +120,10 @@ struct StageRing {
 struct cbd_graph {
   int device = 0;
   int32_t S = 0, A = 0, P = 0, start = 0;
-  int2 *d_off2 = nullptr;
+  int32_t A_lib = 0;              // records of the library's arc array (arcs + closure lists)
+  int4 *d_off2 = nullptr;
   cbd::ArcRec *d_arcs = nullptr;
+  int32_t *d_canon = nullptr;
   int32_t *d_int2pub = nullptr;
   int32_t *d_pub2int = nullptr;   // caller's arc numbering -> library numbering (context lists are translated on the device)
   int32_t *d_olabel = nullptr;
@@ -146,6 +148,7 @@ struct cbd_decoder {
   int32_t g_tok_cap = 0, g_slots = 0, g_log_cap = 0;        // device-memory tables
   int block = 1024;
   int stage_rows = 1;
+  int lean_log_per_wave = 0;
   uint32_t lds_bytes = 0;
   cbd::ChanState *d_chan = nullptr;
   int32_t *d_tok_state = nullptr;
@@ -234,13 +237,15 @@ hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid
 
 AdvanceParams base_params(const cbd_decoder *d) {
   AdvanceParams p{};
-  p.off2 = d->g->d_off2; p.arcs = d->g->d_arcs; p.start_state = d->g->start; p.num_pdfs = d->g->P;
+  p.off2 = d->g->d_off2; p.arcs = d->g->d_arcs; p.canon = d->g->d_canon; p.start_state = d->g->start; p.num_pdfs = d->g->P;
   p.chan = d->d_chan;
   p.beam = d->cfg.beam; p.max_active = d->cfg.max_active; p.max_eps_iters = d->cfg.max_eps_iters;
   p.lookup_mode = d->cfg.lookup_mode;
   p.lds_tok_cap = d->lds_tok_cap; p.lds_slots = d->lds_slots; p.lds_log_cap = d->lds_log_cap;
   p.g_tok_cap = d->g_tok_cap; p.g_slots = d->g_slots; p.g_log_cap = d->g_log_cap;
   p.bp_cap = d->bp_cap; p.max_ctx = d->max_ctx; p.ctx_lds_cap = d->ctx_lds_cap; p.stage_rows = d->stage_rows;
+  p.lean_frames = d->cfg.frame_code == 0 && d->lean_log_per_wave > 0 ? 1 : 0;
+  p.lean_log_per_wave = d->lean_log_per_wave;
   p.tok_state = d->d_tok_state; p.tok_cost = d->d_tok_cost;
   p.tok_row = d->d_tok_row;
   p.bp = d->d_bp; p.g_log = d->d_log; p.ctx = d->d_ctx; p.ctx_n = d->d_ctx_n; p.ctx_off = d->d_ctx_off;
@@ -443,34 +448,92 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) try {
   g->h_dst.assign(desc->dst, desc->dst + A);
   g->h_olabel.assign(desc->olabel, desc->olabel + A);
   if (hipGetDevice(&g->device) != hipSuccess) return fail(CBD_E_HIP, "hipGetDevice failed");
-  // library order: per state, emitting arcs first, then epsilon-input arcs, each in the caller's order
-  std::vector<int2> off2((size_t)S + 1);
-  std::vector<cbd::ArcRec> arcs((size_t)std::max(A, 1));
-  g->pub2int.resize((size_t)std::max(A, 1));
-  g->int2pub.resize((size_t)std::max(A, 1));
-  int32_t k = 0;
+  // Library order: per state, its emitting arcs, then its epsilon-input arcs (each in the caller's order), then
+  // its closure list: one record per path of epsilon-input arcs that starts at the state, depth-first, parents
+  // before children.  A state whose closure is deeper than kClosureMaxDepth or longer than the count field holds
+  // gets no list (the decoding kernel then takes the general closure code for it).
+  std::vector<int32_t> n_emit((size_t)S, 0), n_eps((size_t)S, 0), n_clo((size_t)S, 0);
+  for (int32_t s = 0; s < S; ++s)
+    for (int32_t a = row[s]; a < row[s + 1]; ++a) (desc->ilabel[a] != 0 ? n_emit : n_eps)[(size_t)s]++;
+  struct Frame { int32_t next, end, depth, parent1; };
+  std::vector<Frame> stack;
+  // walks the closure of s depth-first; visit(arc, depth, parent1) per record, parent1 = position of the record
+  // of the arc's source state in the list + 1 (0: s itself); false if the closure is too deep or too long
+  auto walk_closure = [&](int32_t s, auto &&visit) -> bool {
+    stack.clear();
+    stack.push_back({row[s], row[s + 1], 1, 0});
+    int32_t count = 0;
+    while (!stack.empty()) {
+      Frame &f = stack.back();
+      while (f.next < f.end && desc->ilabel[f.next] != 0) ++f.next;
+      if (f.next >= f.end) { stack.pop_back(); continue; }
+      const int32_t a = f.next++;
+      const int32_t depth = f.depth, parent1 = f.parent1;
+      if (depth > cbd::kClosureMaxDepth || ++count >= (int32_t)cbd::kClEscape) return false;
+      visit(a, depth, parent1);
+      const int32_t t = desc->dst[a];
+      if (n_eps[(size_t)t] > 0) stack.push_back({row[t], row[t + 1], depth + 1, count});   // (f is dead after this)
+    }
+    return true;
+  };
+  constexpr int32_t kNoList = -1;
   for (int32_t s = 0; s < S; ++s) {
-    off2[s].x = k;
-    for (int32_t a = row[s]; a < row[s + 1]; ++a)
-      if (desc->ilabel[a] != 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; }
-    off2[s].y = k;
-    for (int32_t a = row[s]; a < row[s + 1]; ++a)
-      if (desc->ilabel[a] == 0) { g->pub2int[a] = k; g->int2pub[k] = a; ++k; }
+    if (n_eps[(size_t)s] == 0) continue;
+    int32_t cnt = 0;
+    const bool ok = n_emit[(size_t)s] < (int32_t)cbd::kEdEscape && n_eps[(size_t)s] < (int32_t)cbd::kXdEscape &&
+                    walk_closure(s, [&](int32_t, int32_t, int32_t) { ++cnt; });
+    n_clo[(size_t)s] = ok ? cnt : kNoList;
   }
-  off2[S].x = k; off2[S].y = k;
-  std::vector<int32_t> olab((size_t)std::max(A, 1));
-  for (int32_t i = 0; i < A; ++i) {
-    int32_t a = g->int2pub[i];
-    int32_t dst = desc->dst[a];
-    int32_t ed = off2[dst].y - off2[dst].x, xd = off2[dst + 1].x - off2[dst].y;
+  std::vector<int4> off2((size_t)S);
+  int64_t total = 0;
+  for (int32_t s = 0; s < S; ++s) {
+    const int64_t first = total, eps = first + n_emit[(size_t)s], end_x = eps + n_eps[(size_t)s];
+    total = end_x + std::max(n_clo[(size_t)s], 0);
+    if (total > 0x7FFFFFF0) return fail(CBD_E_INVALID, "graph: too many arc records");
+    off2[(size_t)s] = make_int4((int)first, (int)eps, (int)end_x, (int)total);
+  }
+  const int32_t AL = (int32_t)total;   // records in the library's arc array
+  g->A_lib = AL;
+  std::vector<cbd::ArcRec> arcs((size_t)std::max(AL, 1));
+  std::vector<int32_t> canon((size_t)std::max(AL, 1)), olab((size_t)std::max(AL, 1));
+  g->pub2int.resize((size_t)std::max(A, 1));
+  g->int2pub.resize((size_t)std::max(AL, 1));
+  for (int32_t s = 0; s < S; ++s) {
+    int32_t ke = off2[(size_t)s].x, kx = off2[(size_t)s].y;
+    for (int32_t a = row[s]; a < row[s + 1]; ++a) {
+      int32_t &k = desc->ilabel[a] != 0 ? ke : kx;
+      g->pub2int[(size_t)a] = k;
+      ++k;
+    }
+  }
+  auto record_of = [&](int32_t a, uint32_t low16) {
+    const int32_t dst = desc->dst[a];
     cbd::ArcRec r;
     r.dst = dst;
     r.weight = desc->weight[a];
-    r.row = off2[dst].x;
-    r.meta = (uint32_t)desc->ilabel[a] | ((uint32_t)std::min<int32_t>(ed, (int32_t)cbd::kDegEscape) << 16) |
-             ((uint32_t)std::min<int32_t>(xd, (int32_t)cbd::kDegEscape) << 24);
-    arcs[i] = r;
-    olab[i] = desc->olabel[a];
+    r.row = off2[(size_t)dst].x;
+    const int32_t cl = n_clo[(size_t)dst];
+    r.meta = cbd::make_meta(low16, (uint32_t)n_emit[(size_t)dst], (uint32_t)n_eps[(size_t)dst],
+                            cl == kNoList ? cbd::kClEscape : (uint32_t)cl);
+    return r;
+  };
+  for (int32_t a = 0; a < A; ++a) {
+    const int32_t i = g->pub2int[(size_t)a];
+    arcs[(size_t)i] = record_of(a, (uint32_t)desc->ilabel[a]);
+    canon[(size_t)i] = i;
+    g->int2pub[(size_t)i] = a;
+    olab[(size_t)i] = desc->olabel[a];
+  }
+  for (int32_t s = 0; s < S; ++s) {
+    if (n_clo[(size_t)s] <= 0) continue;
+    int32_t k = off2[(size_t)s].z;
+    walk_closure(s, [&](int32_t a, int32_t depth, int32_t parent1) {
+      arcs[(size_t)k] = record_of(a, (uint32_t)depth | ((uint32_t)parent1 << 4));
+      canon[(size_t)k] = g->pub2int[(size_t)a];
+      g->int2pub[(size_t)k] = a;
+      olab[(size_t)k] = desc->olabel[a];
+      ++k;
+    });
   }
 #define GCHK(expr)                                                                     \
   do {                                                                                 \
@@ -479,17 +542,19 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) try {
       return fail(CBD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));       \
     }                                                                                  \
   } while (0)
-  GCHK(dmalloc(&g->d_off2, (size_t)S + 1, &g->bytes));
-  GCHK(dmalloc(&g->d_arcs, (size_t)A, &g->bytes));
-  GCHK(dmalloc(&g->d_int2pub, (size_t)A, &g->bytes));
+  GCHK(dmalloc(&g->d_off2, (size_t)S, &g->bytes));
+  GCHK(dmalloc(&g->d_arcs, (size_t)AL, &g->bytes));
+  GCHK(dmalloc(&g->d_canon, (size_t)AL, &g->bytes));
+  GCHK(dmalloc(&g->d_int2pub, (size_t)AL, &g->bytes));
   GCHK(dmalloc(&g->d_pub2int, (size_t)A, &g->bytes));
-  GCHK(dmalloc(&g->d_olabel, (size_t)A, &g->bytes));
-  GCHK(hipMemcpy(g->d_off2, off2.data(), sizeof(int2) * ((size_t)S + 1), hipMemcpyHostToDevice));
+  GCHK(dmalloc(&g->d_olabel, (size_t)AL, &g->bytes));
+  GCHK(hipMemcpy(g->d_off2, off2.data(), sizeof(int4) * (size_t)S, hipMemcpyHostToDevice));
   if (A > 0) {
-    GCHK(hipMemcpy(g->d_arcs, arcs.data(), sizeof(cbd::ArcRec) * (size_t)A, hipMemcpyHostToDevice));
-    GCHK(hipMemcpy(g->d_int2pub, g->int2pub.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_arcs, arcs.data(), sizeof(cbd::ArcRec) * (size_t)AL, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_canon, canon.data(), sizeof(int32_t) * (size_t)AL, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_int2pub, g->int2pub.data(), sizeof(int32_t) * (size_t)AL, hipMemcpyHostToDevice));
     GCHK(hipMemcpy(g->d_pub2int, g->pub2int.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
-    GCHK(hipMemcpy(g->d_olabel, olab.data(), sizeof(int32_t) * (size_t)A, hipMemcpyHostToDevice));
+    GCHK(hipMemcpy(g->d_olabel, olab.data(), sizeof(int32_t) * (size_t)AL, hipMemcpyHostToDevice));
   }
   if (desc->final_cost) {
     GCHK(dmalloc(&g->d_final, (size_t)S, &g->bytes));
@@ -616,6 +681,7 @@ int32_t cbd_graph_free(cbd_graph *g) {
   if (!g) return CBD_OK;
   if (g->d_off2) (void)hipFree(g->d_off2);
   if (g->d_arcs) (void)hipFree(g->d_arcs);
+  if (g->d_canon) (void)hipFree(g->d_canon);
   if (g->d_int2pub) (void)hipFree(g->d_int2pub);
   if (g->d_pub2int) (void)hipFree(g->d_pub2int);
   if (g->d_olabel) (void)hipFree(g->d_olabel);
@@ -638,6 +704,7 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->max_pool_contexts < 0) return fail(CBD_E_INVALID, "decoder: max_pool_contexts");
   if (cfg->workgroups_per_cu < 0 || cfg->workgroups_per_cu > 4) return fail(CBD_E_INVALID, "decoder: workgroups_per_cu");
   if (cfg->compact_records_above < 0) return fail(CBD_E_INVALID, "decoder: compact_records_above");
+  if (cfg->frame_code < 0 || cfg->frame_code > 1) return fail(CBD_E_INVALID, "decoder: frame_code");
   if (cfg->block_threads != 0 && cfg->block_threads != 256 && cfg->block_threads != 512 && cfg->block_threads != 960 &&
       cfg->block_threads != 1024)
     return fail(CBD_E_INVALID, "decoder: block_threads must be 0, 256, 512, 960 or 1024");
@@ -685,13 +752,17 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     if (wgs == 0) wgs = d->C > n_cu ? 2 : 1;
     // (a little LDS per compute unit is left for the partial-result walks, which run beside the decoding)
     const int budget = (lds_limit - 1024) / wgs;
+    // the lean frame code keeps a commit log per wave next to the tokens' rows (decided with the block size below)
+    const int block_guess = cfg->block_threads != 0 ? cfg->block_threads : (wgs >= 4 ? 256 : (wgs >= 2 ? 512 : 1024));
+    const int lean_entries = cfg->frame_code == 0 && cfg->table_location != 2 ? cbd::kLeanLogPerWave * (block_guess / 64) : 0;
     auto best_cap = [&](int pdfs_staged) {
       if (cfg->table_location == 2) return 0;
       int want = cfg->lds_token_cap > 0 ? cfg->lds_token_cap : cbd::kLdsTokLimit;
       want = std::min(want, std::min<int>(d->g_tok_cap, cbd::kLdsTokLimit));
       want = std::min(want, (int)(cbd::LogT<true>::kSrcMask * 2 / 3));   // the LDS change log keeps a table slot in 14 bits
       for (int t = want / 64 * 64; t >= 64; t -= 64) {
-        cbd::LdsLayout l = cbd::make_layout(pdfs_staged, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t));
+        cbd::LdsLayout l = cbd::make_layout(pdfs_staged, d->ctx_lds_cap, t, cbd::lds_slots_for(t), cbd::lds_log_for(t),
+                                            lean_entries);
         if ((int64_t)l.total <= budget) return t;
       }
       return 0;
@@ -712,7 +783,9 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     d->lds_tok_cap = cap;
     d->lds_slots = cap ? cbd::lds_slots_for(cap) : 0;
     d->lds_log_cap = cap ? cbd::lds_log_for(cap) : 0;
-    d->lds_bytes = cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap).total;
+    d->lean_log_per_wave = cap ? lean_entries / (block_guess / 64) : 0;
+    d->lds_bytes = cbd::make_layout(d->stage_rows ? g->P : 0, d->ctx_lds_cap, cap, d->lds_slots, d->lds_log_cap,
+                                    cap ? lean_entries : 0).total;
     // workgroup size: the more channels share a compute unit, the smaller the groups
     d->block = wgs >= 4 ? 256 : (wgs >= 2 ? 512 : 1024);
     if (cfg->block_threads != 0) d->block = cfg->block_threads;
@@ -1487,7 +1560,7 @@ int32_t cbd_get_stats(cbd_decoder *d, int32_t channel, cbd_stats *out) try {
     s.frames += c.frames; s.active_tokens += c.active_tokens; s.emit_arcs += c.emit_arcs; s.eps_arcs += c.eps_arcs;
     s.candidates += c.candidates; s.improvements += c.improvements; s.tokens += c.tokens;
     s.eps_rounds += c.eps_rounds; s.records += c.n_rec; s.slow_frames += c.slow_frames;
-    s.records_dropped += c.gc_dropped; s.compactions += c.gc_runs;
+    s.records_dropped += c.gc_dropped; s.compactions += c.gc_runs; s.lean_frames += c.lean_frames;
     if (s.status == CBD_OK && c.status != CBD_OK) s.status = c.status;
     s.max_tokens = std::max(s.max_tokens, c.max_tokens);
   }
@@ -1537,6 +1610,18 @@ int32_t cbd_selftest(void) {
   (void)hipFree(d_in); (void)hipFree(d_scan); (void)hipFree(d_min);
   return rc;
 }
+
+#ifdef CBD_PROFILE
+// Diagnostic build only: the phase sums a channel's lean frames left (see CBD_STAMP), 15 values.
+int32_t cbd_debug_profile(cbd_decoder *d, int32_t channel, int64_t *out) {
+  if (!d || !out || channel < 0 || channel >= d->C) return CBD_E_INVALID;
+  HIPCHK(hipStreamSynchronize(d->stream));
+  cbd::ChanState cs;
+  HIPCHK(hipMemcpy(&cs, d->d_chan + channel, sizeof(cs), hipMemcpyDeviceToHost));
+  for (int k = 0; k < 15; ++k) out[k] = cs.spare[k];
+  return CBD_OK;
+}
+#endif
 
 int32_t cbd_synchronize(cbd_decoder *d) {
   if (!d) return fail(CBD_E_INVALID, "synchronize: null decoder");

@@ -40,18 +40,33 @@ constexpr int kStatusNoTokens = -4;
 constexpr int kStatusBuffer = -5;
 
 // frame outcomes inside the kernel
-constexpr int kFrameOk = 0, kFrameOverflow = 1, kFrameNoTokens = 2, kFrameDiverged = 3, kFrameRecordsFull = 4;
+constexpr int kFrameOk = 0, kFrameOverflow = 1, kFrameNoTokens = 2, kFrameDiverged = 3, kFrameRecordsFull = 4,
+              kFrameRedo = 5;   // (lean frames only) nothing lasting was written: decode the frame with the general code
 
-// One arc in the library's own order (per state: emitting arcs, then epsilon-input arcs).
+// One record of the arc array.  Per state the array holds: its emitting arcs, its epsilon-input arcs, and then
+// its closure list: every state reachable from it through epsilon-input arcs alone, one record per path, in
+// depth-first preorder (a copy of the arc that ends the path, with the path's depth).  With the closure list a
+// whole epsilon closure is one contiguous read.  Arcs keep their identity: a record of a closure list names the
+// arc it copies (its position among the state rows) in the parallel array `canon`.
 struct __attribute__((aligned(16))) ArcRec {
   int32_t dst;
   float weight;
   int32_t row;     // first arc of dst
-  uint32_t meta;   // bits 0..15 ilabel (0 = epsilon input, else pdf + 1)
-                   // bits 16..23 number of emitting arcs of dst, 24..31 number of epsilon-input arcs of dst;
-                   // 255 in either field: look the row up in the offsets array
+  uint32_t meta;   // bits 0..15: ilabel (0 = epsilon input, else pdf + 1); in a closure list: bits 0..3 the path's
+                   //   depth (1..), bits 4..9 the position in the list of the record one arc shorter, plus 1 (0: none)
+                   // bits 16..21 number of emitting arcs of dst, 22..25 number of epsilon-input arcs of dst
+                   //   (all ones in either field: look the row up in the offsets array)
+                   // bits 26..31 records in dst's closure list (all ones: the list is not stored, too deep or long)
 };
-constexpr uint32_t kDegEscape = 255;
+constexpr uint32_t kEdEscape = 63, kXdEscape = 15, kClEscape = 63;
+constexpr int kClosureMaxDepth = 8;    // deeper closures are not flattened (the general closure code takes them)
+__host__ __device__ inline uint32_t meta_ed(uint32_t m) { return (m >> 16) & 63u; }
+__host__ __device__ inline uint32_t meta_xd(uint32_t m) { return (m >> 22) & 15u; }
+__host__ __device__ inline uint32_t meta_cl(uint32_t m) { return m >> 26; }
+__host__ __device__ inline uint32_t make_meta(uint32_t low16, uint32_t ed, uint32_t xd, uint32_t cl) {
+  return (low16 & 0xFFFFu) | ((ed < kEdEscape ? ed : kEdEscape) << 16) | ((xd < kXdEscape ? xd : kXdEscape) << 22) |
+         ((cl < kClEscape ? cl : kClEscape) << 26);
+}
 
 // Change-log entry: slot h took a value through arc `arc`.  `src` names where the arc
 // started: a token index of the previous frame (emitting arc), or, with kSrcEps, the
@@ -91,12 +106,16 @@ struct __attribute__((aligned(128))) ChanState {
   long long gc_dropped; // records they removed
   int32_t n_fixed_arcs;  // arcs / words of the paths' shared beginning written out so far (in time order, to the
   int32_t n_fixed_words; // channel's fixed_arcs / fixed_words rows)
+  long long lean_frames; // frames decoded by the lean code
+  long long spare[15];
 };
-static_assert(sizeof(ChanState) == 128, "one channel's state fills one 128-byte line");
+static_assert(sizeof(ChanState) == 256, "one channel's state fills two 128-byte lines");
 
 struct AdvanceParams {
-  const int2 *off2;        // [S+1]: x = first arc of the state, y = first epsilon-input arc of the state
+  const int4 *off2;        // [S]: x = first arc of the state, y = its first epsilon-input arc, z = end of those
+                           //      (start of its closure list), w = end of the closure list
   const ArcRec *arcs;      // [A]
+  const int32_t *canon;    // [A] the arc a record stands for (itself, except in closure lists)
   int32_t start_state;
   int32_t num_pdfs;
   ChanState *chan;         // [C]
@@ -119,6 +138,8 @@ struct AdvanceParams {
   int32_t max_ctx;         // row length of ctx
   int32_t ctx_lds_cap;     // context entries that fit the LDS copy
   int32_t stage_rows;      // 1: the frame's log-likelihood row is copied to LDS; 0: read from device memory
+  int32_t lean_frames;     // 1: frames that qualify are decoded by the lean code (run_frame_lean)
+  int32_t lean_log_per_wave;  // entries of a wave's commit log in lean frames
   // per channel, device memory
   int32_t *tok_state;      // [C][g_tok_cap] states of the current tokens (written on the last frame of a call)
   float *tok_cost;         // [C][g_tok_cap]
@@ -161,7 +182,18 @@ struct Shared {
   int32_t big_first[kBigRows], big_deg[kBigRows];
   float big_cost[kBigRows];
   uint32_t big_src[kBigRows];
+  int32_t n_done;             // lean frame: waves through with the look-up phase
+  int32_t redo, redo_b;       // lean frame: something this frame needs the general code (the frame is redone there);
+                              // set before the first / between the first and the second barrier of the frame
+  int32_t wcount[16];         // lean frame: states each wave created; wbase: the same as exclusive prefix sums
+  int32_t wbase[16];
   int32_t a_maxtok, a_slow;   // counters of this call
+  int32_t a_lean;             // frames decoded by the lean code
+#ifdef CBD_PROFILE
+  long long prof[12];
+  long long prof_last;
+  int32_t prof_redo;
+#endif
   unsigned long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
 
@@ -169,25 +201,40 @@ __device__ __forceinline__ int sh_log_n(const Shared *sh) { return (int)(uint32_
 __device__ __forceinline__ int sh_n_claim(const Shared *sh) { return (int)(uint32_t)(sh->log_claim >> 32); }
 
 struct LdsLayout {
-  uint32_t sh, hist, bitmap, owner, ctx, L, hval, hkey, hidx, tcost, log, total;
+  uint32_t sh, hist, bitmap, owner, cmap, ctx, L, hval, hkey, hidx, tcost, log, total;
 };
 
 __host__ __device__ inline uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
 
-__host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, int tok_cap, int slots, int log_cap) {
+// What the lean frame code keeps where the general code has its change log: the tokens' rows (4 + 2 bytes per
+// token), the rows of the states in the table (4 + 1 bytes per slot) and the waves' commit logs (8-byte entries).
+__host__ __device__ inline uint32_t lean_region_bytes(int tok_cap, int slots, int log_entries) {
+  return align_up((uint32_t)tok_cap * 6, 16) + align_up((uint32_t)slots * 5, 16) + (uint32_t)log_entries * 8;
+}
+
+// lean_log_entries: room for the lean frame code's commit logs (all waves together); its region is shared with
+// the change log and sized for whichever needs more.
+__host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, int tok_cap, int slots, int log_cap,
+                                                 int lean_log_entries = 0) {
   LdsLayout l;
   uint32_t o = 0;
   l.sh = o; o += align_up((uint32_t)sizeof(Shared), 16);
   l.hist = o; o += 256 * 4;
   l.bitmap = o; o += 512 * 4;
   l.owner = o; o += 16 * 256;   // per-wave owner map of the first 256 arcs of a tile
+  l.cmap = o; o += 16 * 64;     // per-wave owner map of a closure stage's records
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
   l.L = o; o += align_up((uint32_t)num_pdfs * 4, 16);
   l.hval = o; o += (uint32_t)slots * 8;
   l.hkey = o; o += (uint32_t)slots * 4;
   l.hidx = o; o += align_up((uint32_t)slots * 2, 16);
   l.tcost = o; o += align_up((uint32_t)tok_cap * 4, 16);
-  l.log = o; o += align_up((uint32_t)log_cap * 8, 16);
+  l.log = o;
+  {
+    const uint32_t general = align_up((uint32_t)log_cap * 8, 16);
+    const uint32_t lean = lean_log_entries > 0 ? lean_region_bytes(tok_cap, slots, lean_log_entries) : 0;
+    o += general > lean ? general : lean;
+  }
   l.total = o;
   return l;
 }
@@ -229,6 +276,19 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
   s += dpp_step<kRowShr8, 0xf, 0xc>(0, s);
   s += dpp_step<kRowBcast15, 0xa, 0xf>(0, s);
   s += dpp_step<kRowBcast31, 0xc, 0xf>(0, s);
+  return s;
+}
+
+// Inclusive running maximum over the 64 lanes (values >= 0), same ladder.
+__device__ __forceinline__ int wave_incl_scan_max(int v) {
+  int s = v;
+  s = max(s, dpp_step<kRowShr1, 0xf, 0xf>(0, v));
+  s = max(s, dpp_step<kRowShr2, 0xf, 0xf>(0, v));
+  s = max(s, dpp_step<kRowShr3, 0xf, 0xf>(0, v));
+  s = max(s, dpp_step<kRowShr4, 0xf, 0xe>(0, s));
+  s = max(s, dpp_step<kRowShr8, 0xf, 0xc>(0, s));
+  s = max(s, dpp_step<kRowBcast15, 0xa, 0xf>(0, s));
+  s = max(s, dpp_step<kRowBcast31, 0xc, 0xf>(0, s));
   return s;
 }
 
@@ -344,15 +404,15 @@ struct RowInfo { int first, eps, end; };
 
 __device__ __forceinline__ RowInfo row_of(const AdvanceParams &p, const ArcRec &rec) {
   RowInfo r;
-  uint32_t ed = (rec.meta >> 16) & 255u, xd = rec.meta >> 24;
+  uint32_t ed = meta_ed(rec.meta), xd = meta_xd(rec.meta);
   r.first = rec.row;
-  if (ed == kDegEscape || xd == kDegEscape) {
+  if (ed == kEdEscape || xd == kXdEscape) {
     // a long row (rare): its bounds come from the offsets.  The wait is taken here, inside the rare branch, so
     // that code after it never has to wait for "a load that may have happened" (which would also make it wait
     // for the arc records requested ahead of need).
-    int2 o = p.off2[rec.dst], o2 = p.off2[rec.dst + 1];
+    int4 o = p.off2[rec.dst];
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    r.eps = o.y; r.end = o2.x;
+    r.eps = o.y; r.end = o.z;
   } else {
     r.eps = r.first + (int)ed; r.end = r.eps + (int)xd;
   }
@@ -794,7 +854,7 @@ __device__ __forceinline__ void frame_init(Shared *sh, uint32_t *hist, bool star
     sh->m_ord = start ? f2ord(0.0f) : 0xFFFFFFFFu;
     sh->best_ord = 0xFFFFFFFFu;   // minimum over closure candidates; the table's minimum is min(m, this)
     sh->log_claim = 0; sh->n_front[0] = 0; sh->n_front[1] = 0; sh->n_surv = 0; sh->n_live = 0; sh->rounds = 0;
-    sh->fault = 0; sh->diverged = 0; sh->halt = 0; sh->n_big = 0;
+    sh->fault = 0; sh->diverged = 0; sh->halt = 0; sh->n_big = 0; sh->redo = 0; sh->redo_b = 0; sh->n_done = 0;
   }
 }
 
@@ -840,8 +900,8 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
       uint32_t h = 0;
       uint64_t key = ((uint64_t)f2ord(0.0f) << 32) | kArcNone;
       bool improved = false, claimed = false;
-      int2 o = p.off2[p.start_state], o2 = p.off2[p.start_state + 1];
-      RowInfo row; row.first = o.x; row.eps = o.y; row.end = o2.x;
+      int4 o = p.off2[p.start_state];
+      RowInfo row; row.first = o.x; row.eps = o.y; row.end = o.z;
       if (lane == 0) improved = table_min<kLds>(M, sh, (uint32_t)p.start_state, key, h, claimed);
       uint32_t src = LogE::kSrcNone | ((row.end > row.eps) ? LogE::kSrcHasEps : 0u);
       record<kLds>(M, sh, &sh->n_front[0], no, improved, claimed, kArcNone, h, src, row, lane);
@@ -1139,6 +1199,35 @@ __device__ __forceinline__ int run_frame(const AdvanceParams &p, const Mem<kLds>
   return kFrameOk;
 }
 
+}  // namespace cbd
+#include "cbd_lean.hpp"
+namespace cbd {
+
+// Where the current tokens' arc rows are kept changes with the code that decodes the next frame: the lean code
+// wants them in LDS, the general code in the channel's row buffer in device memory.
+template <int kBlock>
+__device__ __forceinline__ void rows_to_lds(const Mem<true> &M, const LeanMem &R, int n_tok, int row_buf) {
+  const int4 *rows = M.t_row + (size_t)row_buf * M.row_cap;
+  for (int i = threadIdx.x; i < n_tok; i += kBlock) {
+    const int2 fe = load_row_fe(&rows[i]);
+    const int deg = fe.y - fe.x;
+    R.t_first[i] = fe.x;
+    R.t_deg[i] = deg < (int)kEdEscape ? (uint16_t)deg : kLeanDegEscape;
+  }
+  __syncthreads();
+}
+template <int kBlock>
+__device__ __forceinline__ void rows_to_device(const Mem<true> &M, const LeanMem &R, int n_tok, int row_buf) {
+  int4 *rows = M.t_row + (size_t)row_buf * M.row_cap;
+  for (int i = threadIdx.x; i < n_tok; i += kBlock) {
+    const int first = R.t_first[i];
+    const uint16_t deg = R.t_deg[i];
+    // (a row too long for the count field was written to the row buffer when its token was made)
+    if (deg != kLeanDegEscape) rows[i] = make_int4(first, first + (int)deg, 0, 0);
+  }
+  __syncthreads();   // (waits for the stores: other waves read the rows past their L1)
+}
+
 template <int kBlock>
 __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -1146,11 +1235,12 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   const int c = p.chan_ids[blockIdx.x];
   ChanState *cs = p.chan + c;
   const LdsLayout lay = make_layout(p.stage_rows ? p.num_pdfs : 0, p.ctx_lds_cap, p.lds_tok_cap, p.lds_slots,
-                                    p.lds_log_cap);
+                                    p.lds_log_cap, p.lean_log_per_wave * (kBlock / 64));
   Shared *sh = (Shared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
   uint8_t *owner_maps = (uint8_t *)(smem + lay.owner);
+  uint8_t *closure_maps = (uint8_t *)(smem + lay.cmap);
   int32_t *ctx_lds = (int32_t *)(smem + lay.ctx);
   float *Lrow = (float *)(smem + lay.L);
 
@@ -1163,15 +1253,20 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   ML.t_row = p.tok_row + (size_t)c * 2 * p.g_tok_cap;
   ML.slots = (uint32_t)p.lds_slots; ML.tok_cap = p.lds_tok_cap; ML.log_cap = p.lds_log_cap; ML.row_cap = p.g_tok_cap;
 
-  Mem<false> MG;
-  MG.hval = p.g_hval + (size_t)c * p.g_slots;
-  MG.hkey = p.g_hkey + (size_t)c * p.g_slots;
-  MG.hidx = p.g_hidx + (size_t)c * p.g_slots;
-  MG.t_row = ML.t_row;
-  MG.t_cost = p.tok_cost + (size_t)c * p.g_tok_cap;
-  MG.log = p.g_log + (size_t)c * p.g_log_cap;
-  MG.slots = (uint32_t)p.g_slots; MG.tok_cap = p.g_tok_cap; MG.log_cap = p.g_log_cap; MG.row_cap = p.g_tok_cap;
-
+  // (the tables in device memory are described where they are used: few frames need them, and every pointer that
+  // lives through the frame loop costs the lean frames registers)
+  auto make_MG = [&]() {
+    Mem<false> G;
+    G.hval = p.g_hval + (size_t)c * p.g_slots;
+    G.hkey = p.g_hkey + (size_t)c * p.g_slots;
+    G.hidx = p.g_hidx + (size_t)c * p.g_slots;
+    G.t_row = p.tok_row + (size_t)c * 2 * p.g_tok_cap;
+    G.t_cost = p.tok_cost + (size_t)c * p.g_tok_cap;
+    G.log = p.g_log + (size_t)c * p.g_log_cap;
+    G.slots = (uint32_t)p.g_slots; G.tok_cap = p.g_tok_cap; G.log_cap = p.g_log_cap; G.row_cap = p.g_tok_cap;
+    return G;
+  };
+  auto g_cost = [&]() { return p.tok_cost + (size_t)c * p.g_tok_cap; };
   int32_t *g_tok_state = p.tok_state + (size_t)c * p.g_tok_cap;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
   const float *Lbase = p.loglikes + (long long)blockIdx.x * p.channel_stride;
@@ -1220,14 +1315,21 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   int cur = p.do_reset ? 0 : (cs->row_buf & 1);
   for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
   if (fast) {
-    for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = MG.t_cost[i];
+    { float *gc = g_cost(); for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = gc[i]; }
   }
   if (p.n_frames > 0 && p.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = Lbase[i];
   __syncthreads();
 
   int outcome = kFrameOk;
   if (tid < 64) frame_init(sh, hist, p.do_reset != 0, tid);
+  if (tid == 0) sh->a_lean = 0;
+#ifdef CBD_PROFILE
+  if (tid == 0) { for (int k = 0; k < 12; ++k) sh->prof[k] = 0; sh->prof_redo = 0; }
+  const long long prof_k0 = wall_clock64();
+#endif
   __syncthreads();
+  const LeanMem LM = make_lean_mem(ML.log, p.lds_tok_cap, p.lds_slots, p.lean_log_per_wave);
+  bool rows_in_lds = false;   // the current tokens' rows: in LDS (lean frames) or in the row buffer `cur`
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
     const float *Lnext = (p.stage_rows && f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
     Rows rows;
@@ -1235,11 +1337,35 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     const bool last = f == p.n_frames - 1;
     bool slow = !fast;
     if (fast) {
-      outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+      // frames go to the lean code; whatever that cannot take comes back
+      const bool lean = p.lean_frames && f >= 0;
+      if (lean) {
+        if (!rows_in_lds) { rows_to_lds<kBlock>(ML, LM, sh->n_tok, cur); rows_in_lds = true; }
+        outcome = run_frame_lean<kBlock>(p, ML, LM, sh, cx, Lrow, rows, Lnext, hist, owner_maps, closure_maps, cur, bp,
+                                         g_tok_state, last);
+        if (outcome == kFrameRedo) {
+#ifdef CBD_PROFILE
+          if (tid == 0) sh->prof_redo += 1;
+#endif
+          // wipe the table, bring this frame's log-likelihood row back, hand the rows to the general code
+          __syncthreads();
+          for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
+          if (p.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = rows.glob[i];
+          rows_to_device<kBlock>(ML, LM, sh->n_tok, cur);
+          rows_in_lds = false;
+          if (tid < 64) frame_init(sh, hist, false, tid);
+          __syncthreads();
+        }
+      }
+      if (!lean || outcome == kFrameRedo) {
+        if (rows_in_lds) { rows_to_device<kBlock>(ML, LM, sh->n_tok, cur); rows_in_lds = false; }
+        outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+        if (outcome == kFrameOk) cur ^= 1;
+      }
       if (outcome == kFrameOverflow) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the costs over
         for (int i = tid; i < p.lds_slots; i += kBlock) { ML.hval[i] = kEmptyVal; ML.hkey[i] = kEmptyKey; }
-        for (int i = tid; i < sh->n_tok; i += kBlock) MG.t_cost[i] = ML.t_cost[i];
+        { float *gc = g_cost(); for (int i = tid; i < sh->n_tok; i += kBlock) gc[i] = ML.t_cost[i]; }
         // (the abandoned attempt has already parked the next frame's log-likelihood row: bring this frame's back)
         if (p.stage_rows && f >= 0) for (int i = tid; i < p.num_pdfs; i += kBlock) Lrow[i] = rows.glob[i];
         __syncthreads();
@@ -1248,12 +1374,15 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         fast = false; slow = true;
       }
     }
-    if (slow) outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+    if (slow) {
+      const Mem<false> MG = make_MG();
+      outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+      if (outcome == kFrameOk) cur ^= 1;
+    }
     if (outcome != kFrameOk) break;
-    cur ^= 1;
     if (!fast && p.lds_tok_cap > 0 && sh->n_tok <= p.lds_tok_cap) {
       // the token list fits LDS again
-      for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = MG.t_cost[i];
+      { float *gc = g_cost(); for (int i = tid; i < sh->n_tok; i += kBlock) ML.t_cost[i] = gc[i]; }
       fast = true;
       __syncthreads();
     }
@@ -1261,6 +1390,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
 
   // ---- leave: a frame that produced nothing, overflowed or diverged parks the channel
   __syncthreads();
+  if (rows_in_lds && outcome == kFrameOk) rows_to_device<kBlock>(ML, LM, sh->n_tok, cur);   // the next call finds them there
   int status = kStatusOk;
   if (outcome == kFrameOverflow || outcome == kFrameRecordsFull) status = kStatusCapacity;
   else if (outcome == kFrameNoTokens) status = kStatusNoTokens;
@@ -1269,11 +1399,11 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     // the tokens' costs leave through device memory
     const int n = sh->n_tok;
     if (fast) {
-      for (int i = tid; i < n; i += kBlock) MG.t_cost[i] = ML.t_cost[i];
+      { float *gc = g_cost(); for (int i = tid; i < n; i += kBlock) gc[i] = ML.t_cost[i]; }
     }
   } else if (outcome != kFrameNoTokens) {
     // leave the device-memory table empty for the next utterance
-    for (int i = tid; i < p.g_slots; i += kBlock) { stv<false>(&MG.hkey[i], kEmptyKey); stv<false>(&MG.hval[i], kEmptyVal); }
+    { const Mem<false> MG = make_MG(); for (int i = tid; i < p.g_slots; i += kBlock) { stv<false>(&MG.hkey[i], kEmptyKey); stv<false>(&MG.hval[i], kEmptyVal); } }
   }
   if (tid == 0) {
     cs->status = status;
@@ -1287,7 +1417,19 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       cs->frames = 0; cs->active_tokens = 0; cs->emit_arcs = 0; cs->eps_arcs = 0; cs->candidates = 0;
       cs->improvements = 0; cs->tokens = 0; cs->eps_rounds = 0; cs->max_tokens = 0; cs->slow_frames = 0;
       cs->gc_base = 0; cs->gc_runs = 0; cs->gc_dropped = 0; cs->n_fixed_arcs = 0; cs->n_fixed_words = 0;
+      cs->lean_frames = 0;
     }
+    cs->lean_frames += sh->a_lean;
+#ifdef CBD_PROFILE
+    if (p.do_reset) for (int k = 0; k < 15; ++k) cs->spare[k] = 0;
+    for (int k = 0; k < 7; ++k) cs->spare[k] += sh->prof[k];
+    cs->spare[12] += sh->prof[7]; cs->spare[13] += sh->prof[8];
+    cs->spare[7] += sh->prof[9]; cs->spare[14] += sh->prof[10];
+    cs->spare[8] += sh->prof_redo;
+    cs->spare[9] += wall_clock64() - prof_k0;   // the workgroup's whole run
+    cs->spare[10] += sh->a_lean;
+    cs->spare[11] += (long long)sh->a_frames;
+#endif
     cs->frames += sh->a_frames; cs->active_tokens += sh->a_active; cs->emit_arcs += sh->a_emit;
     cs->eps_arcs += sh->a_eps; cs->candidates += sh->a_cand; cs->improvements += sh->a_impr;
     cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
@@ -1309,7 +1451,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       if (status == kStatusOk) {
         const int n = sh->n_tok, base = sh->frame_base;
         for (int t = lane; t < n; t += 64) {
-          const float cost = __hip_atomic_load(&MG.t_cost[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const float cost = __hip_atomic_load(&g_cost()[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           if (!(cost < __builtin_inff())) continue;   // dropped by the frame cutoff
           const unsigned long long rec = __hip_atomic_load((const unsigned long long *)&bp[base + t], __ATOMIC_RELAXED,
                                                            __HIP_MEMORY_SCOPE_AGENT);
