@@ -739,17 +739,16 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     int32_t *sp = nullptr;   // cbd_best_paths_static's array on this device: resolved here, once
     DCHK(static_scratch(g->device, &sp));
   }
-  int lds_limit = 0, n_cu = 0;
+  int lds_limit = 0;
   DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
-  DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
   {
-    // How many workgroups (channels) share a compute unit's LDS.  A 1024-thread workgroup finishes a frame
-    // fastest, so one channel per compute unit is right while there are no more channels than compute units.
-    // With more channels, two 512-thread workgroups side by side hide each other's dependent chains: each is
-    // 1.4x slower, both together get more done (measured: 512 channels -16 % per launch, 2048 channels -2 %), at
-    // half the table capacity each (the log-likelihood row then stays in device memory / L2).
+    // How many workgroups (channels) share a compute unit's LDS.  One 1024-thread workgroup per compute unit is
+    // the default at every channel count: the frame code keeps the vector units busy about half the time, so two
+    // 512-thread workgroups side by side gain little from hiding each other's waits and lose more to the halved
+    // table capacity, which sends their larger frames to the tables in device memory (measured with 512 channels:
+    // 3.3 instead of 2.05 ms per launch; with 2048: 11.2 instead of 5.9 ms).  A caller can still ask for 2 or 4.
     int wgs = cfg->workgroups_per_cu;
-    if (wgs == 0) wgs = d->C > n_cu ? 2 : 1;
+    if (wgs == 0) wgs = 1;
     // (a little LDS per compute unit is left for the partial-result walks, which run beside the decoding)
     const int budget = (lds_limit - 1024) / wgs;
     // the lean frame code keeps a commit log per wave next to the tokens' rows (decided with the block size below)

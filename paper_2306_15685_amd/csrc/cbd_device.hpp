@@ -189,6 +189,8 @@ struct Shared {
   int32_t wbase[16];
   int32_t a_maxtok, a_slow;   // counters of this call
   int32_t a_lean;             // frames decoded by the lean code
+  unsigned long long a_lean_pack[2];   // its counters, two to a word: active tokens | emitting arcs << 32,
+                                       // epsilon-input arcs | candidates << 32
 #ifdef CBD_PROFILE
   long long prof[12];
   long long prof_last;
@@ -279,17 +281,18 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
   return s;
 }
 
-// Inclusive running maximum over the 64 lanes (values >= 0), same ladder.
+// Inclusive running maximum over the 64 lanes (values >= 0), same ladder.  The arithmetic is unsigned: 0 is then
+// the maximum's identity, and a lane a step does not reach keeps its value in one instruction.
 __device__ __forceinline__ int wave_incl_scan_max(int v) {
-  int s = v;
-  s = max(s, dpp_step<kRowShr1, 0xf, 0xf>(0, v));
-  s = max(s, dpp_step<kRowShr2, 0xf, 0xf>(0, v));
-  s = max(s, dpp_step<kRowShr3, 0xf, 0xf>(0, v));
-  s = max(s, dpp_step<kRowShr4, 0xf, 0xe>(0, s));
-  s = max(s, dpp_step<kRowShr8, 0xf, 0xc>(0, s));
-  s = max(s, dpp_step<kRowBcast15, 0xa, 0xf>(0, s));
-  s = max(s, dpp_step<kRowBcast31, 0xc, 0xf>(0, s));
-  return s;
+  uint32_t s = (uint32_t)v;
+  s = max(s, (uint32_t)dpp_step<kRowShr1, 0xf, 0xf>(0, v));
+  s = max(s, (uint32_t)dpp_step<kRowShr2, 0xf, 0xf>(0, v));
+  s = max(s, (uint32_t)dpp_step<kRowShr3, 0xf, 0xf>(0, v));
+  s = max(s, (uint32_t)dpp_step<kRowShr4, 0xf, 0xe>(0, (int)s));
+  s = max(s, (uint32_t)dpp_step<kRowShr8, 0xf, 0xc>(0, (int)s));
+  s = max(s, (uint32_t)dpp_step<kRowBcast15, 0xa, 0xf>(0, (int)s));
+  s = max(s, (uint32_t)dpp_step<kRowBcast31, 0xc, 0xf>(0, (int)s));
+  return (int)s;
 }
 
 __device__ __forceinline__ uint32_t umin32(uint32_t a, uint32_t b) { return a < b ? a : b; }
@@ -336,9 +339,10 @@ __device__ __forceinline__ bool sorted_contains(ListPtr list, int n, int32_t a) 
   return lo < n && list[lo] == a;
 }
 
-constexpr int kBloomWords = 512;  // 16K bits, two hash functions
-__device__ __forceinline__ uint32_t bloom_bit0(int32_t a) { return ((uint32_t)a * 2654435761u) >> 18; }
-__device__ __forceinline__ uint32_t bloom_bit1(int32_t a) { return ((uint32_t)a * 2246822519u + 0x9E3779B9u) >> 18; }
+constexpr int kBloomWords = 512;  // 16K bits; an arc sets two bits of one word, so a test is one read
+__device__ __forceinline__ uint32_t bloom_hash(int32_t a) { return (uint32_t)a * 2654435761u; }
+__device__ __forceinline__ uint32_t bloom_word(uint32_t h) { return h >> 23; }
+__device__ __forceinline__ uint32_t bloom_mask(uint32_t h) { return (1u << ((h >> 18) & 31u)) | (1u << ((h >> 13) & 31u)); }
 
 // LDS-typed pointers: reads through them are plain LDS reads, not generic loads
 typedef const __attribute__((address_space(3))) float *lds_cfloat_ptr;
@@ -369,9 +373,8 @@ struct Rows {
 __device__ __forceinline__ bool ctx_contains(const Ctx &cx, int32_t a) {
   if (cx.n == 0) return false;
   if (cx.use_bitmap) {
-    uint32_t b0 = bloom_bit0(a), b1 = bloom_bit1(a);
-    uint32_t w0 = cx.bitmap[b0 >> 5], w1 = cx.bitmap[b1 >> 5];
-    if (!((w0 >> (b0 & 31)) & (w1 >> (b1 & 31)) & 1u)) return false;
+    const uint32_t h = bloom_hash(a), mask = bloom_mask(h);
+    if ((cx.bitmap[bloom_word(h)] & mask) != mask) return false;
   }
   if (cx.in_lds) return sorted_contains(cx.lds_list, cx.n, a);
   return sorted_contains(cx.g_list, cx.n, a);
@@ -1305,9 +1308,8 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     for (int i = tid; i < kBloomWords; i += kBlock) bitmap[i] = 0;
     __syncthreads();
     for (int i = tid; i < cx.n; i += kBlock) {
-      uint32_t b0 = bloom_bit0(cx.g_list[i]), b1 = bloom_bit1(cx.g_list[i]);
-      atomicOr(&bitmap[b0 >> 5], 1u << (b0 & 31));
-      atomicOr(&bitmap[b1 >> 5], 1u << (b1 & 31));
+      const uint32_t h = bloom_hash(cx.g_list[i]);
+      atomicOr(&bitmap[bloom_word(h)], bloom_mask(h));
     }
   }
   // the tokens' costs enter through device memory; LDS takes them over when they fit
@@ -1322,7 +1324,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
 
   int outcome = kFrameOk;
   if (tid < 64) frame_init(sh, hist, p.do_reset != 0, tid);
-  if (tid == 0) sh->a_lean = 0;
+  if (tid == 0) { sh->a_lean = 0; sh->a_lean_pack[0] = 0; sh->a_lean_pack[1] = 0; }
 #ifdef CBD_PROFILE
   if (tid == 0) { for (int k = 0; k < 12; ++k) sh->prof[k] = 0; sh->prof_redo = 0; }
   const long long prof_k0 = wall_clock64();
@@ -1424,14 +1426,17 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     if (p.do_reset) for (int k = 0; k < 15; ++k) cs->spare[k] = 0;
     for (int k = 0; k < 7; ++k) cs->spare[k] += sh->prof[k];
     cs->spare[12] += sh->prof[7]; cs->spare[13] += sh->prof[8];
-    cs->spare[7] += sh->prof[9]; cs->spare[14] += sh->prof[10];
     cs->spare[8] += sh->prof_redo;
     cs->spare[9] += wall_clock64() - prof_k0;   // the workgroup's whole run
     cs->spare[10] += sh->a_lean;
     cs->spare[11] += (long long)sh->a_frames;
 #endif
-    cs->frames += sh->a_frames; cs->active_tokens += sh->a_active; cs->emit_arcs += sh->a_emit;
-    cs->eps_arcs += sh->a_eps; cs->candidates += sh->a_cand; cs->improvements += sh->a_impr;
+    cs->frames += sh->a_frames;
+    cs->active_tokens += sh->a_active + (sh->a_lean_pack[0] & 0xFFFFFFFFull);
+    cs->emit_arcs += sh->a_emit + (sh->a_lean_pack[0] >> 32);
+    cs->eps_arcs += sh->a_eps + (sh->a_lean_pack[1] & 0xFFFFFFFFull);
+    cs->candidates += sh->a_cand + (sh->a_lean_pack[1] >> 32);
+    cs->improvements += sh->a_impr;
     cs->tokens += sh->a_tokens; cs->eps_rounds += sh->a_rounds;
     if (sh->a_maxtok > cs->max_tokens) cs->max_tokens = sh->a_maxtok;
     cs->slow_frames += sh->a_slow;

@@ -402,6 +402,7 @@ __device__ __forceinline__ void lean_commit(const AdvanceParams &p, const Mem<tr
     }
   }
   const LeanClosure C = lean_closure_begin(p, sh, lane, cmap, pos, len, E.cand);
+  CBD_STAMP(6);   // (diagnostic: cutoff, slot requests, closure records requested)
   // now the emitting candidates' slots
 #pragma unroll
   for (int q = 0; q < 2; ++q) lean_slot_collisions(M, sh, pass[q], (uint32_t)E.rec[q].dst, h[q], k[q]);
@@ -412,7 +413,9 @@ __device__ __forceinline__ void lean_commit(const AdvanceParams &p, const Mem<tr
     const uint64_t key = ((uint64_t)f2ord(E.cand[q]) << 32) | (uint32_t)E.arc[q];
     lean_min_and_log(M, R, sh, pass[q], h[q], k[q], key, E.rec[q], (uint32_t)E.src[q] | kLeanFromToken, wave, lane, W);
   }
+  CBD_STAMP(7);   // (diagnostic: emitting candidates committed)
   lean_closure_end(p, M, R, sh, cx, m, wave, lane, W, C, h);
+  CBD_STAMP(8);   // (diagnostic: closure records committed)
 }
 
 // One frame by the lean code.  Returns kFrameOk, kFrameNoTokens, kFrameRecordsFull, or kFrameRedo (then nothing
@@ -486,17 +489,7 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
   }
   // The emit phase is long over: the next frame's row starts its way.  (Not earlier: loads return in order, and
   // the closure stages' reads would queue behind the row.)
-#ifdef EXP_ROW_REGS
-  constexpr int kPre = kBlock >= 1024 ? 6 : (kBlock >= 960 ? 7 : 8);
-  float pre[kPre];
-#pragma unroll
-  for (int k = 0; k < kPre; ++k) {
-    const int ii = tid + k * kBlock;
-    pre[k] = (Lnext && ii < p.num_pdfs) ? Lnext[ii] : 0.0f;
-  }
-#else
   if (Lnext) stage_row_async<kBlock>(Lstage, Lnext, p.num_pdfs, wave, lane);
-#endif
   if (lane == 0) sh->wcount[wave] = W.n_claimed;
   CBD_STAMP(2);   // commit phase of wave 0
   wg_barrier<true>();
@@ -581,10 +574,9 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
   int done = 0;
   if (lane == 0) {
     if (w_surv) atomicAdd(&sh->n_surv, w_surv);
-    if (n_active_frame) atomicAdd(&sh->a_active, (unsigned long long)n_active_frame);
-    if (n_emit) atomicAdd(&sh->a_emit, (unsigned long long)n_emit);
-    if (W.n_eps) atomicAdd(&sh->a_eps, (unsigned long long)W.n_eps);
-    if (W.n_cand) atomicAdd(&sh->a_cand, (unsigned long long)W.n_cand);
+    // (two counters to an atomic; they are taken apart when the call ends)
+    atomicAdd(&sh->a_lean_pack[0], (unsigned long long)n_active_frame | ((unsigned long long)n_emit << 32));
+    atomicAdd(&sh->a_lean_pack[1], (unsigned long long)W.n_eps | ((unsigned long long)W.n_cand << 32));
     if (W.max_depth) atomicMax(&sh->rounds, W.max_depth);
     done = atomicAdd(&sh->n_done, 1);
   }
@@ -619,16 +611,6 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
     }
     frame_init(sh, hist, false, lane, hist_need);   // for the next frame
   }
-#ifdef EXP_ROW_REGS
-  if (Lnext) {
-#pragma unroll
-    for (int k = 0; k < kPre; ++k) {
-      const int ii = tid + k * kBlock;
-      if (ii < p.num_pdfs) Lstage[ii] = pre[k];
-    }
-    for (int ii = tid + kPre * kBlock; ii < p.num_pdfs; ii += kBlock) Lstage[ii] = Lnext[ii];
-  }
-#endif
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next row have arrived in LDS
   wg_barrier<true>();
   CBD_STAMP(5);   // its wait at the last barrier (with the closing of the frame by the last wave)
