@@ -34,15 +34,33 @@ class Inputs:
     w: synth.Workload
     g: synth.Graph
     loglikes: list  # per segment: device tensor [C, frames, P]
-    contexts: list  # per segment: (lists, offsets)
+    contexts: Optional[list]  # per segment: (arc lists, offsets); None until built from `sequences`
+    sequences: Optional[list] = None  # per segment: (per-channel lists of word sequences, offsets)
+    context_build: Optional[Dict] = None  # host time of Algorithm 1 (filled with `contexts`)
 
 
 def make_inputs(w: synth.Workload, g: Optional[synth.Graph] = None, device: str = "cuda") -> Inputs:
+    """Synthetic inputs of a workload.  A workload whose graph spaces its word labels (word_period) gets its
+    biasing lists as word sequences; the arc lists are made of them by the library (contexts_from_words)."""
     g = g if g is not None else synth.graph_for(w)
     L = [synth.make_loglikes(w.channels, w.frames, w.num_pdfs, w.sigma, seed_stream=(w.config_id, s), device=device)
          for s in range(w.segments)]
+    if w.word_period > 0:
+        return Inputs(w, g, L, None, [synth.make_context_sequences(w, g, segment=s) for s in range(w.segments)])
     ctx = [synth.make_contexts(w, g, segment=s) for s in range(w.segments)]
     return Inputs(w, g, L, ctx)
+
+
+def contexts_from_words(graph_handle, sequences: list):
+    """Algorithm 1 through the library for every channel's list of word sequences (Sec. 4.1) -> the (arc lists,
+    offsets) per segment that the decoder takes, and the host time the calls took."""
+    out, n, t0 = [], 0, time.perf_counter()
+    for per_channel, offs in sequences:
+        out.append(([B.cbd_context_from_words(graph_handle, seqs) for seqs in per_channel], offs))
+        n += len(per_channel)
+    dt = time.perf_counter() - t0
+    arcs = sum(int(x.size) for lists, _ in out for x in lists)
+    return out, {"lists": n, "ms_per_list": 1e3 * dt / max(n, 1), "arcs_per_list": arcs / max(n, 1), "threads": 1}
 
 
 class Session:
@@ -67,9 +85,12 @@ class Session:
         self.own_graph = graph_handle is None
         self.gh = graph_handle if graph_handle is not None else B.cbd_graph_load(
             g.num_states, g.num_pdfs, g.start_state, g.row_offsets, g.dst, g.ilabel, g.olabel, g.weight, g.final_cost)
+        if inp.contexts is None:
+            inp.contexts, inp.context_build = contexts_from_words(self.gh, inp.sequences)
+        max_ctx = max([w.ctx_max, 1] + [int(x.size) for lists, _ in inp.contexts for x in lists])
         self.stream = torch.cuda.current_stream()
         self.dh = B.cbd_decoder_create(
-            self.gh, w.channels, w.beam, w.max_active, record_frames or w.frames, max(w.ctx_max, 1), w.lookup_mode,
+            self.gh, w.channels, w.beam, w.max_active, record_frames or w.frames, max_ctx, w.lookup_mode,
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
             records_per_frame or default_records_per_frame(w), table_location, lds_token_cap,
             w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu, compact_records_above,

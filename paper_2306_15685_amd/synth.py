@@ -47,6 +47,7 @@ class Workload:
     partial_every_chunk: bool = False
     mean_degree: float = 3.0
     word_frac: float = 0.25
+    word_period: int = 0  # > 0: word labels every word_period arcs (see make_graph); contexts are word sequences
     config_id: int = 0
     graph_id: int = -1  # seed stream of the decoding graph (-1: config_id); workloads that share a graph share it
 
@@ -62,6 +63,10 @@ WORKLOADS: Dict[str, Workload] = {
                         10, 1_000, -8.0, -2.0, segments=20, lookup_mode=1, config_id=3, graph_id=2),
     "stress": Workload("stress", 10_000_000, 6_000, 200_000, 0.10, 2_048, 300, 50, 16.0, 20_000, 4.0,
                        1_000, 1_000, -5.0, -5.0, lookup_mode=1, config_id=4, graph_id=2),
+    # contexts given as word sequences and turned into arc lists by Algorithm 1 (Sec. 4.1); the graph keeps its
+    # word labels four arcs apart, as a composed decoding graph does, so that the algorithm's search stays local
+    "words": Workload("words", 2_000_000, 4_000, 50_000, 0.10, 128, 300, 50, 15.0, 10_000, 4.0,
+                      100, 500, -5.0, -5.0, partial_every_chunk=True, lookup_mode=1, word_period=4, config_id=6),
     # second workload: lexicon loop over end-to-end units (dense token activity, a 20,000-arc hub row,
     # max-active pruning engaged); contexts are word-end arcs (unigram boosting)
     "e2e": Workload("e2e", 0, 96, 20_000, 0.0, 64, 200, 50, 10.0, 2_500, 2.0,
@@ -113,7 +118,7 @@ class Graph:
 def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
                seed_stream: Tuple[int, ...] = (0,), mean_degree: float = 3.0,
                word_frac: float = 0.25, with_finals: bool = False,
-               self_loop_frac: float = 0.0) -> Graph:
+               self_loop_frac: float = 0.0, word_period: int = 0) -> Graph:
     """Random HCLG-like graph.
 
     Out-degree is Poisson(mean_degree) clipped to at least 1.  Each arc is an
@@ -123,6 +128,11 @@ def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
     random pdf.  A fraction ``word_frac`` of all arcs carry a uniformly random
     word.  Weights are -ln U(0.05, 1).  Epsilon and emitting arcs are interleaved
     within a row, in no particular order.
+
+    With ``word_period`` p > 0 the words sit as they do in a composed decoding graph, p arcs apart: state s is at
+    position s mod p inside a word, every arc leads to a state at the next position, and exactly the arcs that
+    close a word (into position 0) carry a word label, so ``word_frac`` is 1/p.  From any state only a few dozen
+    states can be reached without crossing a word label, which is what Algorithm 1's search relies on.
     """
     S = int(num_states)
     rng = _rng(1, *seed_stream)
@@ -139,6 +149,14 @@ def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
     eps_dst = src + 1 + np.floor(u * (S - 1 - src)).astype(np.int64)
     eps_dst = np.minimum(eps_dst, S - 1)
     dst = np.where(is_eps, eps_dst, dst)
+    if word_period > 0:
+        p = int(word_period)
+        want = (src + 1) % p                       # position of the destination inside its word
+        moved = dst - (dst % p) + want
+        moved = np.where(is_eps & (moved <= src), moved + p, moved)   # epsilon arcs keep leading upwards
+        fits = moved < S
+        is_eps &= fits                              # (an arc pushed past the last state becomes an emitting arc
+        dst = np.where(fits, moved, want)           #  into the first block of states)
     if self_loop_frac > 0.0:
         loop = (~is_eps) & (rng.random(A) < self_loop_frac)
         dst = np.where(loop, src, dst)
@@ -146,6 +164,8 @@ def make_graph(num_states: int, num_pdfs: int, num_words: int, eps_prob: float,
     ilabel = np.where(is_eps, 0, pdf + 1)
     word = rng.integers(1, num_words + 1, A, dtype=np.int64)
     olabel = np.where(rng.random(A) < word_frac, word, 0)
+    if word_period > 0:
+        olabel = np.where(dst % int(word_period) == 0, word, 0)
     weight = (-np.log(rng.uniform(0.05, 1.0, A))).astype(np.float32)
     final = None
     if with_finals:
@@ -202,7 +222,7 @@ def graph_for(w: Workload, with_finals: bool = False) -> Graph:
         return make_lexicon_graph(w.num_pdfs, w.num_words, seed_stream=(gid,))
     return make_graph(w.num_states, w.num_pdfs, w.num_words, w.eps_prob,
                       seed_stream=(gid,), mean_degree=w.mean_degree,
-                      word_frac=w.word_frac, with_finals=with_finals)
+                      word_frac=w.word_frac, with_finals=with_finals, word_period=w.word_period)
 
 
 def make_loglikes(channels: int, frames: int, num_pdfs: int, sigma: float,
@@ -301,3 +321,58 @@ def make_contexts(w: Workload, g: Graph, segment: int = 0,
         arcs = arcs[rng.permutation(arcs.size)].astype(np.int32)
         lists.append(arcs)
     return lists, offs
+
+
+def word_sequences_on_walks(g: Graph, n_seq: int, words_per_seq: int, rng: np.random.Generator) -> List[List[int]]:
+    """Word sequences that occur in the graph: the output labels along random walks.
+
+    Each walk starts at a uniformly random state and follows uniformly random out-arcs until it has crossed
+    ``words_per_seq`` word arcs (or 64 x that many arcs); the words it crossed, in order, are one sequence.
+    This is input drawing only: which arcs a sequence selects is Algorithm 1's business.
+    """
+    row = g.row_offsets.astype(np.int64)
+    cur = rng.integers(0, g.num_states, n_seq, dtype=np.int64)
+    seqs: List[List[int]] = [[] for _ in range(n_seq)]
+    need = np.full(n_seq, words_per_seq, dtype=np.int64)
+    for _ in range(words_per_seq * 64):
+        live = np.nonzero(need > 0)[0]
+        if live.size == 0:
+            break
+        s = cur[live]
+        deg = row[s + 1] - row[s]
+        ok = deg > 0
+        pick = row[s] + np.floor(rng.random(s.size) * np.maximum(deg, 1)).astype(np.int64)
+        pick = np.where(ok, np.minimum(pick, row[s + 1] - 1), 0)
+        word = np.where(ok, g.olabel[pick], 0)
+        for i in np.nonzero(word != 0)[0]:
+            seqs[int(live[i])].append(int(word[i]))
+        need[live] -= (word != 0).astype(np.int64)
+        cur[live] = np.where(ok, g.dst[pick].astype(np.int64), rng.integers(0, g.num_states, s.size))
+    return [q for q in seqs if q]
+
+
+def make_context_sequences(w: Workload, g: Graph, segment: int = 0,
+                           channels: Optional[int] = None) -> Tuple[List[List[List[int]]], np.ndarray]:
+    """Per-channel biasing lists as WORD SEQUENCES (the form a user supplies, Sec. 4.1) and offsets.
+
+    A channel's list holds sequences of 1 to 3 words; their number is drawn so that the arc lists Algorithm 1 makes
+    of them come out near the workload's context sizes (a word labels about word arcs / vocabulary arcs, and every
+    arc of a sequence's first word is selected).  Offsets are drawn as in make_contexts.
+    """
+    C = w.channels if channels is None else channels
+    per_word = max(1.0, float(np.count_nonzero(g.olabel)) / max(1, g.num_words))
+    out: List[List[List[int]]] = []
+    offs = np.zeros(C, dtype=np.float32)
+    for c in range(C):
+        rng = _rng(6, w.config_id, c, segment)
+        k = int(rng.integers(w.ctx_min, w.ctx_max + 1))
+        if w.offset_lo == w.offset_hi:
+            offs[c] = np.float32(w.offset_lo)
+        else:
+            offs[c] = np.float32(rng.uniform(w.offset_lo, w.offset_hi))
+        n_seq = max(1, int(round(k / (per_word + 2.0))))
+        seqs: List[List[int]] = []
+        for n_words in (3, 2, 1):
+            seqs += word_sequences_on_walks(g, (n_seq + n_words - 1) // 3, n_words, rng)
+        out.append(seqs)
+    return out, offs

@@ -17,6 +17,7 @@ from paper_2306_15685_amd import binding as B
 import gpu_harness as GH
 import helpers as H
 from oracle import OracleGraph, OracleChannel
+from oracle import word_arcs as oracle_word_arcs
 
 pytestmark = pytest.mark.gpu
 
@@ -50,9 +51,29 @@ def check_workload(torch, w, g, og, prop_channels, graph_handle=None):
     inp = runner.make_inputs(w, g)
     sess = runner.Session(inp, graph_handle=graph_handle)
     try:
+        n_seg = w.segments
+        if inp.sequences is not None:
+            # the lists were made by the library from word sequences (Algorithm 1): the checker's own Algorithm 1
+            # must select the same arcs for every channel, and its lists are the ones its decoding then uses
+            checked = []
+            with ThreadPoolExecutor(max_workers=oracle_workers()) as ex:
+                for s in range(n_seg):
+                    per_channel, offs = inp.sequences[s]
+                    want = list(ex.map(lambda seqs: oracle_word_arcs.arcs_for_sequences(g, seqs), per_channel))
+                    got, offs2 = inp.contexts[s]
+                    assert np.array_equal(offs, offs2)
+                    for c in range(w.channels):
+                        assert np.array_equal(np.sort(got[c]), want[c]), f"{w.name} seg {s} ch {c}: Algorithm 1 arcs"
+                    checked.append((want, offs))
+            sizes = [x.size for want, _ in checked for x in want]
+            print(f"{w.name}: {len(sizes)} arc lists from word sequences equal to the checker's "
+                  f"({min(sizes)}-{max(sizes)} arcs)", flush=True)
+            assert min(sizes) > 0 and any(len(q) > 1 for seqs in inp.sequences[0][0] for q in seqs)
+            oracle_contexts = checked
+        else:
+            oracle_contexts = inp.contexts
         finals = sess.step(keep_results=True, collect_stats=False)
         partials = {(ss, tt): r for (ss, tt, r) in sess.partials}
-        n_seg = w.segments
         assert len(finals) == n_seg
         tls = threading.local()
         last_counters = {}
@@ -81,7 +102,7 @@ def check_workload(torch, w, g, og, prop_channels, graph_handle=None):
 
         with ThreadPoolExecutor(max_workers=oracle_workers()) as ex:
             for s in range(n_seg):
-                lists, offs = inp.contexts[s]
+                lists, offs = oracle_contexts[s]
                 Lh = inp.loglikes[s].cpu().numpy()
                 done = list(ex.map(lambda c: one_channel(s, c, Lh, lists, offs), range(w.channels)))
                 assert len(done) == w.channels
@@ -124,6 +145,18 @@ def test_e2e_units_lexicon_loop(torch_cuda):
     og = OracleGraph.from_graph(g)
     total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 8))
     assert total["max_tokens"] > 2500   # far denser token activity than the HCLG-style workloads
+
+
+@pytest.mark.timeout(600)
+def test_word_sequence_contexts(torch_cuda):
+    """Sec. 4.1 end to end: every channel's biasing list is given as word sequences, the library's Algorithm 1
+    turns them into arc lists (checked against the checker's Algorithm 1, list by list), and the decoding with
+    them is checked on every channel.  The graph keeps word labels four arcs apart (see synth.make_graph)."""
+    w = synth.WORKLOADS["words"]
+    g = synth.graph_for(w)
+    og = OracleGraph.from_graph(g)
+    total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 16))
+    assert total["frames"] == w.channels * w.frames
 
 
 @pytest.mark.timeout(900)

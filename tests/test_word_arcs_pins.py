@@ -99,3 +99,33 @@ def test_cycle_of_unlabelled_arcs_terminates():
                     np.ones(4, np.int32), np.array([1, 0, 0, 2], np.int32), np.ones(4, np.float32))
     assert arcs_for_sequence(g, [1, 2]) == {0, 3}
     assert arcs_for_sequence(g, [2, 1]) == {3}
+
+
+def test_spaced_word_labels_keep_the_search_local():
+    """The graph of the word-sequence workload: every arc advances the position inside a word, exactly the arcs
+    that close a word carry a label, epsilon arcs still lead upwards.  A sequence read off a walk then selects,
+    beyond its first word's arcs (all of them: the sequence may start anywhere), at least one arc per later word,
+    and each of those leaves a state within word_period arcs of an arc of the word before."""
+    p = 4
+    g = synth.make_graph(4000, 50, 300, 0.10, seed_stream=(77,), word_period=p)
+    src, dst = g.src.astype(np.int64), g.dst.astype(np.int64)
+    assert ((dst % p) == ((src + 1) % p)).all()
+    assert ((g.olabel != 0) == (dst % p == 0)).all()
+    eps = g.ilabel == 0
+    assert eps.any() and (dst[eps] > src[eps]).all()
+    rng = np.random.default_rng(5)
+    seqs = [q for q in synth.word_sequences_on_walks(g, 40, 3, rng) if len(q) == 3]
+    assert len(seqs) > 20
+    for q in seqs:
+        arcs = arcs_for_sequence(g, q)
+        by_word = {w: [a for a in arcs if g.olabel[a] == w] for w in set(q)}
+        assert set(int(a) for a in np.nonzero(g.olabel == q[0])[0]) <= arcs
+        assert all(by_word[w] for w in q)          # the walk itself is a witness for every word
+        assert all(g.olabel[a] in q for a in arcs)
+
+
+def test_word_period_off_leaves_the_graphs_as_they_were():
+    """(the other workloads' graphs are pinned by stored results: the option must not touch their random draws)"""
+    a = synth.make_graph(3000, 40, 200, 0.15, seed_stream=(3,))
+    b = synth.make_graph(3000, 40, 200, 0.15, seed_stream=(3,), word_period=0)
+    assert np.array_equal(a.dst, b.dst) and np.array_equal(a.olabel, b.olabel) and np.array_equal(a.weight, b.weight)
