@@ -29,7 +29,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # default configuration of the workloads that were profiled, each with the kernel's average launch time in the
 # profiled build: a run whose own launch time is more than 5 % away from it is another kernel (or another machine
 # state) and reports no traffic instead of a stale one.
-MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch when measured)
+MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py reported in the profiled runs)
+    "large": (1291272553, 0.7254),
+    "stress": (15295533675, 5.8986),
+    "dynamic": (4858763561, 2.0645),
+    "medium": (440529209, 2.3278),
+    "words": (533112078, 0.5587),
+    "e2e": (32006914194, 18.8498),
 }
 TRAFFIC_TOLERANCE = 0.05
 
@@ -83,6 +89,37 @@ def cpu_baseline(inp, n_channels, budget_frames):
             "single_core_value": frames * 0.030 / dt1}
 
 
+def phase_report(B, sess, w):
+    """Diagnostic build only: where thread 0 of each workgroup spent the lean frames of the last pass (sums kept per
+    channel by the kernel, 100 MHz counter), per lean frame, averaged over the channels."""
+    import ctypes as C
+    L = B.lib()
+    L.cbd_debug_profile.restype = C.c_int32
+    L.cbd_debug_profile.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    v = np.zeros((w.channels, 15), np.int64)
+    for c in range(w.channels):
+        assert L.cbd_debug_profile(sess.dh, c, v[c].ctypes.data_as(C.c_void_p)) == 0
+    lean, frames = float(max(v[:, 10].sum(), 1)), float(max(v[:, 11].sum(), 1))
+    us = lambda k: float(v[:, k].sum()) * 0.01 / lean
+    launches = (w.frames + w.chunk - 1) // w.chunk
+    run = v[:, 9] * 0.01 / launches
+    return {"unit": "us per lean frame (thread 0 of the workgroup)", "lean_frames": int(lean), "frames": int(frames),
+            "frames_sent_back_to_general_code": int(v[:, 8].sum()),
+            "sent_back_because": {"closure_stage_over_64_records": int(((v[:, 14] >> 0) & 0xFFFF).sum()),
+                                  "commit_log_full": int(((v[:, 14] >> 16) & 0xFFFF).sum()),
+                                  "too_many_tokens": int(((v[:, 14] >> 32) & 0xFFFF).sum()),
+                                  "other": int(((v[:, 14] >> 48) & 0xFFFF).sum()),
+                                  "note": "events, several can fall into one frame"},
+            "us_per_frame_sent_back_second_run": float(v[:, 7].sum()) * 0.01 / max(float(v[:, 8].sum()), 1.0),
+            "sent_back_per_channel_max": int(v[:, 8].max()),
+            "emit": us(0), "wait_barrier_1": us(1), "commit": us(6) + us(12) + us(13) + us(2),
+            "commit_parts": {"slots_and_closure_reads": us(6), "emitting_min_and_log": us(12), "closure_levels_and_commit": us(13),
+                             "next_row_and_rest": us(2)},
+            "wait_barrier_2": us(3), "lookup_and_token_writes": us(4), "close_and_wait_barrier_3": us(5),
+            "workgroup_us_per_launch": {"mean": float(run.mean()), "median": float(np.median(run)),
+                                        "p90": float(np.percentile(run, 90)), "max": float(run.max())}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +147,9 @@ def main():
                     help="partial results with the blocking call instead of begin/finish requests")
     ap.add_argument("--context-mode", default="upload", choices=["upload", "pool"],
                     help="upload every segment's lists, or pre-load all of them and switch by id")
+    ap.add_argument("--phases", action="store_true",
+                    help="run the diagnostic build (python paper_2306_15685_amd/build.py --profile) and report the time "
+                         "thread 0 of each workgroup spent in each phase of the lean frames (the stamps cost a few %%)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-channels", type=int, default=256, help="channels of the workload the CPU checker is timed on")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="BYTES",
@@ -124,6 +164,12 @@ def main():
     from paper_2306_15685_amd import synth, runner
     from paper_2306_15685_amd import binding as B
 
+    if args.phases:
+        from paper_2306_15685_amd import build as _build
+        if not os.path.exists(_build.LIB_PROFILE):
+            log(f"bench.py: {_build.LIB_PROFILE} is missing: python paper_2306_15685_amd/build.py --profile")
+            sys.exit(2)
+        B.LIB_PATH = _build.LIB_PROFILE
     torch.cuda.set_device(0)
     if args.calibrate_copy:
         n = args.calibrate_copy // 4
@@ -231,6 +277,8 @@ def main():
                      "kernel_time_share": sum(kms) / (wall * 1e3)},
     }
     out["config"]["device_bytes"] = B.cbd_decoder_info(sess.dh)["device_bytes"]   # (buffers allocated on first use included)
+    if args.phases:
+        out["phases"] = phase_report(B, sess, w)
     if inp.context_build is not None:   # Algorithm 1 on the host, outside the timed region (lists arrive rarely)
         out["context_build"] = inp.context_build
     if not args.no_cpu_baseline:

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "cbd.hip")
 DEPS = [SRC, os.path.join(HERE, "csrc", "cbd_device.hpp"), os.path.join(HERE, "csrc", "cbd_lean.hpp"), os.path.join(HERE, "..", "include", "cbd.h")]
 LIB = os.path.join(HERE, "libcbdec.so")
+LIB_PROFILE = os.path.join(HERE, "libcbdec_prof.so")   # diagnostic build: phase stamps in the lean frame code
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
@@ -20,17 +21,20 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile libcbdec.so.  With force=False only when a source is newer than the library."""
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
-        return LIB
+def build(force: bool = True, verbose: bool = False, profile: bool = False) -> str:
+    """Compile libcbdec.so.  With force=False only when a source is newer than the library.
+    profile=True builds libcbdec_prof.so instead: the same code with -DCBD_PROFILE, in which thread 0 of every
+    workgroup stamps the phases of the lean frames (bench.py --phases reads the sums); not the product build."""
+    lib = LIB_PROFILE if profile else LIB
+    if not force and os.path.exists(lib) and all(os.path.getmtime(lib) >= os.path.getmtime(d) for d in DEPS):
+        return lib
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB + ".tmp", SRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *(["-DCBD_PROFILE"] if profile else []), "-o", lib + ".tmp", SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    os.replace(LIB + ".tmp", LIB)
-    return LIB
+    os.replace(lib + ".tmp", lib)
+    return lib
 
 
 def resource_usage() -> dict:
@@ -59,4 +63,4 @@ def resource_usage() -> dict:
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    print(build(force=True, verbose=True, profile="--profile" in sys.argv[1:]))

@@ -195,6 +195,8 @@ struct Shared {
   long long prof[12];
   long long prof_last;
   int32_t prof_redo;
+  int32_t prof_why[8];   // why lean frames went back to the general code (see CBD_WHY)
+  long long prof_general;   // time in those frames' second run
 #endif
   unsigned long long a_frames, a_active, a_emit, a_eps, a_cand, a_impr, a_tokens, a_rounds;
 };
@@ -1326,7 +1328,11 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   if (tid < 64) frame_init(sh, hist, p.do_reset != 0, tid);
   if (tid == 0) { sh->a_lean = 0; sh->a_lean_pack[0] = 0; sh->a_lean_pack[1] = 0; }
 #ifdef CBD_PROFILE
-  if (tid == 0) { for (int k = 0; k < 12; ++k) sh->prof[k] = 0; sh->prof_redo = 0; }
+  if (tid == 0) {
+    for (int k = 0; k < 12; ++k) sh->prof[k] = 0;
+    for (int k = 0; k < 8; ++k) sh->prof_why[k] = 0;
+    sh->prof_redo = 0; sh->prof_general = 0;
+  }
   const long long prof_k0 = wall_clock64();
 #endif
   __syncthreads();
@@ -1347,7 +1353,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
                                          g_tok_state, last);
         if (outcome == kFrameRedo) {
 #ifdef CBD_PROFILE
-          if (tid == 0) sh->prof_redo += 1;
+          if (tid == 0) { sh->prof_redo += 1; sh->prof_general -= wall_clock64(); }
 #endif
           // wipe the table, bring this frame's log-likelihood row back, hand the rows to the general code
           __syncthreads();
@@ -1363,6 +1369,9 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         if (rows_in_lds) { rows_to_device<kBlock>(ML, LM, sh->n_tok, cur); rows_in_lds = false; }
         outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
         if (outcome == kFrameOk) cur ^= 1;
+#ifdef CBD_PROFILE
+        if (lean && tid == 0) sh->prof_general += wall_clock64();
+#endif
       }
       if (outcome == kFrameOverflow) {
         // redo the frame with the tables in device memory: wipe the LDS table, hand the costs over
@@ -1427,6 +1436,12 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
     for (int k = 0; k < 7; ++k) cs->spare[k] += sh->prof[k];
     cs->spare[12] += sh->prof[7]; cs->spare[13] += sh->prof[8];
     cs->spare[8] += sh->prof_redo;
+    cs->spare[7] += sh->prof_general;
+    {
+      long long packed = 0;   // eight 8-bit counts (saturating) would be too small: four 16-bit counts per word
+      for (int k = 0; k < 4; ++k) packed |= (long long)(sh->prof_why[k] & 0x7FFF) << (16 * k);
+      cs->spare[14] += packed;
+    }
     cs->spare[9] += wall_clock64() - prof_k0;   // the workgroup's whole run
     cs->spare[10] += sh->a_lean;
     cs->spare[11] += (long long)sh->a_frames;

@@ -31,8 +31,11 @@ namespace cbd {
   do {                                                                                                   \
     if (threadIdx.x == 0) { const long long t_ = wall_clock64(); sh->prof[k] += t_ - sh->prof_last; sh->prof_last = t_; } \
   } while (0)
+// why a lean frame is given back: 0 closure stage over 64 records, 1 commit log full, 2 too many tokens, 3 other
+#define CBD_WHY(k) atomicAdd(&sh->prof_why[k], 1)
 #else
 #define CBD_STAMP(k) do {} while (0)
+#define CBD_WHY(k) do {} while (0)
 #endif
 
 constexpr uint16_t kLeanDegEscape = 0xFFFF;   // t_deg: the row is too long for the lean code
@@ -121,11 +124,11 @@ __device__ __forceinline__ LeanTile lean_load_tile(const AdvanceParams &p, const
     }
     if (alive) { first = R.t_first[i]; deg = (int)R.t_deg[i]; }
   }
-  if (deg == (int)kLeanDegEscape) { sh->redo = 1; deg = 0; }
+  if (deg == (int)kLeanDegEscape) { sh->redo = 1; deg = 0; CBD_WHY(3); }
   const int incl = wave_incl_scan(deg);
   const int pos = incl - deg;
   T.total = __builtin_amdgcn_readlane(incl, 63);
-  if (T.total > kOwnerMap) { if (lane == 0) sh->redo = 1; T.total = 0; }
+  if (T.total > kOwnerMap) { if (lane == 0) { sh->redo = 1; CBD_WHY(3); } T.total = 0; }
   ((uint32_t *)omap)[lane] = 0;
   if (deg > 0 && pos < kOwnerMap) omap[pos] = (uint8_t)(lane + 1);
   T.rel = first - pos;
@@ -236,7 +239,7 @@ __device__ __forceinline__ void lean_slot_collisions(const Mem<true> &M, Shared 
                                                      uint32_t &h, uint32_t &k) {
   const bool collided = ok && k != kEmptyKey && k != state;
   if (__ballot(collided) != 0) {   // rare
-    if (collided && !lean_probe(M, state, h, k)) { sh->redo_b = 1; ok = false; }
+    if (collided && !lean_probe(M, state, h, k)) { sh->redo_b = 1; ok = false; CBD_WHY(3); }
   }
 }
 
@@ -256,7 +259,7 @@ __device__ __forceinline__ bool lean_min_and_log(const Mem<true> &M, const LeanM
     // files the state's row, which the next frame expands
     const int ord = W.n_claimed + __popcll(cm & below);
     if (ord <= kLeanLidMask) M.hidx[h] = (uint16_t)((wave << kLeanLidBits) | ord);
-    else sh->redo_b = 1;
+    else { sh->redo_b = 1; CBD_WHY(3); }
     const uint32_t ed = meta_ed(rec.meta);
     R.hrow[h] = rec.row;
     R.hed[h] = ed == kEdEscape ? kLeanEdEscape : (uint8_t)ed;
@@ -269,6 +272,7 @@ __device__ __forceinline__ bool lean_min_and_log(const Mem<true> &M, const LeanM
       (R.clog + (size_t)wave * R.clog_per_wave)[e] = le;
     } else {
       sh->redo_b = 1;
+      CBD_WHY(1);
     }
   }
   W.n_claimed += __popcll(cm);
@@ -299,7 +303,7 @@ __device__ __forceinline__ LeanClosure lean_closure_begin(const AdvanceParams &p
   C.total = __builtin_amdgcn_readlane(incl, 63);
   if (C.total == 0) return C;   // uniform
   if (C.total > 64) {           // (rare: the general code takes the frame)
-    if (lane == 0) sh->redo_b = 1;
+    if (lane == 0) { sh->redo_b = 1; CBD_WHY(0); }
     C.total = 0;
     return C;
   }
@@ -395,6 +399,7 @@ __device__ __forceinline__ void lean_commit(const AdvanceParams &p, const Mem<tr
     if (pass[q] && cl > 0) {
       if (cl == kClEscape) {
         sh->redo_b = 1;   // no stored list: the general code follows this closure
+        CBD_WHY(3);
       } else {
         pos[q] = E.rec[q].row + (int)meta_ed(E.rec[q].meta) + (int)meta_xd(E.rec[q].meta);
         len[q] = (int)cl;
@@ -505,7 +510,10 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
     n_claim = __builtin_amdgcn_readlane(inc, 63);
     if (lane < NW) sh->wbase[lane] = inc - c;
   }
-  if (n_claim > M.tok_cap) return kFrameRedo;   // (the general code decides what an overflow means)
+  if (n_claim > M.tok_cap) {   // (the general code decides what an overflow means)
+    if (tid == 0) CBD_WHY(2);
+    return kFrameRedo;
+  }
   if (sh->n_rec + n_claim > p.bp_cap) return kFrameRecordsFull;
   const bool hist_need = hist_on && n_claim > p.max_active;
   const float fbest = ord2f(umin32(m_ord, sh->best_ord));
