@@ -108,7 +108,10 @@ typedef struct cbd_config {
   int32_t lookup_mode;        /* 0 sorted list + binary search (Sec. 4.2); 1 hashed bitmap filter, then the search */
   int32_t hash_capacity_log2; /* device-memory state table slots per channel = 2^this; a frame may hold at most
                                  half as many tokens (frames that fit the LDS tables never touch this table) */
-  int32_t max_eps_iters;      /* epsilon-closure round limit; 0 = default 64 */
+  int32_t max_eps_iters;      /* epsilon-closure limit; 0 = default 64.  Counted in levels of a chain of improving
+                                 epsilon-input arcs (and in rounds over the change log): a closure that needs more,
+                                 a legitimate acyclic chain that long included, parks the channel with
+                                 CBD_E_EPS_DIVERGED; raise the limit for graphs with longer epsilon chains */
   int32_t records_per_frame;  /* average back-pointer records per frame to reserve; 0 = table capacity / 2 */
   int32_t table_location;     /* 0 or 1 = LDS tables, frames that outgrow them are redone in device memory;
                                  2 = device-memory tables only */
