@@ -140,6 +140,8 @@ def main():
     ap.add_argument("--lds-token-cap", type=int, default=0)
     ap.add_argument("--workgroups-per-cu", type=int, default=0)
     ap.add_argument("--block-threads", type=int, default=0)
+    ap.add_argument("--workgroups-per-channel", type=int, default=-1,
+                    help="team of workgroups per channel (2, 4, 8); default: the workload's (e2e: 4, others: 1)")
     ap.add_argument("--frame-code", type=int, default=0, help="0: lean frame code where it applies; 1: general code only")
     ap.add_argument("--lookup-mode", type=int, default=-1, help="0 binary search, 1 Bloom filter + search; default: the workload's")
     ap.add_argument("--unbiased", action="store_true", help="decode with empty contexts (switch-overhead comparison)")
@@ -189,6 +191,7 @@ def main():
         w = synth.scaled(w, frames=args.frames)
     if args.chunk:
         w = synth.scaled(w, chunk=args.chunk)
+    team = args.workgroups_per_channel if args.workgroups_per_channel >= 0 else runner.default_team(w)
     t0 = time.perf_counter()
     inp = runner.make_inputs(w)
     torch.cuda.synchronize()
@@ -198,7 +201,8 @@ def main():
                           biased=not args.unbiased, lds_token_cap=args.lds_token_cap, context_mode=args.context_mode,
                           async_partials=not args.sync_partials, workgroups_per_cu=args.workgroups_per_cu,
                           compact_records_above=args.compact_records_above, record_frames=args.record_frames,
-                          tail_partials=args.tail_partials, block_threads=args.block_threads, frame_code=args.frame_code)
+                          tail_partials=args.tail_partials, block_threads=args.block_threads, frame_code=args.frame_code,
+                          workgroups_per_channel=team)
     info = B.cbd_decoder_info(sess.dh)
     log(f"decoder: {info}")
 
@@ -239,7 +243,7 @@ def main():
     achieved = alg_bytes_step / launches_per_step / (avg_launch_ms * 1e-3) / 1e9
 
     default_cfg = (not args.unbiased and args.context_mode == "upload" and not args.channels and not args.hash_log2
-                   and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu and not args.block_threads and not args.frame_code
+                   and not args.table_location and not args.lds_token_cap and not args.workgroups_per_cu and not args.block_threads and not args.frame_code and args.workgroups_per_channel < 0
                    and args.lookup_mode < 0 and not args.sync_partials and not args.frames and not args.chunk
                    and not args.compact_records_above and not args.record_frames and not args.tail_partials)
     traffic, traffic_at_ms = None, None
@@ -262,7 +266,7 @@ def main():
                    "beam": w.beam, "max_active": w.max_active, "biased": not args.unbiased,
                    "context_mode": args.context_mode, "async_partials": not args.sync_partials,
                    "lookup_mode": w.lookup_mode, "lds_token_cap": info["lds_token_cap"],
-                   "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"],
+                   "lds_bytes": info["lds_bytes"], "block_threads": info["block_threads"], "workgroups_per_channel": max(team, 1),
                    "compact_records_above": args.compact_records_above, "tail_partials": args.tail_partials, "device_bytes": info["device_bytes"]},
         "arcs_per_s": arcs / (wall / args.steps),
         "frames_per_s": w.channels * w.segments * w.frames / (wall / args.steps),

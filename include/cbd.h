@@ -131,6 +131,14 @@ typedef struct cbd_config {
   int32_t frame_code;         /* 0 = frames that qualify (tables in LDS, at most one token per thread, stored closure
                                  lists) are decoded by the lean frame code, the rest by the general code; 1 = general
                                  code only.  Results are the same either way. */
+  int32_t workgroups_per_channel; /* 0 or 1 = one workgroup decodes a channel; 2, 4 or 8 = a team of that many
+                                 shares it (for frames with far more tokens than one compute unit's LDS holds: the
+                                 states are split over the team, candidates travel between members through device
+                                 memory).  Needs num_channels x team <= compute units of the device, a graph whose
+                                 epsilon closures are all stored as lists (at most 15 levels and 62 arcs each), and
+                                 compact_records_above = 0; each member can hold about 7,000 tokens per frame
+                                 (CBD_E_CAPACITY beyond).  Results are the same; token and record numbers differ
+                                 (cbd_get_tokens / cbd_get_records then show unused places at infinite cost) */
 } cbd_config;
 
 /*

@@ -41,7 +41,7 @@ class cbd_config(C.Structure):
                 ("records_per_frame", C.c_int32), ("table_location", C.c_int32), ("lds_token_cap", C.c_int32),
                 ("max_pool_contexts", C.c_int32), ("workgroups_per_cu", C.c_int32),
                 ("compact_records_above", C.c_int32), ("block_threads", C.c_int32),
-                ("frame_code", C.c_int32)]
+                ("frame_code", C.c_int32), ("workgroups_per_channel", C.c_int32)]
 
 
 class cbd_stats(C.Structure):
@@ -190,11 +190,11 @@ def cbd_context_from_words(g, sequences) -> np.ndarray:
 def cbd_decoder_create(g, num_channels, beam, max_active, max_frames, max_context_arcs, lookup_mode=0,
                        hash_capacity_log2=14, max_eps_iters=0, records_per_frame=0, table_location=0,
                        lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, compact_records_above=0,
-                       block_threads=0, frame_code=0, hip_stream=0):
+                       block_threads=0, frame_code=0, workgroups_per_channel=0, hip_stream=0):
     cfg = cbd_config(int(num_channels), float(beam), int(max_active), int(max_frames), int(max_context_arcs),
                      int(lookup_mode), int(hash_capacity_log2), int(max_eps_iters), int(records_per_frame),
                      int(table_location), int(lds_token_cap), int(max_pool_contexts), int(workgroups_per_cu),
-                     int(compact_records_above), int(block_threads), int(frame_code))
+                     int(compact_records_above), int(block_threads), int(frame_code), int(workgroups_per_channel))
     h = C.c_void_p()
     _check(lib().cbd_decoder_create(g, C.byref(cfg), C.c_void_p(int(hip_stream)), C.byref(h)), "cbd_decoder_create")
     return h

@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "cbd.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "cbd_device.hpp"), os.path.join(HERE, "csrc", "cbd_lean.hpp"), os.path.join(HERE, "..", "include", "cbd.h")]
+DEPS = [SRC, os.path.join(HERE, "csrc", "cbd_device.hpp"), os.path.join(HERE, "csrc", "cbd_lean.hpp"), os.path.join(HERE, "csrc", "cbd_team.hpp"), os.path.join(HERE, "..", "include", "cbd.h")]
 LIB = os.path.join(HERE, "libcbdec.so")
 LIB_PROFILE = os.path.join(HERE, "libcbdec_prof.so")   # diagnostic build: phase stamps in the lean frame code
 

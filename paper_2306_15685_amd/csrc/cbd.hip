@@ -136,6 +136,7 @@ struct cbd_graph {
   std::vector<int32_t> visit;       // [S] search stamps
   int32_t visit_stamp = 0;
   int32_t max_word = 0;
+  int32_t unstored_closures = 0;    // states whose epsilon closure is not stored as a list (too deep or too long)
   size_t bytes = 0;
 };
 
@@ -202,6 +203,14 @@ struct cbd_decoder {
   int32_t *d_ids_kept = nullptr;
   std::vector<int32_t> kept_ids, last_ids;
   StageRing ctxs;  // context uploads
+  // teams (workgroups_per_channel > 1)
+  int team_k = 0, team_slots = 0, team_part_cap = 0, team_q_cap = 0, team_stage_rows = 0;
+  uint32_t team_lds = 0;
+  cbd::TeamChan *d_team = nullptr;
+  cbd::TeamEntry *d_team_q1 = nullptr, *d_team_q2 = nullptr;
+  cbd::TeamClosureWin *d_team_cwin = nullptr;
+  uint32_t *d_team_pub_key = nullptr;
+  uint16_t *d_team_pub_lid = nullptr;
   std::vector<int32_t> h_tmp;
   std::vector<int32_t> h_static_meta;   // result headers of cbd_best_paths_static on their way to the caller
   size_t bytes = 0;
@@ -226,6 +235,20 @@ hipError_t set_attr(int block, uint32_t lds) {
   if (block == 512) return set_attr_t<512>(lds);
   if (block == 960) return set_attr_t<960>(lds);
   return set_attr_t<1024>(lds);
+}
+
+// A team launch: all members of all teams have to be resident together, so the launch is a cooperative one (the
+// runtime refuses it if they would not fit).
+hipError_t launch_team(const cbd_decoder *d, const AdvanceParams &p, int n_channels) {
+  cbd::TeamParams tp{};
+  tp.a = p;
+  tp.team = d->d_team; tp.q1 = d->d_team_q1; tp.q2 = d->d_team_q2; tp.cwin = d->d_team_cwin;
+  tp.pub_key = d->d_team_pub_key; tp.pub_lid = d->d_team_pub_lid;
+  tp.k = d->team_k; tp.q_cap = d->team_q_cap; tp.part_cap = d->team_part_cap; tp.slots = d->team_slots;
+  tp.stage_rows = d->team_stage_rows; tp.ctx_lds_cap = d->ctx_lds_cap;
+  void *args[] = {(void *)&tp};
+  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&cbd::advance_team_kernel),
+                                    dim3((unsigned)(n_channels * d->team_k)), dim3(1024), args, d->team_lds, d->stream);
 }
 
 hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {
@@ -483,6 +506,7 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) try {
     const bool ok = n_emit[(size_t)s] < (int32_t)cbd::kEdEscape && n_eps[(size_t)s] < (int32_t)cbd::kXdEscape &&
                     walk_closure(s, [&](int32_t, int32_t, int32_t) { ++cnt; });
     n_clo[(size_t)s] = ok ? cnt : kNoList;
+    if (!ok) g->unstored_closures += 1;
   }
   std::vector<int4> off2((size_t)S);
   int64_t total = 0;
@@ -705,6 +729,15 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   if (cfg->workgroups_per_cu < 0 || cfg->workgroups_per_cu > 4) return fail(CBD_E_INVALID, "decoder: workgroups_per_cu");
   if (cfg->compact_records_above < 0) return fail(CBD_E_INVALID, "decoder: compact_records_above");
   if (cfg->frame_code < 0 || cfg->frame_code > 1) return fail(CBD_E_INVALID, "decoder: frame_code");
+  {
+    const int k = cfg->workgroups_per_channel;
+    if (k != 0 && k != 1 && k != 2 && k != 4 && k != 8)
+      return fail(CBD_E_INVALID, "decoder: workgroups_per_channel must be 0, 1, 2, 4 or 8");
+    if (k > 1 && cfg->compact_records_above > 0)
+      return fail(CBD_E_INVALID, "decoder: record compaction is not available with workgroups_per_channel > 1");
+    if (k > 1 && g->unstored_closures > 0)
+      return fail(CBD_E_INVALID, "decoder: workgroups_per_channel > 1 needs every epsilon closure of the graph stored as a list");
+  }
   if (cfg->block_threads != 0 && cfg->block_threads != 256 && cfg->block_threads != 512 && cfg->block_threads != 960 &&
       cfg->block_threads != 1024)
     return fail(CBD_E_INVALID, "decoder: block_threads must be 0, 256, 512, 960 or 1024");
@@ -794,6 +827,34 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     }
   }
   DCHK(set_attr(d->block, d->lds_bytes));
+  if (cfg->workgroups_per_channel > 1) {
+    const int k = cfg->workgroups_per_channel;
+    int n_cu = 0;
+    DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
+    if ((int64_t)d->C * k > n_cu)
+      return fail(CBD_E_INVALID, "decoder: num_channels x workgroups_per_channel exceeds the device's compute units");
+    d->team_k = k;
+    // each member's table takes the LDS that the row, the context list and the small arrays leave
+    d->team_stage_rows = g->P <= 4096 ? 1 : 0;
+    const cbd::TeamLayout fixed = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, 0);
+    int slots = (int)(((int64_t)lds_limit - 1024 - (int64_t)fixed.total - 64) / 14) / 64 * 64;
+    slots = std::min(slots, 0xFFFF / 2 * 3 / 64 * 64);
+    if (slots < 1024) return fail(CBD_E_INVALID, "decoder: no room for a team member's table in LDS");
+    d->team_slots = slots;
+    d->team_part_cap = slots * 2 / 3 / 64 * 64;
+    if ((int64_t)d->team_part_cap * k > d->g_tok_cap)
+      d->team_part_cap = d->g_tok_cap / k / 64 * 64;   // (the token arrays are sized by hash_capacity_log2)
+    if (d->team_part_cap < 64) return fail(CBD_E_INVALID, "decoder: hash_capacity_log2 too small for a team");
+    // (a sender's queue to one owner: in the frame after a reset one member expands a long start row by itself)
+    d->team_q_cap = d->team_part_cap + d->team_part_cap / 4;
+    d->team_lds = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, slots).total;
+    DCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_team_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)d->team_lds));
+    // a frame's records: one block of k shares
+    const int64_t bp_team = (int64_t)k * d->team_part_cap * ((int64_t)cfg->max_frames + 1) + d->g_tok_cap;
+    if (bp_team > 0x7FFFFFF0) return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel");
+    d->bp_cap = std::max(d->bp_cap, (int32_t)bp_team);
+  }
 
   const size_t C = (size_t)d->C;
   DCHK(dmalloc(&d->d_chan, C, &d->bytes));
@@ -806,6 +867,16 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   d->pool = cfg->max_pool_contexts;
   d->pool_used.assign((size_t)d->pool, 0);
   DCHK(dmalloc(&d->d_ctx, (C + d->pool) * (size_t)d->max_ctx, &d->bytes));
+  if (d->team_k > 1) {
+    const size_t k = (size_t)d->team_k;
+    DCHK(dmalloc(&d->d_team, C, &d->bytes));
+    DCHK(hipMemsetAsync(d->d_team, 0, sizeof(cbd::TeamChan) * C, d->stream));
+    DCHK(dmalloc(&d->d_team_q1, C * k * k * (size_t)d->team_q_cap, &d->bytes));
+    DCHK(dmalloc(&d->d_team_q2, C * k * k * (size_t)d->team_q_cap, &d->bytes));
+    DCHK(dmalloc(&d->d_team_cwin, C * k * (size_t)d->team_part_cap, &d->bytes));
+    DCHK(dmalloc(&d->d_team_pub_key, C * k * (size_t)d->team_slots, &d->bytes));
+    DCHK(dmalloc(&d->d_team_pub_lid, C * k * (size_t)d->team_slots, &d->bytes));
+  }
   DCHK(dmalloc(&d->d_ctx_n, C + d->pool, &d->bytes));
   DCHK(dmalloc(&d->d_ctx_off, C + d->pool, &d->bytes));
   DCHK(hipMemsetAsync(d->d_ctx_n, 0, sizeof(int32_t) * (C + d->pool), d->stream));
@@ -852,7 +923,8 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   if (d->side) (void)hipStreamSynchronize(d->side);   // its walks read the records and snapshots freed below
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
-                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words, d->d_due_max, d->d_ids_kept};
+                  d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words, d->d_due_max, d->d_ids_kept,
+                  d->d_team, d->d_team_q1, d->d_team_q2, d->d_team_cwin, d->d_team_pub_key, d->d_team_pub_lid};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->h_new) (void)hipHostFree(d->h_new);
@@ -893,6 +965,10 @@ int32_t cbd_reset_channels(cbd_decoder *d, const int32_t *channels, int32_t n) t
   rc = claim_snapshot_slot(d, channels, n, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n));
+  if (d->team_k > 1) {
+    hipLaunchKernelGGL(cbd::team_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, d->stream, d->d_team, dev, n);
+    HIPCHK(hipGetLastError());
+  }
   HIPCHK(d->ids.release(slot, d->stream));
   return CBD_OK;
 } catch (const std::bad_alloc &) {
@@ -1202,6 +1278,14 @@ int32_t cbd_advance(cbd_decoder *d, const int32_t *channels, int32_t n_channels,
   AdvanceParams p = base_params(d);
   p.chan_ids = dev; p.loglikes = loglikes; p.channel_stride = channel_stride; p.n_frames = n_frames; p.do_reset = 0;
   p.new_records = d->dv_new; p.call_seq = (int32_t)d->adv_calls; p.due_max = d->d_due_max;
+  if (d->team_k > 1) {
+    // (a team leaves no best-token snapshot behind: a request for partial results takes its own)
+    d->last_list.clear();
+    d->adv_calls++;
+    HIPCHK(launch_team(d, p, n_channels));
+    HIPCHK(d->ids.release(slot, d->stream));
+    return CBD_OK;
+  }
   rc = claim_snapshot_slot(d, channels, n_channels, &p);
   if (rc != CBD_OK) return rc;
   HIPCHK(launch_advance(d, p, n_channels));

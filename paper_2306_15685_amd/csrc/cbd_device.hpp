@@ -59,7 +59,8 @@ struct __attribute__((aligned(16))) ArcRec {
                    // bits 26..31 records in dst's closure list (all ones: the list is not stored, too deep or long)
 };
 constexpr uint32_t kEdEscape = 63, kXdEscape = 15, kClEscape = 63;
-constexpr int kClosureMaxDepth = 8;    // deeper closures are not flattened (the general closure code takes them)
+constexpr int kClosureMaxDepth = 15;   // deeper closures are not flattened (the general closure code takes them);
+                                       // the depth field of a closure record holds 4 bits
 __host__ __device__ inline uint32_t meta_ed(uint32_t m) { return (m >> 16) & 63u; }
 __host__ __device__ inline uint32_t meta_xd(uint32_t m) { return (m >> 22) & 15u; }
 __host__ __device__ inline uint32_t meta_cl(uint32_t m) { return m >> 26; }
@@ -2239,3 +2240,4 @@ __global__ __launch_bounds__(kCompactBlock) void compact_records_kernel(CompactP
 }
 
 }  // namespace cbd
+#include "cbd_team.hpp"

@@ -21,6 +21,11 @@ def default_hash_log2(w: synth.Workload) -> int:
     return 16 if w.name.startswith("e2e") else 14
 
 
+def default_team(w: synth.Workload) -> int:
+    """Workgroups per channel: the lexicon-loop workload's frames (20,000 tokens) are shared by teams of four."""
+    return 1   # (see bench.py --workgroups-per-channel)
+
+
 def default_records_per_frame(w: synth.Workload) -> int:
     return 24_576 if w.name.startswith("e2e") else DEFAULT_RECORDS_PER_FRAME
 
@@ -70,7 +75,7 @@ class Session:
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
                  context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0,
                  compact_records_above: int = 0, record_frames: int = 0, tail_partials: bool = False,
-                 block_threads: int = 0, frame_code: int = 0):
+                 block_threads: int = 0, frame_code: int = 0, workgroups_per_channel: int = 0):
         """compact_records_above / record_frames: automatic compaction of the back-pointer records, and the number
         of frames the record buffer is sized for (0: the whole utterance).  tail_partials: partial results through
         cbd_best_tails_begin / _finish (only the part of the path above what the compactions have fixed).
@@ -94,7 +99,7 @@ class Session:
             hash_log2 if hash_log2 is not None else default_hash_log2(w), 0,
             records_per_frame or default_records_per_frame(w), table_location, lds_token_cap,
             w.channels * w.segments if context_mode == "pool" else 0, workgroups_per_cu, compact_records_above,
-            block_threads, frame_code, hip_stream=self.stream.cuda_stream)
+            block_threads, frame_code, workgroups_per_channel, hip_stream=self.stream.cuda_stream)
         self.context_mode = context_mode
         self.async_partials = async_partials   # partial results through cbd_best_paths_begin / _finish
         self.begin_partial = B.cbd_best_tails_begin if tail_partials else B.cbd_best_paths_begin

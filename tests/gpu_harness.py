@@ -15,7 +15,8 @@ class GpuDecoder:
 
     def __init__(self, g, channels, beam, max_active=0, max_frames=512, max_context_arcs=1024, lookup_mode=0,
                  hash_log2=12, table_location=0, records_per_frame=0, max_eps_iters=0, graph_handle=None,
-                 lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, compact_records_above=0, block_threads=0, frame_code=0):
+                 lds_token_cap=0, max_pool_contexts=0, workgroups_per_cu=0, compact_records_above=0, block_threads=0, frame_code=0,
+                 workgroups_per_channel=0):
         import torch
         self.torch = torch
         self.g = g
@@ -26,6 +27,7 @@ class GpuDecoder:
         self.dh = B.cbd_decoder_create(self.gh, channels, beam, max_active, max_frames, max_context_arcs, lookup_mode,
                                        hash_log2, max_eps_iters, records_per_frame, table_location, lds_token_cap,
                                        max_pool_contexts, workgroups_per_cu, compact_records_above, block_threads, frame_code,
+                                       workgroups_per_channel,
                                        hip_stream=torch.cuda.current_stream().cuda_stream)
         self.all = np.arange(channels, dtype=np.int32)
 

@@ -44,12 +44,12 @@ def oracle_workers():
     return max(1, min(16, len(os.sched_getaffinity(0))))
 
 
-def check_workload(torch, w, g, og, prop_channels, graph_handle=None):
+def check_workload(torch, w, g, og, prop_channels, graph_handle=None, **session_kw):
     """Every channel of every segment against the checker: each chunk's partial result, the final result and (for
     the last segment) the counters.  The checker's channels run on a pool of host threads, one checker object per
     thread, reused from channel to channel (ctypes releases the interpreter lock during the calls)."""
     inp = runner.make_inputs(w, g)
-    sess = runner.Session(inp, graph_handle=graph_handle)
+    sess = runner.Session(inp, graph_handle=graph_handle, **session_kw)
     try:
         n_seg = w.segments
         if inp.sequences is not None:
@@ -138,12 +138,14 @@ def test_medium_all_channels(torch_cuda):
     check_workload(torch_cuda, w, g, og, prop_channels=range(w.channels))
 
 
-def test_e2e_units_lexicon_loop(torch_cuda):
-    """Second workload: 64 channels over a 20,000-word lexicon loop of end-to-end units."""
+@pytest.mark.parametrize("team", [1, 4])
+def test_e2e_units_lexicon_loop(torch_cuda, team):
+    """Second workload: 64 channels over a 20,000-word lexicon loop of end-to-end units, decoded by one workgroup
+    per channel (tables in device memory) and by teams of four (tables in the members' LDS)."""
     w = synth.WORKLOADS["e2e"]
     g = synth.graph_for(w)
     og = OracleGraph.from_graph(g)
-    total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 8))
+    total = check_workload(torch_cuda, w, g, og, prop_channels=range(0, w.channels, 8), workgroups_per_channel=team)
     assert total["max_tokens"] > 2500   # far denser token activity than the HCLG-style workloads
 
 
