@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py
     "dynamic": (4858763561, 2.0645),
     "medium": (440529209, 2.3278),
     "words": (533112078, 0.5587),
-    "e2e": (32006914194, 18.8498),
+    "e2e": (12648971504, 5.1849),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
 
@@ -276,7 +276,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_measured_at_launch_ms": traffic_at_ms,
                      "achieved_is": "a model: per-unit bytes x the decoder's counters / measured kernel time "
                                     "(counts table and candidate traffic that this design keeps in LDS)",
-                     "kernel": "advance_kernel", "launches_per_step": launches_per_step,
+                     "kernel": "advance_team_kernel" if team > 1 else "advance_kernel", "launches_per_step": launches_per_step,
                      "avg_launch_ms": avg_launch_ms, "algorithmic_bytes_per_launch": alg_bytes_step / launches_per_step,
                      "kernel_time_share": sum(kms) / (wall * 1e3)},
     }

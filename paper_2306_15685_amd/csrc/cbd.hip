@@ -237,18 +237,26 @@ hipError_t set_attr(int block, uint32_t lds) {
   return set_attr_t<1024>(lds);
 }
 
-// A team launch: all members of all teams have to be resident together, so the launch is a cooperative one (the
-// runtime refuses it if they would not fit).
+// A team launch.  The members of a team wait for one another inside the kernel, so all of a launch's workgroups
+// have to become resident without waiting for one another: the grid never exceeds the device's compute units
+// (checked when the decoder is made), a workgroup fills a compute unit's LDS, launches of one decoder follow one
+// another on its stream, and whatever else runs on the device (result walks on the side stream) is finite.  The
+// members' polls are bounded all the same.
 hipError_t launch_team(const cbd_decoder *d, const AdvanceParams &p, int n_channels) {
   cbd::TeamParams tp{};
   tp.a = p;
   tp.team = d->d_team; tp.q1 = d->d_team_q1; tp.q2 = d->d_team_q2; tp.cwin = d->d_team_cwin;
   tp.pub_key = d->d_team_pub_key; tp.pub_lid = d->d_team_pub_lid;
+  // (teams padded to a multiple of 8 where the device has room: see the kernel's note on dies)
+  int n_cu = 0;
+  (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, d->g->device);
+  int padded = (n_channels + 7) / 8 * 8;
+  if ((int64_t)padded * d->team_k > n_cu) padded = n_channels;
+  tp.n_teams = n_channels;
   tp.k = d->team_k; tp.q_cap = d->team_q_cap; tp.part_cap = d->team_part_cap; tp.slots = d->team_slots;
   tp.stage_rows = d->team_stage_rows; tp.ctx_lds_cap = d->ctx_lds_cap;
-  void *args[] = {(void *)&tp};
-  return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&cbd::advance_team_kernel),
-                                    dim3((unsigned)(n_channels * d->team_k)), dim3(1024), args, d->team_lds, d->stream);
+  hipLaunchKernelGGL(cbd::advance_team_kernel, dim3((unsigned)(padded * d->team_k)), dim3(1024), d->team_lds, d->stream, tp);
+  return hipGetLastError();
 }
 
 hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {

@@ -26,26 +26,27 @@
 // The barrier is a counter in device memory that every member's thread 0 increments and then polls (agent-scope
 // atomics, release / acquire fences around them, a bounded number of polls: a member that waits too long marks the
 // channel failed and leaves, and so then do the others).  All members of all teams have to be resident at once:
-// the kernel is launched cooperatively and the host refuses more teams than the device has compute units.
+// the host refuses more teams than the device has compute units, and a member fills its unit's LDS.
 #pragma once
 
 namespace cbd {
 
 constexpr int kTeamMax = 8;       // members of a team
 constexpr int kTeamBig = 32;      // long rows a frame can share out
-constexpr int kTeamSpinLimit = 4 << 20;   // polls of a barrier before a member gives up (seconds)
+constexpr int kTeamSpinLimit = 8 << 20;   // polls of a barrier before a member gives up (seconds)
 constexpr int kStatusTeam = -6;   // a member waited too long at a team barrier (reported as a HIP-level failure)
 
 // A candidate on its way to the owner of its destination state.
-struct __attribute__((aligned(8))) TeamEntry {
+struct __attribute__((aligned(16))) TeamEntry {
   uint32_t dst;
   float cost;
   uint32_t arc;     // library arc index (closure records: the arc they stand for)
   int32_t from;     // emitting arc: the source token's place in the previous frame; closure: the source STATE
   int32_t row;      // first arc of dst
   uint32_t meta;    // degrees and closure length of dst (ArcRec::meta with the low 16 bits cleared)
+  uint32_t pad[2];  // (an entry is one aligned 32-byte sector: written whole, so nothing has to be read to merge it)
 };
-static_assert(sizeof(TeamEntry) == 24, "queue entries are 24 bytes");
+static_assert(sizeof(TeamEntry) == 32, "queue entries are 32 bytes");
 
 struct TeamClosureWin { int32_t idx; uint32_t arc; uint32_t parent_state; };
 
@@ -63,10 +64,8 @@ struct TeamFrame {
 };
 
 struct __attribute__((aligned(256))) TeamChan {
-  uint32_t barrier;        // arrivals at team barriers since the decoder was made
+  uint32_t barrier;        // arrivals at team barriers since the last reset (low 30 bits), failure marks (bits 30, 31)
   int32_t status;          // why the channel is parked (sticky until reset)
-  int32_t flag[4];         // a failure met before team barrier n is noted in flag[n & 3] and looked for there after
-                           // that barrier: a member that is already past it cannot change what a slower one reads
   int32_t partitioned;     // 0: the token list is the dense one a reset leaves; 1: members' shares
   int32_t ntok[kTeamMax];  // tokens of each member's share
   int32_t carry_n;         // long rows found in the last frame of the previous call
@@ -82,6 +81,7 @@ struct TeamParams {
   TeamClosureWin *cwin;    // [C][k][part_cap]
   uint32_t *pub_key;       // [C][k][slots] each member's table keys as of the end of phase 3
   uint16_t *pub_lid;       // [C][k][slots] and the tokens they name
+  int32_t n_teams;         // channels of this launch (the grid may hold more teams: padding, they return at once)
   int32_t k;               // members per team
   int32_t q_cap;
   int32_t part_cap;        // tokens per member and frame
@@ -90,12 +90,13 @@ struct TeamParams {
   int32_t ctx_lds_cap;
 };
 
-struct TeamLayout { uint32_t sh, hist, bitmap, ctx, L, hval, hkey, hidx, total; };
+struct TeamLayout { uint32_t sh, hist, bitmap, stage, ctx, L, hval, hkey, hidx, total; };
+struct TeamLive { float cost; int32_t first; int32_t deg; int32_t idx; };   // a token that survived pruning, on its way to a lane
 struct TeamShared {
   int32_t abort_flag, fault, failed;
   int32_t n_mine;            // tokens this member has made in the current frame
   int32_t n_cwin;            // closure winners noted for phase 4
-  int32_t cnt1[kTeamMax], cnt2[kTeamMax];   // entries pushed to each owner's queues
+  unsigned long long cnt1[2], cnt2[2];       // entries pushed to each owner's queues (16 bits per owner)
   uint32_t m_ord, best_ord;  // this member's minima before they go to the team
   int32_t n_big;             // long rows met unannounced in this member's own tokens
   int32_t big_first[kBigRows], big_deg[kBigRows], big_src[kBigRows];
@@ -110,6 +111,7 @@ __host__ __device__ inline TeamLayout team_layout(int num_pdfs_staged, int ctx_l
   l.sh = o; o += align_up((uint32_t)sizeof(TeamShared), 16);
   l.hist = o; o += 256 * 4;
   l.bitmap = o; o += kBloomWords * 4;
+  l.stage = o; o += 16 * 64 * (uint32_t)sizeof(TeamLive);   // per wave: up to 64 live tokens waiting for a full group
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
   l.L = o; o += align_up((uint32_t)num_pdfs_staged * 4, 16);
   l.hval = o; o += (uint32_t)slots * 8;
@@ -126,23 +128,29 @@ __device__ __forceinline__ uint32_t team_home(uint32_t state, uint32_t slots) {
   return __umulhi(team_hash(state) * 0x9E3779B1u, slots);
 }
 
-// Barrier across the k members of a team; `seq` counts the team barriers of this call.  A member that met a
-// failure on its way here says so first.  Returns false if the team has to give up waiting (then abort_flag is
-// set); `failed` receives the failure, if any, that some member met before this barrier.
+// Barrier across the k members of a team.  The word counts arrivals in its low 30 bits (the counter runs on from
+// barrier to barrier: a barrier is complete when the count reaches the next multiple of k; a reset starts it again)
+// and carries two failure marks, one for even and one for odd barriers of the call: a member that met a failure
+// on its way to barrier n sets the mark of n's parity before it arrives, and whoever leaves barrier n looks at that
+// mark only (a member that is already on its way to barrier n + 1 sets the other one).  Returns false if the team
+// has to give up waiting (then abort_flag is set); `failed` receives the failure, if any, met before this barrier.
+constexpr uint32_t kTeamCountMask = 0x3FFFFFFFu;
 __device__ __forceinline__ bool team_barrier(TeamChan *tc, TeamShared *sh, int k, int &seq, int &failed) {
   __syncthreads();
   if (threadIdx.x == 0) {
-    if (sh->fault) atomicCAS(&tc->flag[seq & 3], 0, kStatusCapacity);
+    const uint32_t mark = 0x40000000u << (seq & 1);
+    if (sh->fault) atomicOr(&tc->barrier, mark);
     __threadfence();   // what this member wrote is visible to the device before its arrival is
-    const uint32_t old = atomicAdd(&tc->barrier, 1u);
-    const uint32_t target = (old / (uint32_t)k + 1u) * (uint32_t)k;
+    uint32_t v = atomicAdd(&tc->barrier, 1u) + 1u;
+    const uint32_t target = (((v & kTeamCountMask) - 1u) / (uint32_t)k + 1u) * (uint32_t)k;
     int polls = 0;
-    while ((int32_t)(__hip_atomic_load(&tc->barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-      __builtin_amdgcn_s_sleep(8);
+    while ((v & kTeamCountMask) < target) {   // (the last to arrive does not wait)
+      __builtin_amdgcn_s_sleep(2);
+      v = __hip_atomic_load(&tc->barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (++polls > kTeamSpinLimit) { sh->abort_flag = 1; break; }
     }
     __threadfence();   // and what the others wrote before theirs is visible here
-    sh->failed = __hip_atomic_load(&tc->flag[seq & 3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sh->failed = (v & mark) ? kStatusCapacity : 0;
   }
   __syncthreads();
   failed = sh->failed;
@@ -150,23 +158,51 @@ __device__ __forceinline__ bool team_barrier(TeamChan *tc, TeamShared *sh, int k
   return sh->abort_flag == 0;
 }
 
-// Appends one entry per lane with `act` set to the queues of the entries' owners: one LDS atomic per wave and
-// owner hands out the places.
-__device__ __forceinline__ void team_push(TeamEntry *q_base, int32_t *cnt, TeamShared *sh, int k, int q_cap, int me,
-                                          bool act, int owner, const TeamEntry &e, int lane) {
+// Appends up to U entries per lane (those with act[u] set) to the queues of the entries' owners.  The members'
+// counters are 16-bit fields of 64-bit LDS words (owners 0-3 and 4-7), so ONE atomic per wave hands out the places
+// of all owners and all U groups at once (the waves of a member all add to the same word, and such atomics queue).
+// (A queue holds fewer than 32,768 entries; once one is full nothing is added any more, so no field overflows.)
+template <int U>
+__device__ __forceinline__ void team_push(TeamEntry *q_base, unsigned long long *cnt, TeamShared *sh, int k, int q_cap,
+                                          int me, const bool (&act)[U], const int (&owner)[U], const TeamEntry (&e)[U],
+                                          int lane) {
+  bool any = false;
+#pragma unroll
+  for (int u = 0; u < U; ++u) any = any || act[u];
+  if (__ballot(any) == 0) return;   // uniform
+  if (__hip_atomic_load(&sh->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0) return;
   const unsigned long long below = (1ull << lane) - 1ull;
-  for (int o = 0; o < k; ++o) {   // uniform
-    const unsigned long long m = __ballot(act && owner == o);
-    if (m == 0) continue;
-    int base = 0;
-    if (lane == (int)__builtin_ctzll(m)) base = atomicAdd(&cnt[o], (int)__popcll(m));
-    base = __shfl(base, (int)__builtin_ctzll(m), 64);
-    if (act && owner == o) {
-      const int pos = base + (int)__popcll(m & below);
-      if (pos < q_cap) q_base[((size_t)o * k + me) * q_cap + pos] = e;
+  unsigned long long add[2] = {0, 0};
+  int rank[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    rank[u] = 0;
+    for (int o = 0; o < k; ++o) {   // uniform
+      const unsigned long long m = __ballot(act[u] && owner[u] == o);
+      if (owner[u] == o) rank[u] = (int)__popcll(m & below) + (int)((add[o >> 2] >> (16 * (o & 3))) & 0xFFFFull);
+      add[o >> 2] += (unsigned long long)__popcll(m) << (16 * (o & 3));
+    }
+  }
+  unsigned long long base[2] = {0, 0};
+  if (lane == 0) {
+    if (add[0]) base[0] = atomicAdd(&cnt[0], add[0]);
+    if (add[1]) base[1] = atomicAdd(&cnt[1], add[1]);
+  }
+  base[0] = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(base[0] >> 32), 0) << 32) |
+            (uint32_t)__builtin_amdgcn_readlane((int)base[0], 0);
+  if (k > 4) base[1] = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)(base[1] >> 32), 0) << 32) |
+                       (uint32_t)__builtin_amdgcn_readlane((int)base[1], 0);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (act[u]) {
+      const int pos = (int)((base[owner[u] >> 2] >> (16 * (owner[u] & 3))) & 0xFFFFull) + rank[u];
+      if (pos < q_cap) q_base[((size_t)owner[u] * k + me) * q_cap + pos] = e[u];
       else sh->fault = 1;
     }
   }
+}
+__device__ __forceinline__ int team_count(const unsigned long long *cnt, int o) {
+  return (int)((cnt[o >> 2] >> (16 * (o & 3))) & 0xFFFFull);
 }
 
 // Finds or makes the slot of `state` in this member's table.  Returns false if the table is full.
@@ -216,25 +252,57 @@ __device__ __forceinline__ void team_min(uint64_t *hval, uint32_t *hkey, uint32_
   }
 }
 
-// Expansion of one emitting arc per lane: candidate cost (step 2: cost + biased weight - log-likelihood), the
-// member's running minimum, and the entry on its way to the destination's owner.
+// Expansion of one emitting arc per lane, in two halves so that several records can be on their way at once:
+// the record is asked for, and later the candidate cost (step 2: cost + biased weight - log-likelihood) joins the
+// member's running minimum and the entry goes on its way to the destination's owner.
+__device__ __forceinline__ ArcRec team_arc(const TeamParams &tp, bool act, int a) {
+  ArcRec rec; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
+  if (act) rec = tp.a.arcs[a];
+  return rec;
+}
+template <int U>
 __device__ __forceinline__ void team_emit(const TeamParams &tp, const Ctx &cx, const Rows &Lrow, TeamShared *sh,
-                                          TeamEntry *q1c, int me, bool act, int a, float c_own, int src_tok, int lane,
-                                          uint32_t &lmin) {
-  TeamEntry e; e.dst = 0; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0;
-  int owner = 0;
-  if (act) {
-    const ArcRec rec = tp.a.arcs[a];
-    float w = rec.weight;
-    if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1: boosted weight = weight + discount
-    const float cand = (c_own + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u);
-    const uint32_t o = f2ord(cand);
-    lmin = o < lmin ? o : lmin;
-    e.dst = (uint32_t)rec.dst; e.cost = cand; e.arc = (uint32_t)a; e.from = src_tok; e.row = rec.row;
-    e.meta = rec.meta & 0xFFFF0000u;
-    owner = team_owner(e.dst, tp.k);
+                                          TeamEntry *q1c, int me, const bool (&act)[U], const int (&a)[U],
+                                          const ArcRec (&rec)[U], float c_own, int src_tok, int lane, uint32_t &lmin) {
+  TeamEntry e[U];
+  int owner[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    e[u].dst = 0; e[u].cost = 0.0f; e[u].arc = 0; e[u].from = 0; e[u].row = 0; e[u].meta = 0; e[u].pad[0] = 0; e[u].pad[1] = 0;
+    owner[u] = 0;
+    if (act[u]) {
+      float w = rec[u].weight;
+      if (ctx_contains(cx, a[u])) w = w + cx.offset;   // Sec. 4.1: boosted weight = weight + discount
+      const float cand = (c_own + w) - Lrow.at((rec[u].meta & 0xFFFFu) - 1u);
+      const uint32_t o = f2ord(cand);
+      lmin = o < lmin ? o : lmin;
+      e[u].dst = (uint32_t)rec[u].dst; e[u].cost = cand; e[u].arc = (uint32_t)a[u]; e[u].from = src_tok; e[u].row = rec[u].row;
+      e[u].meta = rec[u].meta & 0xFFFF0000u;
+      owner[u] = team_owner(e[u].dst, tp.k);
+    }
   }
-  team_push(q1c, sh->cnt1, sh, tp.k, tp.q_cap, me, act, owner, e, lane);
+  team_push<U>(q1c, sh->cnt1, sh, tp.k, tp.q_cap, me, act, owner, e, lane);
+}
+// A long row shared out: this wave takes the groups of 64 arcs at j_begin, j_begin + j_step, ..., four at a time:
+// all four records are asked for before the first entry is stored (loads and stores complete in order, so a
+// load issued behind stores also waits for them).
+__device__ __forceinline__ void team_long_row(const TeamParams &tp, const Ctx &cx, const Rows &Lrow, TeamShared *sh,
+                                              TeamEntry *q1c, int me, int first, int deg, float cost, int src,
+                                              int j_begin, int j_step, int lane, uint32_t &lmin, uint32_t &n_emit) {
+  for (int j0 = j_begin; j0 < deg; j0 += 4 * j_step) {   // uniform
+    ArcRec r[4];
+    bool act[4];
+    int a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * j_step + lane;
+      act[u] = j < deg;
+      a[u] = first + j;
+      r[u] = team_arc(tp, act[u], a[u]);
+      n_emit += (uint32_t)__popcll(__ballot(act[u]));
+    }
+    team_emit<4>(tp, cx, Lrow, sh, q1c, me, act, a, r, cost, src, lane, lmin);
+  }
 }
 
 // A reset leaves the dense token list of the one-workgroup code behind and clears what the team kept.
@@ -244,9 +312,14 @@ __global__ void team_reset_kernel(TeamChan *team, const int32_t *chan_ids, int n
   TeamChan *tc = team + chan_ids[i];
   tc->status = 0; tc->partitioned = 0; tc->carry_n = 0;
   tc->barrier = 0;   // (a team that gave up waiting leaves its count between two multiples of k)
-  for (int q = 0; q < 4; ++q) tc->flag[q] = 0;
   for (int q = 0; q < kTeamMax; ++q) tc->ntok[q] = 0;
 }
+
+#ifdef CBD_PROFILE
+#define TEAM_STAMP(k_) do { if (tid == 0) { const long long t_ = wall_clock64(); tprof[k_] += t_ - tlast; tlast = t_; } } while (0)
+#else
+#define TEAM_STAMP(k_) do {} while (0)
+#endif
 
 __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -254,7 +327,12 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int NW = 16;
   const int k = tp.k;
-  const int ci = blockIdx.x / k, me = blockIdx.x % k;   // (members of a team are neighbours in the grid)
+  // Workgroups are handed to the chip's eight dies in turn.  With the teams' members a whole number of rounds apart
+  // in the grid (the host pads the number of teams to a multiple of 8), a team sits on one die and its queues stay in
+  // that die's L2.  (Only speed depends on it: the fences and atomics are device-wide.)
+  const int n_teams = (int)gridDim.x / k;
+  const int ci = blockIdx.x % n_teams, me = blockIdx.x / n_teams;
+  if (ci >= tp.n_teams) return;
   const int c = p.chan_ids[ci];
   ChanState *cs = p.chan + c;
   TeamChan *tc = tp.team + c;
@@ -263,6 +341,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
   TeamShared *sh = (TeamShared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
+  TeamLive *stage = (TeamLive *)(smem + lay.stage) + wave * 64;
   int32_t *ctx_lds = (int32_t *)(smem + lay.ctx);
   float *Lstage = (float *)(smem + lay.L);
   uint64_t *hval = (uint64_t *)(smem + lay.hval);
@@ -335,6 +414,10 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     }
     if (tid == 0) f1->n_big = carry_n < kTeamBig ? carry_n : kTeamBig;
   }
+#ifdef CBD_PROFILE
+  long long tprof[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  long long tlast = wall_clock64();
+#endif
   int bar_seq = 0, failed = 0;
   bool alive_team = team_barrier(tc, sh, k, bar_seq, failed);
   if (failed != 0 && status == kStatusOk) status = failed;
@@ -355,7 +438,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     if (tid == 0) {
       sh->n_mine = 0; sh->n_cwin = 0; sh->m_ord = 0xFFFFFFFFu; sh->best_ord = 0xFFFFFFFFu; sh->n_big = 0; sh->n_surv = 0;
     }
-    if (tid < kTeamMax) { sh->cnt1[tid] = 0; sh->cnt2[tid] = 0; }
+    if (tid < 2) { sh->cnt1[tid] = 0; sh->cnt2[tid] = 0; }
     for (int i = tid; i < 256; i += 1024) hist[i] = 0;
     __syncthreads();
 
@@ -366,13 +449,40 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       // this member's tokens: its share, or (first frame after a reset) its part of the dense list
       const int t0 = dense && f == 0 ? (int)((long long)n_dense * me / k) : me * part_cap;
       const int t1 = dense && f == 0 ? (int)((long long)n_dense * (me + 1) / k) : t0 + n_mine_prev;
+      // Most tokens of a dense frame fall to the histogram cut: the live ones are gathered in the wave's staging
+      // list and expanded a full group at a time (one lane per token; rows are short, the long ones are shared
+      // out), two arcs of a token together.  (A tile's tokens are asked for one tile ahead.)
+      auto expand_staged = [&](int n) {
+        TeamLive tk; tk.cost = 0.0f; tk.first = 0; tk.deg = 0; tk.idx = 0;
+        if (lane < n) tk = stage[lane];
+        for (int j = 0; __ballot(j < tk.deg) != 0; j += 2) {   // uniform
+          bool act[2] = {j < tk.deg, j + 1 < tk.deg};
+          int a[2] = {tk.first + j, tk.first + j + 1};
+          ArcRec r[2];
+          r[0] = team_arc(tp, act[0], a[0]);
+          r[1] = team_arc(tp, act[1], a[1]);
+          n_emit += (uint32_t)__popcll(__ballot(act[0])) + (uint32_t)__popcll(__ballot(act[1]));
+          team_emit<2>(tp, cx, Lrow, sh, q1c, me, act, a, r, tk.cost, tk.idx, lane, lmin);
+        }
+      };
+      int n_staged = 0;
+      float n_cost = 0.0f;
+      int4 n_row = make_int4(0, 0, 0, 0);
+      {
+        const int i = t0 + wave * 64 + lane;
+        if (i < t1) { n_cost = t_cost[i]; n_row = t_row[co + i]; }
+      }
       for (int i0 = t0 + wave * 64; i0 < t1; i0 += NW * 64) {
         const int i = i0 + lane;
+        const float cost = n_cost;
+        const int4 row = n_row;
+        {
+          const int in = i + NW * 64;
+          if (in < t1) { n_cost = t_cost[in]; n_row = t_row[co + in]; }
+        }
         bool alive = false;
-        float cost = 0.0f;
         int first = 0, deg = 0;
         if (i < t1) {
-          cost = t_cost[i];
           const float r = cost - best;
           alive = !(r > p.beam) && cost < __builtin_inff();
           if (alive && cut_bin < 255) {
@@ -380,7 +490,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
             bin = bin > 255 ? 255 : bin;
             alive = bin <= cut_bin;
           }
-          if (alive) { const int4 row = t_row[co + i]; first = row.x; deg = row.y - row.x; }
+          if (alive) { first = row.x; deg = row.y - row.x; }
         }
         n_active += (uint32_t)__popcll(__ballot(alive));
         if (deg > kBigRowArcs) {
@@ -391,16 +501,18 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
             deg = 0;
           }
         }
-        // one lane per token, its arcs one after the other (rows are short: the long ones are shared out)
-        int maxdeg = deg;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { const int t = __shfl_xor(maxdeg, d, 64); maxdeg = t > maxdeg ? t : maxdeg; }
-        for (int j = 0; j < maxdeg; ++j) {   // uniform
-          const bool act = j < deg;
-          n_emit += (uint32_t)__popcll(__ballot(act));
-          team_emit(tp, cx, Lrow, sh, q1c, me, act, first + j, cost, i, lane, lmin);
+        const unsigned long long lm = __ballot(deg > 0);
+        const int n_new = (int)__popcll(lm);
+        if (n_new == 0) continue;   // uniform
+        if (n_staged + n_new > 64) { expand_staged(n_staged); n_staged = 0; }
+        if (deg > 0) {
+          TeamLive tk; tk.cost = cost; tk.first = first; tk.deg = deg; tk.idx = i;
+          stage[n_staged + (int)__popcll(lm & ((1ull << lane) - 1ull))] = tk;
         }
+        n_staged += n_new;
       }
+      if (n_staged > 0) expand_staged(n_staged);
+      TEAM_STAMP(7);   // (diagnostic: own tokens expanded)
       // long rows announced by the previous frame: every wave of every member takes every (k * NW)-th group of 64
       const int nbig = fprev->n_big < kTeamBig ? fprev->n_big : kTeamBig;
       for (int r = 0; r < nbig; ++r) {
@@ -414,30 +526,25 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
         }
         if (!alive) continue;   // uniform (the token itself is counted where it lives, with an empty row)
         const int first = fprev->big_first[r], deg = fprev->big_deg[r], src = fprev->big_src[r];
-        for (int j0 = (me * NW + wave) * 64; j0 < deg; j0 += k * NW * 64) {
-          const bool act = j0 + lane < deg;
-          n_emit += (uint32_t)__popcll(__ballot(act));
-          team_emit(tp, cx, Lrow, sh, q1c, me, act, first + j0 + lane, cost, src, lane, lmin);
-        }
+        team_long_row(tp, cx, Lrow, sh, q1c, me, first, deg, cost, src, (me * NW + wave) * 64, k * NW * 64, lane, lmin, n_emit);
       }
+      TEAM_STAMP(8);   // (diagnostic: announced long rows expanded)
       __syncthreads();
+      TEAM_STAMP(9);   // (diagnostic: wait for the member's other waves)
       const int nloc = sh->n_big < kBigRows ? sh->n_big : kBigRows;
       for (int r = 0; r < nloc; ++r) {
         const int first = sh->big_first[r], deg = sh->big_deg[r], src = sh->big_src[r];
-        const float cost = sh->big_cost[r];
-        for (int j0 = wave * 64; j0 < deg; j0 += NW * 64) {
-          const bool act = j0 + lane < deg;
-          n_emit += (uint32_t)__popcll(__ballot(act));
-          team_emit(tp, cx, Lrow, sh, q1c, me, act, first + j0 + lane, cost, src, lane, lmin);
-        }
+        team_long_row(tp, cx, Lrow, sh, q1c, me, first, deg, sh->big_cost[r], src, wave * 64, NW * 64, lane, lmin, n_emit);
       }
       const uint32_t wmin = wave_min_u32(lmin);
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->m_ord, wmin);
       __syncthreads();
-      if (tid < k) fr->qn[tid][me] = sh->cnt1[tid] < tp.q_cap ? sh->cnt1[tid] : tp.q_cap;
+      if (tid < k) fr->qn[tid][me] = team_count(sh->cnt1, tid) < tp.q_cap ? team_count(sh->cnt1, tid) : tp.q_cap;
       if (tid == 0 && sh->m_ord != 0xFFFFFFFFu) atomicMin(&fr->m_ord, sh->m_ord);
     }
+    TEAM_STAMP(0);
     if (!(alive_team = team_barrier(tc, sh, k, bar_seq, failed))) break;
+    TEAM_STAMP(1);
     if (me == 0 && tid < 64) {
       // the other copy of the frame scalars is free now (its long rows have been expanded): clean it for frame f + 1
       for (int i = tid; i < 256; i += 64) fprev->hist[i] = 0;
@@ -446,7 +553,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       if (tid == 0) { fprev->m_ord = 0xFFFFFFFFu; fprev->best_ord = 0xFFFFFFFFu; fprev->n_big = 0; }
     }
     if (failed != 0) { status = failed; break; }
-    const uint32_t m_ord = __hip_atomic_load(&fr->m_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t m_ord = fr->m_ord;
     if (m_ord == 0xFFFFFFFFu) { status = kStatusNoTokens; break; }   // (every member sees the same)
     const float m = ord2f(m_ord);
 
@@ -455,20 +562,27 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     uint32_t cmin = 0xFFFFFFFFu;
     {
       int qn[kTeamMax], total = 0;
-      for (int s = 0; s < k; ++s) { qn[s] = __hip_atomic_load(&fr->qn[me][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); total += qn[s]; }
+      for (int s = 0; s < k; ++s) { qn[s] = fr->qn[me][s]; total += qn[s]; }   // (plain reads: the barrier's fence made them current)
       const int rounds = (total + 1023) / 1024;
-      for (int rd = 0; rd < rounds; ++rd) {   // uniform
+      auto fetch = [&](int rd) {   // this thread's entry of round rd (dst = kEmptyKey: none)
+        TeamEntry e; e.dst = kEmptyKey; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
         int t = rd * 1024 + tid;
-        bool act = t < total;
-        int s = 0;
-        if (act) { while (t >= qn[s]) { t -= qn[s]; ++s; } }
-        TeamEntry e; e.dst = 0; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0;
-        if (act) e = q1c[((size_t)me * k + s) * tp.q_cap + t];
+        if (t < total) {
+          int s = 0;
+          while (t >= qn[s]) { t -= qn[s]; ++s; }
+          e = q1c[((size_t)me * k + s) * tp.q_cap + t];
+        }
+        return e;
+      };
+      TeamEntry e_next = fetch(0);
+      for (int rd = 0; rd < rounds; ++rd) {   // uniform
+        const TeamEntry e = e_next;
+        if (rd + 1 < rounds) e_next = fetch(rd + 1);
+        const bool act = e.dst != kEmptyKey;
         const bool pass = act && !(e.cost - m > p.beam);
         n_cand += (uint32_t)__popcll(__ballot(pass));
-        team_min(hval, hkey, slots, sh, pass, e.dst, ((uint64_t)f2ord(e.cost) << 32) | e.arc, lane);
         // the closure list of the state reached (stored with the graph: depth-first preorder, a record's source
-        // is the latest record one level up)
+        // is the latest record one level up); its first record is asked for before the table is touched
         int pos = 0, len = 0;
         if (pass) {
           const uint32_t cl = meta_cl(e.meta);
@@ -480,33 +594,44 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
             pos = e.row + (int)meta_ed(e.meta) + (int)meta_xd(e.meta); len = (int)cl;
           }
         }
+        ArcRec rec0; rec0.dst = 0; rec0.weight = 0.0f; rec0.row = 0; rec0.meta = 0;
+        int can0 = 0;
+        if (len > 0) { rec0 = p.arcs[pos]; can0 = p.canon[pos]; }
+        team_min(hval, hkey, slots, sh, pass, e.dst, ((uint64_t)f2ord(e.cost) << 32) | e.arc, lane);
         int maxlen = len;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) { const int tt = __shfl_xor(maxlen, d, 64); maxlen = tt > maxlen ? tt : maxlen; }
         float cstack[kClosureMaxDepth + 1];
         uint32_t sstack[kClosureMaxDepth + 1];
+        const bool flat = maxlen == 1;   // (uniform) every list of this wave is one arc long: no levels to keep
+        if (!flat) {
 #pragma unroll
-        for (int d = 0; d <= kClosureMaxDepth; ++d) { cstack[d] = __builtin_inff(); sstack[d] = 0; }
-        cstack[0] = e.cost; sstack[0] = e.dst;
+          for (int d = 0; d <= kClosureMaxDepth; ++d) { cstack[d] = __builtin_inff(); sstack[d] = 0; }
+          cstack[0] = e.cost; sstack[0] = e.dst;
+        }
         for (int j = 0; j < maxlen; ++j) {   // uniform
           const bool has = j < len;
           bool ok = false;
-          TeamEntry ce; ce.dst = 0; ce.cost = 0.0f; ce.arc = 0; ce.from = 0; ce.row = 0; ce.meta = 0;
+          TeamEntry ce; ce.dst = 0; ce.cost = 0.0f; ce.arc = 0; ce.from = 0; ce.row = 0; ce.meta = 0; ce.pad[0] = 0; ce.pad[1] = 0;
           int owner = 0;
           if (has) {
-            const ArcRec rec = p.arcs[pos + j];
-            const int can = p.canon[pos + j];
+            const ArcRec rec = j == 0 ? rec0 : p.arcs[pos + j];
+            const int can = j == 0 ? can0 : p.canon[pos + j];
             const int depth = (int)(rec.meta & 0xFu);
             float w = rec.weight;
             if (ctx_contains(cx, can)) w = w + cx.offset;   // Sec. 4.1
-            float pc = __builtin_inff();
-            uint32_t ps = 0;
+            float pc = e.cost;
+            uint32_t ps = e.dst;
+            if (!flat) {
 #pragma unroll
-            for (int d = 1; d <= kClosureMaxDepth; ++d) if (d == depth) { pc = cstack[d - 1]; ps = sstack[d - 1]; }
+              for (int d = 1; d <= kClosureMaxDepth; ++d) if (d == depth) { pc = cstack[d - 1]; ps = sstack[d - 1]; }
+            }
             const float cc = pc + w;
             ok = cc < __builtin_inff() && !(cc - m > p.beam);
+            if (!flat) {
 #pragma unroll
-            for (int d = 1; d <= kClosureMaxDepth; ++d) if (d == depth) { cstack[d] = ok ? cc : __builtin_inff(); sstack[d] = (uint32_t)rec.dst; }
+              for (int d = 1; d <= kClosureMaxDepth; ++d) if (d == depth) { cstack[d] = ok ? cc : __builtin_inff(); sstack[d] = (uint32_t)rec.dst; }
+            }
             if (ok) {
               ce.dst = (uint32_t)rec.dst; ce.cost = cc; ce.arc = (uint32_t)can; ce.from = (int32_t)ps; ce.row = rec.row;
               ce.meta = rec.meta & 0xFFFF0000u;
@@ -533,48 +658,64 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
               ok = ok && lane == (int)__builtin_ctzll(wm);
             }
           }
-          team_push(q2c, sh->cnt2, sh, k, tp.q_cap, me, ok, owner, ce, lane);
+          {
+            const bool act1[1] = {ok};
+            const int owner1[1] = {owner};
+            const TeamEntry e1[1] = {ce};
+            team_push<1>(q2c, sh->cnt2, sh, k, tp.q_cap, me, act1, owner1, e1, lane);
+          }
         }
       }
       const uint32_t wmin = wave_min_u32(cmin);
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->best_ord, wmin);
       __syncthreads();
-      if (tid < k) fr->q2n[tid][me] = sh->cnt2[tid] < tp.q_cap ? sh->cnt2[tid] : tp.q_cap;
+      if (tid < k) fr->q2n[tid][me] = team_count(sh->cnt2, tid) < tp.q_cap ? team_count(sh->cnt2, tid) : tp.q_cap;
       if (tid == 0 && sh->best_ord != 0xFFFFFFFFu) atomicMin(&fr->best_ord, sh->best_ord);
     }
+    TEAM_STAMP(2);
     if (!(alive_team = team_barrier(tc, sh, k, bar_seq, failed))) break;
+    TEAM_STAMP(3);
     if (failed != 0) { status = failed; break; }
     if (n_rec + k * part_cap > p.bp_cap) { status = kStatusCapacity; break; }   // (the same for all)
 
     // ================= phase 3: closure candidates in; winners write their tokens
-    const uint32_t best_ord = umin32(m_ord, __hip_atomic_load(&fr->best_ord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const uint32_t best_ord = umin32(m_ord, fr->best_ord);
     const float fbest = ord2f(best_ord);
     int qn1[kTeamMax], qn2[kTeamMax], tot1 = 0, tot2 = 0;
     for (int s = 0; s < k; ++s) {
-      qn1[s] = __hip_atomic_load(&fr->qn[me][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); tot1 += qn1[s];
-      qn2[s] = __hip_atomic_load(&fr->q2n[me][s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); tot2 += qn2[s];
+      qn1[s] = fr->qn[me][s]; tot1 += qn1[s];
+      qn2[s] = fr->q2n[me][s]; tot2 += qn2[s];
     }
     for (int rd = 0; rd * 1024 < tot2; ++rd) {   // uniform
       int t = rd * 1024 + tid;
       const bool act = t < tot2;
       int s = 0;
       if (act) { while (t >= qn2[s]) { t -= qn2[s]; ++s; } }
-      TeamEntry e; e.dst = 0; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0;
+      TeamEntry e; e.dst = 0; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
       if (act) e = q2c[((size_t)me * k + s) * tp.q_cap + t];
       team_min(hval, hkey, slots, sh, act, e.dst, ((uint64_t)f2ord(e.cost) << 32) | e.arc, lane);
     }
     __syncthreads();
+    TEAM_STAMP(10);   // (diagnostic: closure candidates recombined)
     const int tok0 = me * part_cap;
-    for (int rd = 0; rd * 1024 < tot1 + tot2; ++rd) {   // uniform
+    auto fetch_any = [&](int rd, bool &closure) {   // this thread's entry of round rd over both sets of queues
+      TeamEntry e; e.dst = kEmptyKey; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
       int t = rd * 1024 + tid;
-      const bool act = t < tot1 + tot2;
-      const bool closure = act && t >= tot1;
-      TeamEntry e; e.dst = 0; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0;
-      if (act) {
+      closure = t >= tot1;
+      if (t < tot1 + tot2) {
         int s = 0;
         if (!closure) { while (t >= qn1[s]) { t -= qn1[s]; ++s; } e = q1c[((size_t)me * k + s) * tp.q_cap + t]; }
         else { t -= tot1; while (t >= qn2[s]) { t -= qn2[s]; ++s; } e = q2c[((size_t)me * k + s) * tp.q_cap + t]; }
       }
+      return e;
+    };
+    bool closure_next = false;
+    TeamEntry w_next = fetch_any(0, closure_next);
+    for (int rd = 0; rd * 1024 < tot1 + tot2; ++rd) {   // uniform
+      const TeamEntry e = w_next;
+      const bool closure = closure_next;
+      if ((rd + 1) * 1024 < tot1 + tot2) w_next = fetch_any(rd + 1, closure_next);
+      const bool act = e.dst != kEmptyKey;
       bool win = false;
       uint32_t h = 0;
       uint64_t v = 0;
@@ -635,6 +776,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       if (sm != 0 && lane == 0) atomicAdd(&sh->n_surv, (int)__popcll(sm));
     }
     __syncthreads();
+    TEAM_STAMP(11);   // (diagnostic: winners done)
     // publish (state -> token) of this share, then empty the table for the next frame
     const int n_mine = sh->n_mine < part_cap ? sh->n_mine : part_cap;
     for (uint32_t i = tid; i < slots; i += 1024) {
@@ -650,7 +792,9 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       atomicAdd(&sh->a_active, (unsigned long long)n_active); atomicAdd(&sh->a_emit, (unsigned long long)n_emit);
       atomicAdd(&sh->a_eps, (unsigned long long)n_eps); atomicAdd(&sh->a_cand, (unsigned long long)n_cand);
     }
+    TEAM_STAMP(4);
     if (!(alive_team = team_barrier(tc, sh, k, bar_seq, failed))) break;
+    TEAM_STAMP(5);
     if (failed != 0) { status = failed; break; }
 
     // ================= phase 4: records of the closure winners; the next frame's scalars
@@ -669,14 +813,14 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
         bp[n_rec + cw.idx] = make_int2((int)cw.arc, n_rec + o * part_cap + plid);
       }
       int n_total = 0, n_surv = 0;
-      for (int s = 0; s < k; ++s) n_total += __hip_atomic_load(&fr->count[s], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int s = 0; s < k; ++s) n_total += fr->count[s];
       int cutb = 255;
       if (hist_on && n_total > p.max_active) {
         // (every member computes the same cut from the team's histogram; only wave 0's result is kept)
         if (wave == 0) {
           int loc[4], sum = 0;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) { loc[q] = (int)__hip_atomic_load(&fr->hist[lane * 4 + q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); sum += loc[q]; }
+          for (int q = 0; q < 4; ++q) { loc[q] = (int)fr->hist[lane * 4 + q]; sum += loc[q]; }
           const int inc = wave_incl_scan(sum);
           n_surv = __builtin_amdgcn_readlane(inc, 63);
           if (n_surv > p.max_active) {
@@ -703,6 +847,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       max_tok = n_total > max_tok ? n_total : max_tok;
       __syncthreads();   // (cut_bin in LDS is free again)
     }
+    TEAM_STAMP(6);
   }
 
   // ---- leave
@@ -737,6 +882,12 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
         tc->carry_first[i] = lf->big_first[i]; tc->carry_deg[i] = lf->big_deg[i];
         tc->carry_src[i] = lf->big_src[i]; tc->carry_cost[i] = lf->big_cost[i];
       }
+#ifdef CBD_PROFILE
+      for (int q = 0; q < 7; ++q) cs->spare[q] += tprof[q];
+      cs->spare[12] += tprof[7]; cs->spare[13] += tprof[8]; cs->spare[14] += tprof[9];
+      cs->spare[7] += tprof[10]; cs->spare[8] += tprof[11];
+      cs->spare[11] += frames_done;
+#endif
       const int n_new = n_rec - cs->gc_base;
       if (p.new_records) p.new_records[c] = make_int2(n_new, p.call_seq);
       if (p.due_max) atomicMax(p.due_max, ((unsigned long long)(uint32_t)p.call_seq << 32) | (uint32_t)n_new);

@@ -22,8 +22,9 @@ def default_hash_log2(w: synth.Workload) -> int:
 
 
 def default_team(w: synth.Workload) -> int:
-    """Workgroups per channel: the lexicon-loop workload's frames (20,000 tokens) are shared by teams of four."""
-    return 1   # (see bench.py --workgroups-per-channel)
+    """Workgroups per channel: the lexicon-loop workload's frames (20,000 tokens) are shared by teams of four
+    (64 channels x 4 = the 256 compute units); the HCLG-style workloads fit one workgroup's LDS."""
+    return 4 if w.name.startswith("e2e") and w.channels * 4 <= 256 else 1
 
 
 def default_records_per_frame(w: synth.Workload) -> int:
@@ -75,7 +76,7 @@ class Session:
                  records_per_frame: int = 0, graph_handle=None, biased: bool = True, lds_token_cap: int = 0,
                  context_mode: str = "upload", async_partials: bool = True, workgroups_per_cu: int = 0,
                  compact_records_above: int = 0, record_frames: int = 0, tail_partials: bool = False,
-                 block_threads: int = 0, frame_code: int = 0, workgroups_per_channel: int = 0):
+                 block_threads: int = 0, frame_code: int = 0, workgroups_per_channel: int = -1):
         """compact_records_above / record_frames: automatic compaction of the back-pointer records, and the number
         of frames the record buffer is sized for (0: the whole utterance).  tail_partials: partial results through
         cbd_best_tails_begin / _finish (only the part of the path above what the compactions have fixed).
@@ -93,6 +94,8 @@ class Session:
         if inp.contexts is None:
             inp.contexts, inp.context_build = contexts_from_words(self.gh, inp.sequences)
         max_ctx = max([w.ctx_max, 1] + [int(x.size) for lists, _ in inp.contexts for x in lists])
+        if workgroups_per_channel < 0:
+            workgroups_per_channel = default_team(w)
         self.stream = torch.cuda.current_stream()
         self.dh = B.cbd_decoder_create(
             self.gh, w.channels, w.beam, w.max_active, record_frames or w.frames, max_ctx, w.lookup_mode,
