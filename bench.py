@@ -30,11 +30,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # profiled build: a run whose own launch time is more than 5 % away from it is another kernel (or another machine
 # state) and reports no traffic instead of a stale one.
 MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py reported in the profiled runs)
-    "large": (1291272553, 0.7254),
-    "stress": (15295533675, 5.8986),
-    "dynamic": (4858763561, 2.0645),
-    "medium": (440529209, 2.3278),
-    "words": (533112078, 0.5587),
+    "large": (1283385840, 0.7205),
+    "stress": (15171310986, 5.8236),
+    "dynamic": (4832273296, 2.0221),
+    "medium": (439996098, 2.3255),
+    "words": (530768285, 0.5391),
     "e2e": (12648971504, 5.1849),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
