@@ -136,7 +136,7 @@ typedef struct cbd_config {
                                  states are split over the team, candidates travel between members through device
                                  memory).  Needs num_channels x team <= compute units of the device, a graph whose
                                  epsilon closures are all stored as lists (at most 15 levels and 62 arcs each), and
-                                 compact_records_above = 0; each member can hold about 7,000 tokens per frame
+                                 compact_records_above = 0; members are 1024-thread workgroups, each can hold about 7,000 tokens per frame
                                  (CBD_E_CAPACITY beyond).  Results are the same; token and record numbers differ
                                  (cbd_get_tokens / cbd_get_records then show unused places at infinite cost) */
 } cbd_config;

@@ -204,7 +204,7 @@ struct cbd_decoder {
   std::vector<int32_t> kept_ids, last_ids;
   StageRing ctxs;  // context uploads
   // teams (workgroups_per_channel > 1)
-  int team_k = 0, team_slots = 0, team_part_cap = 0, team_q_cap = 0, team_stage_rows = 0;
+  int team_k = 0, team_block = 1024, team_slots = 0, team_part_cap = 0, team_q_cap = 0, team_stage_rows = 0;
   uint32_t team_lds = 0;
   cbd::TeamChan *d_team = nullptr;
   cbd::TeamEntry *d_team_q1 = nullptr, *d_team_q2 = nullptr;
@@ -255,7 +255,7 @@ hipError_t launch_team(const cbd_decoder *d, const AdvanceParams &p, int n_chann
   tp.n_teams = n_channels;
   tp.k = d->team_k; tp.q_cap = d->team_q_cap; tp.part_cap = d->team_part_cap; tp.slots = d->team_slots;
   tp.stage_rows = d->team_stage_rows; tp.ctx_lds_cap = d->ctx_lds_cap;
-  hipLaunchKernelGGL(cbd::advance_team_kernel, dim3((unsigned)(padded * d->team_k)), dim3(1024), d->team_lds, d->stream, tp);
+  hipLaunchKernelGGL(cbd::advance_team_kernel<1024>, dim3((unsigned)(padded * d->team_k)), dim3(1024), d->team_lds, d->stream, tp);
   return hipGetLastError();
 }
 
@@ -839,13 +839,21 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     const int k = cfg->workgroups_per_channel;
     int n_cu = 0;
     DCHK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, g->device));
+    // members resident at once: one 1024-thread member per compute unit (it fills the LDS).  (Two 512-thread members
+    // per unit were tried for teams of eight: every phase and every wait got longer, 160 instead of 100 us per frame.)
     if ((int64_t)d->C * k > n_cu)
       return fail(CBD_E_INVALID, "decoder: num_channels x workgroups_per_channel exceeds the device's compute units");
+    d->team_block = 1024;
     d->team_k = k;
+    const int64_t lds_member = (int64_t)lds_limit - 1024;
     // each member's table takes the LDS that the row, the context list and the small arrays leave
     d->team_stage_rows = g->P <= 4096 ? 1 : 0;
-    const cbd::TeamLayout fixed = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, 0);
-    int slots = (int)(((int64_t)lds_limit - 1024 - (int64_t)fixed.total - 64) / 14) / 64 * 64;
+    cbd::TeamLayout fixed = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, 0, d->team_block / 64);
+    if ((int64_t)fixed.total + 14 * 1024 > lds_member) {
+      d->team_stage_rows = 0;
+      fixed = cbd::team_layout(0, d->ctx_lds_cap, 0, d->team_block / 64);
+    }
+    int slots = (int)((lds_member - (int64_t)fixed.total - 64) / 14) / 64 * 64;
     slots = std::min(slots, 0xFFFF / 2 * 3 / 64 * 64);
     if (slots < 1024) return fail(CBD_E_INVALID, "decoder: no room for a team member's table in LDS");
     d->team_slots = slots;
@@ -855,9 +863,16 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     if (d->team_part_cap < 64) return fail(CBD_E_INVALID, "decoder: hash_capacity_log2 too small for a team");
     // (a sender's queue to one owner: in the frame after a reset one member expands a long start row by itself)
     d->team_q_cap = d->team_part_cap + d->team_part_cap / 4;
-    d->team_lds = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, slots).total;
-    DCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_team_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)d->team_lds));
+    d->team_lds = cbd::team_layout(d->team_stage_rows ? g->P : 0, d->ctx_lds_cap, slots, d->team_block / 64).total;
+    DCHK(hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_team_kernel<1024>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)d->team_lds));
+    {
+      // the members wait for one another inside the kernel: the device has to hold all of them at once
+      int per_cu = 0;
+      DCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, cbd::advance_team_kernel<1024>, 1024, d->team_lds));
+      if ((int64_t)per_cu * n_cu < (int64_t)d->C * k)
+        return fail(CBD_E_INVALID, "decoder: the device cannot hold all members of all teams at once");
+    }
     // a frame's records: one block of k shares
     const int64_t bp_team = (int64_t)k * d->team_part_cap * ((int64_t)cfg->max_frames + 1) + d->g_tok_cap;
     if (bp_team > 0x7FFFFFF0) return fail(CBD_E_INVALID, "decoder: back-pointer buffer too large per channel");

@@ -26,7 +26,7 @@
 // The barrier is a counter in device memory that every member's thread 0 increments and then polls (agent-scope
 // atomics, release / acquire fences around them, a bounded number of polls: a member that waits too long marks the
 // channel failed and leaves, and so then do the others).  All members of all teams have to be resident at once:
-// the host refuses more teams than the device has compute units, and a member fills its unit's LDS.
+// the host refuses more members than the device has compute units, and a member fills its unit's LDS.
 #pragma once
 
 namespace cbd {
@@ -105,13 +105,13 @@ struct TeamShared {
   unsigned long long a_active, a_emit, a_eps, a_cand;
 };
 
-__host__ __device__ inline TeamLayout team_layout(int num_pdfs_staged, int ctx_lds_cap, int slots) {
+__host__ __device__ inline TeamLayout team_layout(int num_pdfs_staged, int ctx_lds_cap, int slots, int n_waves) {
   TeamLayout l;
   uint32_t o = 0;
   l.sh = o; o += align_up((uint32_t)sizeof(TeamShared), 16);
   l.hist = o; o += 256 * 4;
   l.bitmap = o; o += kBloomWords * 4;
-  l.stage = o; o += 16 * 64 * (uint32_t)sizeof(TeamLive);   // per wave: up to 64 live tokens waiting for a full group
+  l.stage = o; o += (uint32_t)n_waves * 64 * (uint32_t)sizeof(TeamLive);   // per wave: up to 64 live tokens waiting for a full group
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
   l.L = o; o += align_up((uint32_t)num_pdfs_staged * 4, 16);
   l.hval = o; o += (uint32_t)slots * 8;
@@ -321,11 +321,12 @@ __global__ void team_reset_kernel(TeamChan *team, const int32_t *chan_ids, int n
 #define TEAM_STAMP(k_) do {} while (0)
 #endif
 
-__global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
+template <int kBlock>
+__global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const AdvanceParams &p = tp.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  constexpr int NW = 16;
+  constexpr int NW = kBlock / 64;
   const int k = tp.k;
   // Workgroups are handed to the chip's eight dies in turn.  With the teams' members a whole number of rounds apart
   // in the grid (the host pads the number of teams to a multiple of 8), a team sits on one die and its queues stay in
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
   ChanState *cs = p.chan + c;
   TeamChan *tc = tp.team + c;
 
-  const TeamLayout lay = team_layout(tp.stage_rows ? p.num_pdfs : 0, tp.ctx_lds_cap, tp.slots);
+  const TeamLayout lay = team_layout(tp.stage_rows ? p.num_pdfs : 0, tp.ctx_lds_cap, tp.slots, NW);
   TeamShared *sh = (TeamShared *)(smem + lay.sh);
   uint32_t *hist = (uint32_t *)(smem + lay.hist);
   uint32_t *bitmap = (uint32_t *)(smem + lay.bitmap);
@@ -376,12 +377,12 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
   cx.lds_list = (lds_cint_ptr)ctx_lds; cx.bitmap = bitmap;
   cx.in_lds = cx.n <= tp.ctx_lds_cap;
   cx.use_bitmap = p.lookup_mode == 1;
-  if (cx.in_lds) for (int i = tid; i < cx.n; i += 1024) ctx_lds[i] = cx.g_list[i];
-  for (int i = tid; i < kBloomWords; i += 1024) bitmap[i] = 0;
-  for (uint32_t i = tid; i < slots; i += 1024) { hval[i] = kEmptyVal; hkey[i] = kEmptyKey; }
+  if (cx.in_lds) for (int i = tid; i < cx.n; i += kBlock) ctx_lds[i] = cx.g_list[i];
+  for (int i = tid; i < kBloomWords; i += kBlock) bitmap[i] = 0;
+  for (uint32_t i = tid; i < slots; i += kBlock) { hval[i] = kEmptyVal; hkey[i] = kEmptyKey; }
   __syncthreads();
   if (cx.use_bitmap) {
-    for (int i = tid; i < cx.n; i += 1024) {
+    for (int i = tid; i < cx.n; i += kBlock) {
       const uint32_t h = bloom_hash(cx.g_list[i]);
       atomicOr(&bitmap[bloom_word(h)], bloom_mask(h));
     }
@@ -434,12 +435,12 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     const int co = cur * p.g_tok_cap, no = (cur ^ 1) * p.g_tok_cap;
     Rows Lrow;
     Lrow.lds = (lds_cfloat_ptr)Lstage; Lrow.glob = Lbase + (long long)f * p.num_pdfs; Lrow.staged = tp.stage_rows != 0;
-    if (tp.stage_rows) for (int i = tid; i < p.num_pdfs; i += 1024) Lstage[i] = Lrow.glob[i];
+    if (tp.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lstage[i] = Lrow.glob[i];
     if (tid == 0) {
       sh->n_mine = 0; sh->n_cwin = 0; sh->m_ord = 0xFFFFFFFFu; sh->best_ord = 0xFFFFFFFFu; sh->n_big = 0; sh->n_surv = 0;
     }
     if (tid < 2) { sh->cnt1[tid] = 0; sh->cnt2[tid] = 0; }
-    for (int i = tid; i < 256; i += 1024) hist[i] = 0;
+    for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
     __syncthreads();
 
     // ================= phase 1: prune and expand this member's tokens
@@ -563,10 +564,10 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     {
       int qn[kTeamMax], total = 0;
       for (int s = 0; s < k; ++s) { qn[s] = fr->qn[me][s]; total += qn[s]; }   // (plain reads: the barrier's fence made them current)
-      const int rounds = (total + 1023) / 1024;
+      const int rounds = (total + kBlock - 1) / kBlock;
       auto fetch = [&](int rd) {   // this thread's entry of round rd (dst = kEmptyKey: none)
         TeamEntry e; e.dst = kEmptyKey; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
-        int t = rd * 1024 + tid;
+        int t = rd * kBlock + tid;
         if (t < total) {
           int s = 0;
           while (t >= qn[s]) { t -= qn[s]; ++s; }
@@ -686,8 +687,8 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
       qn1[s] = fr->qn[me][s]; tot1 += qn1[s];
       qn2[s] = fr->q2n[me][s]; tot2 += qn2[s];
     }
-    for (int rd = 0; rd * 1024 < tot2; ++rd) {   // uniform
-      int t = rd * 1024 + tid;
+    for (int rd = 0; rd * kBlock < tot2; ++rd) {   // uniform
+      int t = rd * kBlock + tid;
       const bool act = t < tot2;
       int s = 0;
       if (act) { while (t >= qn2[s]) { t -= qn2[s]; ++s; } }
@@ -700,7 +701,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     const int tok0 = me * part_cap;
     auto fetch_any = [&](int rd, bool &closure) {   // this thread's entry of round rd over both sets of queues
       TeamEntry e; e.dst = kEmptyKey; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
-      int t = rd * 1024 + tid;
+      int t = rd * kBlock + tid;
       closure = t >= tot1;
       if (t < tot1 + tot2) {
         int s = 0;
@@ -711,10 +712,10 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     };
     bool closure_next = false;
     TeamEntry w_next = fetch_any(0, closure_next);
-    for (int rd = 0; rd * 1024 < tot1 + tot2; ++rd) {   // uniform
+    for (int rd = 0; rd * kBlock < tot1 + tot2; ++rd) {   // uniform
       const TeamEntry e = w_next;
       const bool closure = closure_next;
-      if ((rd + 1) * 1024 < tot1 + tot2) w_next = fetch_any(rd + 1, closure_next);
+      if ((rd + 1) * kBlock < tot1 + tot2) w_next = fetch_any(rd + 1, closure_next);
       const bool act = e.dst != kEmptyKey;
       bool win = false;
       uint32_t h = 0;
@@ -779,14 +780,14 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     TEAM_STAMP(11);   // (diagnostic: winners done)
     // publish (state -> token) of this share, then empty the table for the next frame
     const int n_mine = sh->n_mine < part_cap ? sh->n_mine : part_cap;
-    for (uint32_t i = tid; i < slots; i += 1024) {
+    for (uint32_t i = tid; i < slots; i += kBlock) {
       const uint32_t key = hkey[i];
       pub_key[(size_t)me * slots + i] = key;
       if (key != kEmptyKey) pub_lid[(size_t)me * slots + i] = hidx[i];
       hkey[i] = kEmptyKey; hval[i] = kEmptyVal;
     }
-    if (last) for (int i = tid + n_mine; i < part_cap; i += 1024) t_cost[tok0 + i] = __builtin_inff();   // unused places
-    if (hist_on) for (int i = tid; i < 256; i += 1024) if (hist[i]) atomicAdd(&fr->hist[i], hist[i]);
+    if (last) for (int i = tid + n_mine; i < part_cap; i += kBlock) t_cost[tok0 + i] = __builtin_inff();   // unused places
+    if (hist_on) for (int i = tid; i < 256; i += kBlock) if (hist[i]) atomicAdd(&fr->hist[i], hist[i]);
     if (tid == 0) fr->count[me] = n_mine;
     if (lane == 0) {   // (per-wave counters of the frame)
       atomicAdd(&sh->a_active, (unsigned long long)n_active); atomicAdd(&sh->a_emit, (unsigned long long)n_emit);
@@ -800,7 +801,7 @@ __global__ __launch_bounds__(1024) void advance_team_kernel(TeamParams tp) {
     // ================= phase 4: records of the closure winners; the next frame's scalars
     {
       const int ncw = sh->n_cwin;
-      for (int i = tid; i < ncw; i += 1024) {
+      for (int i = tid; i < ncw; i += kBlock) {
         const TeamClosureWin cw = cwin[i];
         const int o = team_owner(cw.parent_state, k);
         const uint32_t *pk = pub_key + (size_t)o * slots;

@@ -105,7 +105,7 @@ def test_worked_example_on_gpu(torch_cuda):
 
 def run_batch(torch, g, L, ctxs, offs, beam, max_active, chunks, lookup_mode=0, table_location=0, hash_log2=12,
               use_final=False, partial_check=True, swap=None, lds_token_cap=0, workgroups_per_cu=0,
-              workgroups_per_channel=0):
+              workgroups_per_channel=0, block_threads=0):
     """Decode all channels of L on the GPU and one by one on the checker; compare partial results
     after every chunk, final results, tables and counters.  swap = (frame, lists, offsets): replace
     all contexts before that frame (must be a chunk boundary)."""
@@ -113,7 +113,7 @@ def run_batch(torch, g, L, ctxs, offs, beam, max_active, chunks, lookup_mode=0, 
     Lh = L.cpu().numpy()
     dec = GH.GpuDecoder(g, C, beam, max_active, max_frames=T, lookup_mode=lookup_mode, table_location=table_location,
                         hash_log2=hash_log2, lds_token_cap=lds_token_cap, workgroups_per_cu=workgroups_per_cu,
-                        workgroups_per_channel=workgroups_per_channel,
+                        workgroups_per_channel=workgroups_per_channel, block_threads=block_threads,
                         max_context_arcs=max(1, max(len(x) for x in ctxs),
                                                                   max((len(x) for x in swap[1]), default=1) if swap else 1))
     try:
