@@ -137,6 +137,7 @@ struct cbd_graph {
   int32_t visit_stamp = 0;
   int32_t max_word = 0;
   int32_t unstored_closures = 0;    // states whose epsilon closure is not stored as a list (too deep or too long)
+  std::vector<int4> long_rows;      // states with more than kBigRowArcs emitting arcs: (state, first arc, arcs, 0), by state
   size_t bytes = 0;
 };
 
@@ -211,6 +212,9 @@ struct cbd_decoder {
   cbd::TeamClosureWin *d_team_cwin = nullptr;
   uint32_t *d_team_pub_key = nullptr;
   uint16_t *d_team_pub_lid = nullptr;
+  int4 *d_team_big_rows = nullptr;
+  int32_t *d_team_big_group = nullptr, *d_team_big_perm = nullptr;
+  int32_t team_n_big_rows = 0;
   std::vector<int32_t> h_tmp;
   std::vector<int32_t> h_static_meta;   // result headers of cbd_best_paths_static on their way to the caller
   size_t bytes = 0;
@@ -247,6 +251,8 @@ hipError_t launch_team(const cbd_decoder *d, const AdvanceParams &p, int n_chann
   tp.a = p;
   tp.team = d->d_team; tp.q1 = d->d_team_q1; tp.q2 = d->d_team_q2; tp.cwin = d->d_team_cwin;
   tp.pub_key = d->d_team_pub_key; tp.pub_lid = d->d_team_pub_lid;
+  tp.big_rows = d->d_team_big_rows; tp.big_group = d->d_team_big_group; tp.big_perm = d->d_team_big_perm;
+  tp.n_big_rows = d->team_n_big_rows;
   // (teams padded to a multiple of 8 where the device has room: see the kernel's note on dies)
   int n_cu = 0;
   (void)hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, d->g->device);
@@ -523,6 +529,7 @@ int32_t cbd_graph_load(const cbd_graph_desc *desc, cbd_graph **out) try {
     total = end_x + std::max(n_clo[(size_t)s], 0);
     if (total > 0x7FFFFFF0) return fail(CBD_E_INVALID, "graph: too many arc records");
     off2[(size_t)s] = make_int4((int)first, (int)eps, (int)end_x, (int)total);
+    if (n_emit[(size_t)s] > cbd::kBigRowArcs) g->long_rows.push_back(make_int4(s, (int)first, n_emit[(size_t)s], 0));
   }
   const int32_t AL = (int32_t)total;   // records in the library's arc array
   g->A_lib = AL;
@@ -899,6 +906,23 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     DCHK(dmalloc(&d->d_team_cwin, C * k * (size_t)d->team_part_cap, &d->bytes));
     DCHK(dmalloc(&d->d_team_pub_key, C * k * (size_t)d->team_slots, &d->bytes));
     DCHK(dmalloc(&d->d_team_pub_lid, C * k * (size_t)d->team_slots, &d->bytes));
+    // the graph's long rows, their arcs sorted by owning member (a few thousand rows at most: beyond that the
+    // rows are shared out arc by arc through the queues, as are rows this table does not know)
+    if (!g->long_rows.empty() && g->long_rows.size() <= 4096) {
+      std::vector<int4> rows = g->long_rows;
+      int64_t total = 0;
+      for (auto &r : rows) { r.w = (int)total; total += r.z; }
+      if (total < 0x7FFFFFF0) {
+        d->team_n_big_rows = (int32_t)rows.size();
+        DCHK(dmalloc(&d->d_team_big_rows, rows.size(), &d->bytes));
+        DCHK(dmalloc(&d->d_team_big_group, rows.size() * (k + 1), &d->bytes));
+        DCHK(dmalloc(&d->d_team_big_perm, (size_t)total, &d->bytes));
+        DCHK(hipMemcpy(d->d_team_big_rows, rows.data(), sizeof(int4) * rows.size(), hipMemcpyHostToDevice));
+        hipLaunchKernelGGL(cbd::team_prepare_rows_kernel, dim3((unsigned)rows.size()), dim3(256), 0, d->stream, g->d_arcs,
+                           d->d_team_big_rows, d->d_team_big_group, d->d_team_big_perm, d->team_k);
+        DCHK(hipGetLastError());
+      }
+    }
   }
   DCHK(dmalloc(&d->d_ctx_n, C + d->pool, &d->bytes));
   DCHK(dmalloc(&d->d_ctx_off, C + d->pool, &d->bytes));
@@ -947,7 +971,8 @@ int32_t cbd_decoder_free(cbd_decoder *d) {
   void *ptrs[] = {d->d_chan, d->d_tok_state, d->d_tok_cost, d->d_tok_row, d->d_bp,
                   d->d_log, d->d_ctx, d->d_ctx_n, d->d_ctx_off, d->d_hkey, d->d_hval, d->d_hidx, d->d_auto_snap,
                   d->d_gc_mark, d->d_gc_prefix, d->d_gc_cross, d->d_fixed_arcs, d->d_fixed_words, d->d_due_max, d->d_ids_kept,
-                  d->d_team, d->d_team_q1, d->d_team_q2, d->d_team_cwin, d->d_team_pub_key, d->d_team_pub_lid};
+                  d->d_team, d->d_team_q1, d->d_team_q2, d->d_team_cwin, d->d_team_pub_key, d->d_team_pub_lid,
+                  d->d_team_big_rows, d->d_team_big_group, d->d_team_big_perm};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (d->h_new) (void)hipHostFree(d->h_new);

@@ -61,6 +61,7 @@ struct TeamFrame {
   // long rows among this frame's tokens: expanded by the whole team in the next frame
   int32_t big_first[kTeamBig], big_deg[kTeamBig], big_src[kTeamBig];
   float big_cost[kTeamBig];
+  int32_t big_id[kTeamBig];   // the row's place in TeamParams::big_rows, or -1
 };
 
 struct __attribute__((aligned(256))) TeamChan {
@@ -69,7 +70,7 @@ struct __attribute__((aligned(256))) TeamChan {
   int32_t partitioned;     // 0: the token list is the dense one a reset leaves; 1: members' shares
   int32_t ntok[kTeamMax];  // tokens of each member's share
   int32_t carry_n;         // long rows found in the last frame of the previous call
-  int32_t carry_first[kTeamBig], carry_deg[kTeamBig], carry_src[kTeamBig];
+  int32_t carry_first[kTeamBig], carry_deg[kTeamBig], carry_src[kTeamBig], carry_id[kTeamBig];
   float carry_cost[kTeamBig];
   TeamFrame fr[2];
 };
@@ -82,6 +83,12 @@ struct TeamParams {
   uint32_t *pub_key;       // [C][k][slots] each member's table keys as of the end of phase 3
   uint16_t *pub_lid;       // [C][k][slots] and the tokens they name
   int32_t n_teams;         // channels of this launch (the grid may hold more teams: padding, they return at once)
+  // Rows with more than kBigRowArcs emitting arcs, known when the graph was loaded: for each, its arcs sorted by the
+  // member that owns their destination (a member then expands the arcs it owns itself: nothing travels)
+  const int4 *big_rows;    // [n_big_rows] x = state (ascending), y = first emitting arc, z = emitting arcs, w = start in big_perm
+  const int32_t *big_group;  // [n_big_rows][k + 1] where each member's arcs begin in the row's stretch of big_perm
+  const int32_t *big_perm;   // library arc indices
+  int32_t n_big_rows;
   int32_t k;               // members per team
   int32_t q_cap;
   int32_t part_cap;        // tokens per member and frame
@@ -101,7 +108,7 @@ struct TeamShared {
   int32_t n_big;             // long rows met unannounced in this member's own tokens
   int32_t big_first[kBigRows], big_deg[kBigRows], big_src[kBigRows];
   float big_cost[kBigRows];
-  int32_t cut_bin, n_surv;
+  int32_t cut_bin;
   unsigned long long a_active, a_emit, a_eps, a_cand;
 };
 
@@ -232,7 +239,7 @@ __device__ __forceinline__ void team_min(uint64_t *hval, uint32_t *hkey, uint32_
   const unsigned long long am = __ballot(act);
   if (am == 0) return;
   const int first = (int)__builtin_ctzll(am);
-  const uint32_t s0 = (uint32_t)__shfl((int)state, first, 64);
+  const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)state, first);
   if (__popcll(am) > 1 && __ballot(act && state == s0) == am) {
     const uint32_t hi = act ? (uint32_t)(key >> 32) : 0xFFFFFFFFu;
     const uint32_t mhi = wave_min_u32(hi);
@@ -303,6 +310,37 @@ __device__ __forceinline__ void team_long_row(const TeamParams &tp, const Ctx &c
     }
     team_emit<4>(tp, cx, Lrow, sh, q1c, me, act, a, r, cost, src, lane, lmin);
   }
+}
+
+// One workgroup per long row: sorts the row's arcs by the member that owns their destination (counting sort; the
+// order inside a member's group does not matter).
+__global__ __launch_bounds__(256) void team_prepare_rows_kernel(const ArcRec *arcs, const int4 *big_rows, int32_t *big_group,
+                                                                int32_t *big_perm, int k) {
+  __shared__ int32_t count[kTeamMax + 1], fill[kTeamMax];
+  const int4 row = big_rows[blockIdx.x];
+  if (threadIdx.x <= kTeamMax) count[threadIdx.x] = 0;
+  __syncthreads();
+  for (int j = threadIdx.x; j < row.z; j += blockDim.x) atomicAdd(&count[team_owner((uint32_t)arcs[row.y + j].dst, k)], 1);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int o = 0; o < k; ++o) { const int c = count[o]; big_group[blockIdx.x * (k + 1) + o] = run; fill[o] = run; run += c; }
+    big_group[blockIdx.x * (k + 1) + k] = run;
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < row.z; j += blockDim.x) {
+    const int o = team_owner((uint32_t)arcs[row.y + j].dst, k);
+    big_perm[row.w + atomicAdd(&fill[o], 1)] = row.y + j;
+  }
+}
+// The place of `state` among the long rows, or -1.
+__device__ __forceinline__ int team_long_row_id(const TeamParams &tp, uint32_t state) {
+  int lo = 0, hi = tp.n_big_rows;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if ((uint32_t)tp.big_rows[mid].x < state) lo = mid + 1; else hi = mid;
+  }
+  return (lo < tp.n_big_rows && (uint32_t)tp.big_rows[lo].x == state) ? lo : -1;
 }
 
 // A reset leaves the dense token list of the one-workgroup code behind and clears what the team kept.
@@ -411,12 +449,12 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
     TeamFrame *f1 = &tc->fr[1];
     if (tid < carry_n && tid < kTeamBig) {
       f1->big_first[tid] = tc->carry_first[tid]; f1->big_deg[tid] = tc->carry_deg[tid];
-      f1->big_src[tid] = tc->carry_src[tid]; f1->big_cost[tid] = tc->carry_cost[tid];
+      f1->big_src[tid] = tc->carry_src[tid]; f1->big_cost[tid] = tc->carry_cost[tid]; f1->big_id[tid] = tc->carry_id[tid];
     }
     if (tid == 0) f1->n_big = carry_n < kTeamBig ? carry_n : kTeamBig;
   }
 #ifdef CBD_PROFILE
-  long long tprof[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  long long tprof[14] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   long long tlast = wall_clock64();
 #endif
   int bar_seq = 0, failed = 0;
@@ -437,11 +475,58 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
     Lrow.lds = (lds_cfloat_ptr)Lstage; Lrow.glob = Lbase + (long long)f * p.num_pdfs; Lrow.staged = tp.stage_rows != 0;
     if (tp.stage_rows) for (int i = tid; i < p.num_pdfs; i += kBlock) Lstage[i] = Lrow.glob[i];
     if (tid == 0) {
-      sh->n_mine = 0; sh->n_cwin = 0; sh->m_ord = 0xFFFFFFFFu; sh->best_ord = 0xFFFFFFFFu; sh->n_big = 0; sh->n_surv = 0;
+      sh->n_mine = 0; sh->n_cwin = 0; sh->m_ord = 0xFFFFFFFFu; sh->best_ord = 0xFFFFFFFFu; sh->n_big = 0;
     }
     if (tid < 2) { sh->cnt1[tid] = 0; sh->cnt2[tid] = 0; }
     for (int i = tid; i < 256; i += kBlock) hist[i] = 0;
     __syncthreads();
+
+    // a token's fate at the start of this frame (step 1), and one arc of a long row as the candidate it makes
+    auto row_alive = [&](float cost) {
+      const float rr = cost - best;
+      bool alive = !(rr > p.beam) && cost < __builtin_inff();
+      if (alive && cut_bin < 255) {
+        int bin = (int)floorf(rr * inv);
+        bin = bin > 255 ? 255 : bin;
+        alive = bin <= cut_bin;
+      }
+      return alive;
+    };
+    // (asked for a round ahead: the arc's place in the sorted list, then its record; made into an entry afterwards)
+    auto long_load = [&](int perm0, int t, int t_end, int &a, ArcRec &rec) {
+      a = -1; rec.dst = 0; rec.weight = 0.0f; rec.row = 0; rec.meta = 0;
+      if (t < t_end) { a = tp.big_perm[perm0 + t]; rec = p.arcs[a]; }
+    };
+    auto long_entry = [&](int a, const ArcRec &rec, float cost, int src) {
+      TeamEntry e; e.dst = kEmptyKey; e.cost = 0.0f; e.arc = 0; e.from = 0; e.row = 0; e.meta = 0; e.pad[0] = 0; e.pad[1] = 0;
+      if (a >= 0) {
+        float w = rec.weight;
+        if (ctx_contains(cx, a)) w = w + cx.offset;   // Sec. 4.1
+        e.dst = (uint32_t)rec.dst; e.cost = (cost + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u); e.arc = (uint32_t)a; e.from = src;
+        e.row = rec.row; e.meta = rec.meta & 0xFFFF0000u;
+      }
+      return e;
+    };
+    const int nbig_prev = fprev->n_big < kTeamBig ? fprev->n_big : kTeamBig;
+    // every candidate this member owns of the announced long rows with sorted arcs, one per thread and round
+    auto for_owned_long_arcs = [&](auto &&fn) {
+      for (int r = 0; r < nbig_prev; ++r) {
+        const int id = fprev->big_id[r];
+        const float cost = fprev->big_cost[r];
+        if (id < 0 || !row_alive(cost)) continue;   // uniform
+        const int src = fprev->big_src[r];
+        const int4 row = tp.big_rows[id];
+        const int g0 = tp.big_group[id * (k + 1) + me], g1 = tp.big_group[id * (k + 1) + me + 1];
+        int a0, a1;
+        ArcRec r0, r1;
+        long_load(row.w, g0 + tid, g1, a0, r0);
+        for (int t0 = g0; t0 < g1; t0 += kBlock) {   // uniform
+          long_load(row.w, t0 + kBlock + tid, g1, a1, r1);
+          fn(long_entry(a0, r0, cost, src));
+          a0 = a1; r0 = r1;
+        }
+      }
+    };
 
     // ================= phase 1: prune and expand this member's tokens
     uint32_t n_active = 0, n_emit = 0;
@@ -450,12 +535,25 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
       // this member's tokens: its share, or (first frame after a reset) its part of the dense list
       const int t0 = dense && f == 0 ? (int)((long long)n_dense * me / k) : me * part_cap;
       const int t1 = dense && f == 0 ? (int)((long long)n_dense * (me + 1) / k) : t0 + n_mine_prev;
-      // Most tokens of a dense frame fall to the histogram cut: the live ones are gathered in the wave's staging
-      // list and expanded a full group at a time (one lane per token; rows are short, the long ones are shared
-      // out), two arcs of a token together.  (A tile's tokens are asked for one tile ahead.)
+      // Most tokens of a dense frame fall to the histogram cut.  So only the costs are read for all of them (four
+      // tiles of a wave at a time); the live ones are gathered in the wave's staging list and expanded a full
+      // group at a time: their rows are read then, one lane per token (rows are short, the long ones are shared
+      // out), two arcs of a token together.
       auto expand_staged = [&](int n) {
         TeamLive tk; tk.cost = 0.0f; tk.first = 0; tk.deg = 0; tk.idx = 0;
-        if (lane < n) tk = stage[lane];
+        if (lane < n) {
+          tk = stage[lane];
+          const int4 row = t_row[co + tk.idx];
+          tk.first = row.x; tk.deg = row.y - row.x;
+          if (tk.deg > kBigRowArcs) {
+            // a long row that was not announced (the start token's): this member's waves share it out below
+            const int slot = atomicAdd(&sh->n_big, 1);
+            if (slot < kBigRows) {
+              sh->big_first[slot] = tk.first; sh->big_deg[slot] = tk.deg; sh->big_cost[slot] = tk.cost; sh->big_src[slot] = tk.idx;
+              tk.deg = 0;
+            }
+          }
+        }
         for (int j = 0; __ballot(j < tk.deg) != 0; j += 2) {   // uniform
           bool act[2] = {j < tk.deg, j + 1 < tk.deg};
           int a[2] = {tk.first + j, tk.first + j + 1};
@@ -467,56 +565,34 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         }
       };
       int n_staged = 0;
-      float n_cost = 0.0f;
-      int4 n_row = make_int4(0, 0, 0, 0);
-      {
-        const int i = t0 + wave * 64 + lane;
-        if (i < t1) { n_cost = t_cost[i]; n_row = t_row[co + i]; }
-      }
-      for (int i0 = t0 + wave * 64; i0 < t1; i0 += NW * 64) {
-        const int i = i0 + lane;
-        const float cost = n_cost;
-        const int4 row = n_row;
-        {
-          const int in = i + NW * 64;
-          if (in < t1) { n_cost = t_cost[in]; n_row = t_row[co + in]; }
+      for (int base = t0 + wave * 64; base < t1; base += 4 * NW * 64) {   // uniform
+        float c4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = base + u * NW * 64 + lane;
+          c4[u] = i < t1 ? t_cost[i] : __builtin_inff();
         }
-        bool alive = false;
-        int first = 0, deg = 0;
-        if (i < t1) {
-          const float r = cost - best;
-          alive = !(r > p.beam) && cost < __builtin_inff();
-          if (alive && cut_bin < 255) {
-            int bin = (int)floorf(r * inv);
-            bin = bin > 255 ? 255 : bin;
-            alive = bin <= cut_bin;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (base + u * NW * 64 >= t1) break;   // uniform
+          const int i = base + u * NW * 64 + lane;
+          const bool alive = i < t1 && row_alive(c4[u]);
+          const unsigned long long lm = __ballot(alive);
+          const int n_new = (int)__popcll(lm);
+          n_active += (uint32_t)n_new;
+          if (n_new == 0) continue;   // uniform
+          if (n_staged + n_new > 64) { expand_staged(n_staged); n_staged = 0; }
+          if (alive) {
+            TeamLive tk; tk.cost = c4[u]; tk.first = 0; tk.deg = 0; tk.idx = i;
+            stage[n_staged + (int)__popcll(lm & ((1ull << lane) - 1ull))] = tk;
           }
-          if (alive) { first = row.x; deg = row.y - row.x; }
+          n_staged += n_new;
         }
-        n_active += (uint32_t)__popcll(__ballot(alive));
-        if (deg > kBigRowArcs) {
-          // a long row that was not announced (the start token's): this member's waves share it out below
-          const int slot = atomicAdd(&sh->n_big, 1);
-          if (slot < kBigRows) {
-            sh->big_first[slot] = first; sh->big_deg[slot] = deg; sh->big_cost[slot] = cost; sh->big_src[slot] = i;
-            deg = 0;
-          }
-        }
-        const unsigned long long lm = __ballot(deg > 0);
-        const int n_new = (int)__popcll(lm);
-        if (n_new == 0) continue;   // uniform
-        if (n_staged + n_new > 64) { expand_staged(n_staged); n_staged = 0; }
-        if (deg > 0) {
-          TeamLive tk; tk.cost = cost; tk.first = first; tk.deg = deg; tk.idx = i;
-          stage[n_staged + (int)__popcll(lm & ((1ull << lane) - 1ull))] = tk;
-        }
-        n_staged += n_new;
       }
       if (n_staged > 0) expand_staged(n_staged);
       TEAM_STAMP(7);   // (diagnostic: own tokens expanded)
       // long rows announced by the previous frame: every wave of every member takes every (k * NW)-th group of 64
-      const int nbig = fprev->n_big < kTeamBig ? fprev->n_big : kTeamBig;
-      for (int r = 0; r < nbig; ++r) {
+      for (int r = 0; r < nbig_prev; ++r) {
         const float cost = fprev->big_cost[r];
         const float rr = cost - best;
         bool alive = !(rr > p.beam) && cost < __builtin_inff();
@@ -527,7 +603,23 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         }
         if (!alive) continue;   // uniform (the token itself is counted where it lives, with an empty row)
         const int first = fprev->big_first[r], deg = fprev->big_deg[r], src = fprev->big_src[r];
-        team_long_row(tp, cx, Lrow, sh, q1c, me, first, deg, cost, src, (me * NW + wave) * 64, k * NW * 64, lane, lmin, n_emit);
+        if (fprev->big_id[r] < 0) {
+          team_long_row(tp, cx, Lrow, sh, q1c, me, first, deg, cost, src, (me * NW + wave) * 64, k * NW * 64, lane, lmin, n_emit);
+          continue;
+        }
+        // its arcs are sorted by owner: every member will expand the ones it owns after the barrier.  Here the team
+        // only needs their minimum (each wave looks at its share of the row)
+        for (int j0 = (me * NW + wave) * 64; j0 < deg; j0 += k * NW * 64) {   // uniform
+          const int j = j0 + lane;
+          if (j < deg) {
+            const ArcRec rec = p.arcs[first + j];
+            float w = rec.weight;
+            if (ctx_contains(cx, first + j)) w = w + cx.offset;   // Sec. 4.1
+            const uint32_t o = f2ord((cost + w) - Lrow.at((rec.meta & 0xFFFFu) - 1u));
+            lmin = o < lmin ? o : lmin;
+          }
+          n_emit += (uint32_t)__popcll(__ballot(j < deg));
+        }
       }
       TEAM_STAMP(8);   // (diagnostic: announced long rows expanded)
       __syncthreads();
@@ -575,10 +667,8 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         }
         return e;
       };
-      TeamEntry e_next = fetch(0);
-      for (int rd = 0; rd < rounds; ++rd) {   // uniform
-        const TeamEntry e = e_next;
-        if (rd + 1 < rounds) e_next = fetch(rd + 1);
+      // what happens to one received candidate (dst = kEmptyKey: this lane has none)
+      auto recombine = [&](const TeamEntry &e) {
         const bool act = e.dst != kEmptyKey;
         const bool pass = act && !(e.cost - m > p.beam);
         n_cand += (uint32_t)__popcll(__ballot(pass));
@@ -599,18 +689,15 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         int can0 = 0;
         if (len > 0) { rec0 = p.arcs[pos]; can0 = p.canon[pos]; }
         team_min(hval, hkey, slots, sh, pass, e.dst, ((uint64_t)f2ord(e.cost) << 32) | e.arc, lane);
-        int maxlen = len;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { const int tt = __shfl_xor(maxlen, d, 64); maxlen = tt > maxlen ? tt : maxlen; }
         float cstack[kClosureMaxDepth + 1];
         uint32_t sstack[kClosureMaxDepth + 1];
-        const bool flat = maxlen == 1;   // (uniform) every list of this wave is one arc long: no levels to keep
+        const bool flat = __ballot(len > 1) == 0;   // (uniform) no list of this wave is longer than one arc: no levels to keep
         if (!flat) {
 #pragma unroll
           for (int d = 0; d <= kClosureMaxDepth; ++d) { cstack[d] = __builtin_inff(); sstack[d] = 0; }
           cstack[0] = e.cost; sstack[0] = e.dst;
         }
-        for (int j = 0; j < maxlen; ++j) {   // uniform
+        for (int j = 0; __ballot(j < len) != 0; ++j) {   // uniform
           const bool has = j < len;
           bool ok = false;
           TeamEntry ce; ce.dst = 0; ce.cost = 0.0f; ce.arc = 0; ce.from = 0; ce.row = 0; ce.meta = 0; ce.pad[0] = 0; ce.pad[1] = 0;
@@ -647,7 +734,7 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
           const unsigned long long om = __ballot(ok);
           if (om != 0) {
             const int fl = (int)__builtin_ctzll(om);
-            const uint32_t d0 = (uint32_t)__shfl((int)ce.dst, fl, 64);
+            const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)ce.dst, fl);
             if (__popcll(om) > 1 && __ballot(ok && ce.dst == d0) == om) {
               const uint32_t hi = ok ? f2ord(ce.cost) : 0xFFFFFFFFu;
               const uint32_t mhi = wave_min_u32(hi);
@@ -666,7 +753,16 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
             team_push<1>(q2c, sh->cnt2, sh, k, tp.q_cap, me, act1, owner1, e1, lane);
           }
         }
+      };
+      TeamEntry e_next = fetch(0);
+      for (int rd = 0; rd < rounds; ++rd) {   // uniform
+        const TeamEntry e = e_next;
+        if (rd + 1 < rounds) e_next = fetch(rd + 1);
+        recombine(e);
       }
+      // long rows whose arcs are sorted by owner: this member expands the arcs it owns, here, with the cutoff known
+      TEAM_STAMP(12);   // (diagnostic: candidates from the queues recombined)
+      for_owned_long_arcs([&](const TeamEntry &e) { recombine(e); });
       const uint32_t wmin = wave_min_u32(cmin);
       if (lane == 0 && wmin != 0xFFFFFFFFu) atomicMin(&sh->best_ord, wmin);
       __syncthreads();
@@ -710,12 +806,8 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
       }
       return e;
     };
-    bool closure_next = false;
-    TeamEntry w_next = fetch_any(0, closure_next);
-    for (int rd = 0; rd * kBlock < tot1 + tot2; ++rd) {   // uniform
-      const TeamEntry e = w_next;
-      const bool closure = closure_next;
-      if ((rd + 1) * kBlock < tot1 + tot2) w_next = fetch_any(rd + 1, closure_next);
+    // the entry whose key is its state's value writes the token
+    auto winner = [&](const TeamEntry &e, bool closure) {
       const bool act = e.dst != kEmptyKey;
       bool win = false;
       uint32_t h = 0;
@@ -723,17 +815,18 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
       if (act && !(e.cost - m > p.beam)) {
         h = team_find(hkey, slots, e.dst);
         v = hval[h];
-        // the entry whose key is the state's value wins; equal keys (a closure record reached twice, or a copy
-        // of an entry) are told apart by the exchange
-        win = v != kEmptyVal && (uint32_t)v == e.arc && (uint32_t)(v >> 32) == f2ord(e.cost) &&
-              atomicCAS((unsigned long long *)&hval[h], (unsigned long long)v, (unsigned long long)kEmptyVal) == v;
+        // the entry whose key is the state's value wins.  An emitting arc is expanded once per frame, so its entry
+        // is the only one with its key; a closure record can have been reached twice with the same key: there an
+        // exchange lets one of the two through
+        win = v != kEmptyVal && (uint32_t)v == e.arc && (uint32_t)(v >> 32) == f2ord(e.cost);
+        if (win && closure)
+          win = atomicCAS((unsigned long long *)&hval[h], (unsigned long long)v, (unsigned long long)kEmptyVal) == v;
       }
       const unsigned long long wm = __ballot(win);
-      if (wm == 0) continue;   // uniform
+      if (wm == 0) return;   // uniform
       int base = 0;
       if (lane == (int)__builtin_ctzll(wm)) base = atomicAdd(&sh->n_mine, (int)__popcll(wm));
-      base = __shfl(base, (int)__builtin_ctzll(wm), 64);
-      bool surv = false;
+      base = __builtin_amdgcn_readlane(base, (int)__builtin_ctzll(wm));
       if (win) {
         const int lid = base + (int)__popcll(wm & ((1ull << lane) - 1ull));
         if (lid >= part_cap) { sh->fault = 1; }
@@ -749,6 +842,7 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
             const int slot = atomicAdd(&fr->n_big, 1);
             if (slot < kTeamBig) {
               fr->big_first[slot] = first; fr->big_deg[slot] = eps - first; fr->big_src[slot] = idx; fr->big_cost[slot] = e.cost;
+              fr->big_id[slot] = team_long_row_id(tp, e.dst);
               first = eps;   // (the token's own row has no emitting arcs left: the team expands them)
             }
           }
@@ -765,7 +859,6 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
           if (hist_on) {
             const float r = e.cost - fbest;
             if (!(r > p.beam)) {
-              surv = true;
               int bin = (int)floorf(r * inv);
               bin = bin > 255 ? 255 : bin;
               atomicAdd(&hist[bin], 1u);
@@ -773,9 +866,17 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
           }
         }
       }
-      const unsigned long long sm = __ballot(surv);
-      if (sm != 0 && lane == 0) atomicAdd(&sh->n_surv, (int)__popcll(sm));
+    };
+    bool closure_next = false;
+    TeamEntry w_next = fetch_any(0, closure_next);
+    for (int rd = 0; rd * kBlock < tot1 + tot2; ++rd) {   // uniform
+      const TeamEntry e = w_next;
+      const bool closure = closure_next;
+      if ((rd + 1) * kBlock < tot1 + tot2) w_next = fetch_any(rd + 1, closure_next);
+      winner(e, closure);
     }
+    TEAM_STAMP(13);   // (diagnostic: winners among the queues' candidates)
+    for_owned_long_arcs([&](const TeamEntry &e) { winner(e, false); });   // (made once more: the same bits)
     __syncthreads();
     TEAM_STAMP(11);   // (diagnostic: winners done)
     // publish (state -> token) of this share, then empty the table for the next frame
@@ -807,10 +908,10 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         const uint32_t *pk = pub_key + (size_t)o * slots;
         uint32_t h = team_home(cw.parent_state, slots);
         uint32_t probe = 0;
-        while (__hip_atomic_load(&pk[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != cw.parent_state && probe < slots) {
+        while (pk[h] != cw.parent_state && probe < slots) {   // (plain reads: the barrier's fence made them current)
           h = h + 1 == slots ? 0 : h + 1; ++probe;
         }
-        const int plid = (int)__hip_atomic_load(&pub_lid[(size_t)o * slots + h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int plid = (int)pub_lid[(size_t)o * slots + h];
         bp[n_rec + cw.idx] = make_int2((int)cw.arc, n_rec + o * part_cap + plid);
       }
       int n_total = 0, n_surv = 0;
@@ -881,12 +982,12 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
       tc->carry_n = nb;
       for (int i = 0; i < nb; ++i) {
         tc->carry_first[i] = lf->big_first[i]; tc->carry_deg[i] = lf->big_deg[i];
-        tc->carry_src[i] = lf->big_src[i]; tc->carry_cost[i] = lf->big_cost[i];
+        tc->carry_src[i] = lf->big_src[i]; tc->carry_cost[i] = lf->big_cost[i]; tc->carry_id[i] = lf->big_id[i];
       }
 #ifdef CBD_PROFILE
       for (int q = 0; q < 7; ++q) cs->spare[q] += tprof[q];
       cs->spare[12] += tprof[7]; cs->spare[13] += tprof[8]; cs->spare[14] += tprof[9];
-      cs->spare[7] += tprof[10]; cs->spare[8] += tprof[11];
+      cs->spare[7] += tprof[10]; cs->spare[8] += tprof[11]; cs->spare[9] += tprof[12]; cs->spare[10] += tprof[13];
       cs->spare[11] += frames_done;
 #endif
       const int n_new = n_rec - cs->gc_base;
