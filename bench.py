@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py
     "dynamic": (4832273296, 2.0221),
     "medium": (439996098, 2.3255),
     "words": (530768285, 0.5391),
-    "e2e": (5182438502, 4.2498),   # teams of four workgroups per channel
+    "e2e": (4278575727, 4.1282),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
 

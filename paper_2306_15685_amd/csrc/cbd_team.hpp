@@ -543,8 +543,10 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
         TeamLive tk; tk.cost = 0.0f; tk.first = 0; tk.deg = 0; tk.idx = 0;
         if (lane < n) {
           tk = stage[lane];
-          const int4 row = t_row[co + tk.idx];
-          tk.first = row.x; tk.deg = row.y - row.x;
+          // (the team keeps 8 bytes of a token's row: first emitting arc, first epsilon arc; the list a reset leaves
+          // has the one-workgroup code's 16-byte rows)
+          if (dense && f == 0) { const int4 row = t_row[co + tk.idx]; tk.first = row.x; tk.deg = row.y - row.x; }
+          else { const int2 row = ((const int2 *)(t_row + co))[tk.idx]; tk.first = row.x; tk.deg = row.y - row.x; }
           if (tk.deg > kBigRowArcs) {
             // a long row that was not announced (the start token's): this member's waves share it out below
             const int slot = atomicAdd(&sh->n_big, 1);
@@ -834,10 +836,10 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
           hidx[h] = (uint16_t)lid;
           const int idx = tok0 + lid;
           // the state's row: from the arc record's fields, or (long rows) from the offsets
-          int first = e.row, eps, end;
-          const uint32_t ed = meta_ed(e.meta), xd = meta_xd(e.meta);
-          if (ed == kEdEscape || xd == kXdEscape) { const int4 o = p.off2[e.dst]; eps = o.y; end = o.z; }
-          else { eps = first + (int)ed; end = eps + (int)xd; }
+          int first = e.row, eps;
+          const uint32_t ed = meta_ed(e.meta);
+          if (ed == kEdEscape) eps = p.off2[e.dst].y;
+          else eps = first + (int)ed;
           if (eps - first > kBigRowArcs) {
             const int slot = atomicAdd(&fr->n_big, 1);
             if (slot < kTeamBig) {
@@ -847,7 +849,7 @@ __global__ __launch_bounds__(kBlock) void advance_team_kernel(TeamParams tp) {
             }
           }
           t_cost[idx] = e.cost;
-          t_row[no + idx] = make_int4(first, eps, end, 0);
+          ((int2 *)(t_row + no))[idx] = make_int2(first, eps);
           if (last) t_state[idx] = (int32_t)e.dst;
           if (!closure) {
             bp[n_rec + idx] = make_int2((int)e.arc, frame_base + e.from);
