@@ -128,8 +128,8 @@ typedef struct cbd_config {
                                  overshot by the records of a few calls: size the buffer with that room */
   int32_t block_threads;      /* threads per workgroup of the decoding kernel: 256, 512, 960 or 1024; 0 = chosen by
                                  the library from workgroups_per_cu (1024 / 512 / 256 for 1 / 2 / 4) */
-  int32_t frame_code;         /* 0 = frames that qualify (tables in LDS, at most one token per thread, stored closure
-                                 lists) are decoded by the lean frame code, the rest by the general code; 1 = general
+  int32_t frame_code;         /* 0 = frames that qualify (tables in LDS, every closure met stored as a list with the
+                                 graph) are decoded by the lean frame code, the rest by the general code; 1 = general
                                  code only.  Results are the same either way. */
   int32_t workgroups_per_channel; /* 0 or 1 = one workgroup decodes a channel; 2, 4 or 8 = a team of that many
                                  shares it (for frames with far more tokens than one compute unit's LDS holds: the
