@@ -30,12 +30,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # profiled build: a run whose own launch time is more than 5 % away from it is another kernel (or another machine
 # state) and reports no traffic instead of a stale one.
 MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py reported in the profiled runs)
-    "large": (1283385840, 0.7205),
-    "stress": (15171310986, 5.8236),
-    "dynamic": (4832273296, 2.0221),
-    "medium": (439996098, 2.3255),
-    "words": (530768285, 0.5391),
-    "e2e": (4278575727, 4.1282),   # teams of four workgroups per channel
+    "large": (1283632345, 0.7143),
+    "stress": (15270464448, 5.6538),
+    "dynamic": (4834990698, 1.9789),
+    "medium": (439933841, 2.3262),
+    "words": (530753309, 0.5256),
+    "e2e": (4275270043, 4.1032),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
 

@@ -205,6 +205,17 @@ struct Shared {
 __device__ __forceinline__ int sh_log_n(const Shared *sh) { return (int)(uint32_t)sh->log_claim; }
 __device__ __forceinline__ int sh_n_claim(const Shared *sh) { return (int)(uint32_t)(sh->log_claim >> 32); }
 
+// Bloom filter in front of the context list's binary search: an arc sets two bits of one 32-bit word, so a test is
+// one LDS read.  64 Kbit: with a 1,000-arc list 3 % of the bits are set and one lane in a thousand passes by chance;
+// the search loop runs for a whole wave whenever one of its lanes passes (with 16 Kbit that was 6 in 10 wave
+// instructions on 1,000-arc lists, and cost 3 % of the launch; 32 and 128 Kbit measured no better: the filter's
+// 8 KB come out of the LDS tables).
+#ifndef CBD_BLOOM_LOG2_WORDS
+#define CBD_BLOOM_LOG2_WORDS 11
+#endif
+constexpr int kBloomLog2Words = CBD_BLOOM_LOG2_WORDS;
+constexpr int kBloomWords = 1 << kBloomLog2Words;
+
 struct LdsLayout {
   uint32_t sh, hist, bitmap, owner, cmap, ctx, L, hval, hkey, hidx, tcost, log, total;
 };
@@ -225,7 +236,7 @@ __host__ __device__ inline LdsLayout make_layout(int num_pdfs, int ctx_lds_cap, 
   uint32_t o = 0;
   l.sh = o; o += align_up((uint32_t)sizeof(Shared), 16);
   l.hist = o; o += 256 * 4;
-  l.bitmap = o; o += 512 * 4;
+  l.bitmap = o; o += kBloomWords * 4;
   l.owner = o; o += 16 * 256;   // per-wave owner map of the first 256 arcs of a tile
   l.cmap = o; o += 16 * 64;     // per-wave owner map of a closure stage's records
   l.ctx = o; o += align_up((uint32_t)ctx_lds_cap * 4, 16);
@@ -342,10 +353,11 @@ __device__ __forceinline__ bool sorted_contains(ListPtr list, int n, int32_t a) 
   return lo < n && list[lo] == a;
 }
 
-constexpr int kBloomWords = 512;  // 16K bits; an arc sets two bits of one word, so a test is one read
 __device__ __forceinline__ uint32_t bloom_hash(int32_t a) { return (uint32_t)a * 2654435761u; }
-__device__ __forceinline__ uint32_t bloom_word(uint32_t h) { return h >> 23; }
-__device__ __forceinline__ uint32_t bloom_mask(uint32_t h) { return (1u << ((h >> 18) & 31u)) | (1u << ((h >> 13) & 31u)); }
+__device__ __forceinline__ uint32_t bloom_word(uint32_t h) { return h >> (32 - kBloomLog2Words); }
+__device__ __forceinline__ uint32_t bloom_mask(uint32_t h) {
+  return (1u << ((h >> (27 - kBloomLog2Words)) & 31u)) | (1u << ((h >> (22 - kBloomLog2Words)) & 31u));
+}
 
 // LDS-typed pointers: reads through them are plain LDS reads, not generic loads
 typedef const __attribute__((address_space(3))) float *lds_cfloat_ptr;
