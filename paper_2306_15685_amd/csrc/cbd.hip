@@ -241,6 +241,14 @@ hipError_t set_attr(int block, uint32_t lds) {
   return set_attr_t<1024>(lds);
 }
 
+// Workgroups of the decode kernel that one compute unit holds at once (registers, waves and LDS together).
+hipError_t resident_per_cu(int block, uint32_t lds, int *n) {
+  if (block == 256) return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, cbd::advance_kernel<256>, 256, lds);
+  if (block == 512) return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, cbd::advance_kernel<512>, 512, lds);
+  if (block == 960) return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, cbd::advance_kernel<960>, 960, lds);
+  return hipOccupancyMaxActiveBlocksPerMultiprocessor(n, cbd::advance_kernel<1024>, 1024, lds);
+}
+
 // A team launch.  The members of a team wait for one another inside the kernel, so all of a launch's workgroups
 // have to become resident without waiting for one another: the grid never exceeds the device's compute units
 // (checked when the decoder is made), a workgroup fills a compute unit's LDS, launches of one decoder follow one
@@ -791,10 +799,11 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
   DCHK(hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, g->device));
   {
     // How many workgroups (channels) share a compute unit's LDS.  One 1024-thread workgroup per compute unit is
-    // the default at every channel count: the frame code keeps the vector units busy about half the time, so two
-    // 512-thread workgroups side by side gain little from hiding each other's waits and lose more to the halved
-    // table capacity, which sends their larger frames to the tables in device memory (measured with 512 channels:
-    // 3.3 instead of 2.05 ms per launch; with 2048: 11.2 instead of 5.9 ms).  A caller can still ask for 2 or 4.
+    // the default at every channel count: the frame code keeps the vector units busy about half the time, two
+    // 512-thread workgroups side by side each run their frames 1.6 times slower (two rounds per wave, and the
+    // halved table capacity sends their larger frames to the tables in device memory) and gain nothing back from
+    // sharing the unit (measured with 512 channels: 2.8 instead of 2.0 ms per launch; with 2048: 8.8 instead of
+    // 5.6 ms).  A caller can still ask for 2 or 4 (the kernel is held to 128 vector registers for that).
     int wgs = cfg->workgroups_per_cu;
     if (wgs == 0) wgs = 1;
     // (a little LDS per compute unit is left for the partial-result walks, which run beside the decoding)
@@ -842,6 +851,14 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     }
   }
   DCHK(set_attr(d->block, d->lds_bytes));
+  if (cfg->workgroups_per_cu > 1) {
+    // the LDS was divided for that many workgroups side by side: registers and waves have to allow them too
+    int per_cu = 0;
+    DCHK(resident_per_cu(d->block, d->lds_bytes, &per_cu));
+    if (per_cu < cfg->workgroups_per_cu)
+      return fail(CBD_E_INVALID, "decoder: a compute unit holds " + std::to_string(per_cu) +
+                                 " workgroups of this size, fewer than workgroups_per_cu");
+  }
   if (cfg->workgroups_per_channel > 1) {
     const int k = cfg->workgroups_per_channel;
     int n_cu = 0;

@@ -120,7 +120,7 @@ struct AdvanceParams {
   int32_t start_state;
   int32_t num_pdfs;
   ChanState *chan;         // [C]
-  const int32_t *chan_ids; // [grid] channel of each workgroup
+  const int32_t *chan_ids; // [grid] the call's channel list
   const float *loglikes;
   long long channel_stride;
   int32_t n_frames;
@@ -1246,11 +1246,11 @@ __device__ __forceinline__ void rows_to_device(const Mem<true> &M, const LeanMem
   __syncthreads();   // (waits for the stores: other waves read the rows past their L1)
 }
 
+// One call's work on one channel: `pos` is the channel's place in the call's list.
 template <int kBlock>
-__global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
-  extern __shared__ __align__(16) unsigned char smem[];
+__device__ __forceinline__ void advance_channel(const AdvanceParams &p, const int pos, unsigned char *smem) {
   const int tid = threadIdx.x;
-  const int c = p.chan_ids[blockIdx.x];
+  const int c = p.chan_ids[pos];
   ChanState *cs = p.chan + c;
   const LdsLayout lay = make_layout(p.stage_rows ? p.num_pdfs : 0, p.ctx_lds_cap, p.lds_tok_cap, p.lds_slots,
                                     p.lds_log_cap, p.lean_log_per_wave * (kBlock / 64));
@@ -1287,7 +1287,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   auto g_cost = [&]() { return p.tok_cost + (size_t)c * p.g_tok_cap; };
   int32_t *g_tok_state = p.tok_state + (size_t)c * p.g_tok_cap;
   int2 *bp = p.bp + (size_t)c * p.bp_cap;
-  const float *Lbase = p.loglikes + (long long)blockIdx.x * p.channel_stride;
+  const float *Lbase = p.loglikes + (long long)pos * p.channel_stride;
 
   if (tid == 0) {
     sh->status = p.do_reset ? kStatusOk : cs->status;
@@ -1303,7 +1303,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
   if (sh->status != kStatusOk) {  // uniform: the channel is parked until reset
     if (p.new_records && tid == 0) p.new_records[c] = make_int2(0, p.call_seq);
     if (p.auto_snap && tid == 0) {
-      int32_t *snap = p.auto_snap + (size_t)blockIdx.x * kSnapInts;
+      int32_t *snap = p.auto_snap + (size_t)pos * kSnapInts;
       snap[0] = sh->status; snap[1] = -1; snap[2] = (int)0xFFFFFFFFu; snap[3] = cs->n_rec; snap[4] = c;
       snap[5] = 0; snap[6] = 0; snap[7] = 0;
     }
@@ -1499,7 +1499,7 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
         }
       }
       if (lane == 0) {
-        int32_t *snap = p.auto_snap + (size_t)blockIdx.x * kSnapInts;
+        int32_t *snap = p.auto_snap + (size_t)pos * kSnapInts;
         snap[0] = status != kStatusOk ? status : (besti < 0 ? kStatusNoTokens : kStatusOk);
         snap[1] = besti < 0 ? -1 : sh->frame_base + besti;
         snap[2] = (int)(uint32_t)(bestk >> 32);
@@ -1508,6 +1508,13 @@ __global__ __launch_bounds__(kBlock) void advance_kernel(AdvanceParams p) {
       }
     }
   }
+}
+
+// The decode kernel: workgroup b takes place b of the call's channel list.
+template <int kBlock>
+__global__ __launch_bounds__(kBlock, 4) void advance_kernel(AdvanceParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  advance_channel<kBlock>(p, (int)blockIdx.x, smem);
 }
 
 // ---- self-test of the cross-lane primitives ------------------------------------
