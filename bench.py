@@ -89,16 +89,17 @@ def cpu_baseline(inp, n_channels, budget_frames):
             "single_core_value": frames * 0.030 / dt1}
 
 
-def phase_report(B, sess, w):
+def phase_report(B, sess, w, team=1):
     """Diagnostic build only: where thread 0 of each workgroup spent the lean frames of the last pass (sums kept per
     channel by the kernel, 100 MHz counter), per lean frame, averaged over the channels."""
     import ctypes as C
     L = B.lib()
     L.cbd_debug_profile.restype = C.c_int32
     L.cbd_debug_profile.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
-    v = np.zeros((w.channels, 15), np.int64)
+    v = np.zeros((w.channels, 19), np.int64)
     for c in range(w.channels):
         assert L.cbd_debug_profile(sess.dh, c, v[c].ctypes.data_as(C.c_void_p)) == 0
+    timeline = None if team > 1 or not v[:, 16].any() else launch_timeline(v[:, 15:19])
     lean, frames = float(max(v[:, 10].sum(), 1)), float(max(v[:, 11].sum(), 1))
     us = lambda k: float(v[:, k].sum()) * 0.01 / lean
     launches = (w.frames + w.chunk - 1) // w.chunk
@@ -117,7 +118,40 @@ def phase_report(B, sess, w):
                              "next_row_and_rest": us(2)},
             "wait_barrier_2": us(3), "lookup_and_token_writes": us(4), "close_and_wait_barrier_3": us(5),
             "workgroup_us_per_launch": {"mean": float(run.mean()), "median": float(np.median(run)),
-                                        "p90": float(np.percentile(run, 90)), "max": float(run.max())}}
+                                        "p90": float(np.percentile(run, 90)), "max": float(run.max())},
+            "last_launch": timeline}
+
+
+def launch_timeline(t):
+    """The pass's last advance launch, from each workgroup's start and end stamp (one 100 MHz counter for the whole
+    device) and hardware ids: how long the workgroups ran, how busy the compute units were until the launch ended,
+    how long they stood between two workgroups and after their last one. Times in us."""
+    st, en, hw = t[:, 0], t[:, 1], t[:, 2]
+    t0 = st.min()
+    st, en = (st - t0) * 0.01, (en - t0) * 0.01
+    die, hwid = (hw >> 32) & 0xF, hw & 0xFFFFFFFF
+    unit = die * 4096 + ((hwid >> 13) & 7) * 256 + ((hwid >> 12) & 1) * 16 + ((hwid >> 8) & 0xF)  # die, engine, array, CU
+    dur, span = en - st, float(en.max())
+    gaps, last_end = [], []
+    for u in np.unique(unit):
+        m = unit == u
+        o = np.argsort(st[m])
+        s, e = st[m][o], en[m][o]
+        gaps += list(s[1:] - e[:-1])
+        last_end.append(e.max())
+    n_units = len(last_end)
+    gaps, last_end = np.array(gaps if gaps else [0.0]), np.array(last_end)
+    busy = float(dur.sum()) / n_units
+    return {"span": span, "workgroups": int(len(dur)), "compute_units": n_units,
+            "workgroup_us": {"mean": float(dur.mean()), "median": float(np.median(dur)), "p90": float(np.percentile(dur, 90)),
+                             "max": float(dur.max())},
+            "busy_per_compute_unit": busy, "busy_share": busy / span,
+            "gap_between_workgroups": {"median": float(np.median(gaps)), "p90": float(np.percentile(gaps, 90)),
+                                       "max": float(gaps.max()), "sum_per_compute_unit": float(gaps.sum()) / n_units,
+                                       "share": float(gaps.sum()) / n_units / span},
+            "compute_unit_last_end": {"min": float(last_end.min()), "mean": float(last_end.mean()), "max": float(last_end.max())},
+            "tail_share": float(span - last_end.mean()) / span,
+            "workgroups_per_die": [int((die == x).sum()) for x in np.unique(die)]}
 
 
 def main():
@@ -276,13 +310,16 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_measured_at_launch_ms": traffic_at_ms,
                      "achieved_is": "a model: per-unit bytes x the decoder's counters / measured kernel time "
                                     "(counts table and candidate traffic that this design keeps in LDS)",
-                     "kernel": "advance_team_kernel" if team > 1 else "advance_kernel", "launches_per_step": launches_per_step,
+                     "kernel": "advance_team_kernel" if team > 1 else "advance_kernel",
+                     "kernel_note": None if team > 1 else "launches that start while result walks of earlier calls are in flight run "
+                                    "as advance_beside_kernel (the same code held to 120 vector registers); both are timed here",
+                     "launches_per_step": launches_per_step,
                      "avg_launch_ms": avg_launch_ms, "algorithmic_bytes_per_launch": alg_bytes_step / launches_per_step,
                      "kernel_time_share": sum(kms) / (wall * 1e3)},
     }
     out["config"]["device_bytes"] = B.cbd_decoder_info(sess.dh)["device_bytes"]   # (buffers allocated on first use included)
     if args.phases:
-        out["phases"] = phase_report(B, sess, w)
+        out["phases"] = phase_report(B, sess, w, team)
     if inp.context_build is not None:   # Algorithm 1 on the host, outside the timed region (lists arrive rarely)
         out["context_build"] = inp.context_build
     if not args.no_cpu_baseline:

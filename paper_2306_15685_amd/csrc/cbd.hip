@@ -192,6 +192,8 @@ struct cbd_decoder {
     hipEvent_t done = nullptr;
   } out[kOutSlots];
   hipStream_t side = nullptr;      // walks and copies of asynchronous requests
+  bool walk_room = false;          // the LDS layout leaves room for walks beside a decoding workgroup
+  int walk_room_min_grid = 0;      // calls with at least this many channels use it
   // Best-token snapshots left by the decoding kernel itself, one ring slot per advance / reset call
   static constexpr int kSnapRing = 8;
   int32_t *d_auto_snap = nullptr;  // [kSnapRing][C][kSnapInts]
@@ -235,6 +237,11 @@ template <int kBlock> hipError_t set_attr_t(uint32_t lds) {
 }
 
 hipError_t set_attr(int block, uint32_t lds) {
+  if (block == 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&cbd::advance_beside_kernel<1024>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
   if (block == 256) return set_attr_t<256>(lds);
   if (block == 512) return set_attr_t<512>(lds);
   if (block == 960) return set_attr_t<960>(lds);
@@ -273,7 +280,21 @@ hipError_t launch_team(const cbd_decoder *d, const AdvanceParams &p, int n_chann
   return hipGetLastError();
 }
 
+// Is a result walk of an earlier call still on the side stream (enqueued and not finished)?
+bool walks_in_flight(const cbd_decoder *d) {
+  bool any = false;
+  for (int k = 1; k < cbd_decoder::kOutSlots && !any; ++k)
+    if (d->out[k].pending && d->out[k].done && hipEventQuery(d->out[k].done) == hipErrorNotReady) any = true;
+  (void)hipGetLastError();   // (a "not ready" answer is no error)
+  return any;
+}
+
 hipError_t launch_advance(const cbd_decoder *d, const AdvanceParams &p, int grid) {
+  if (d->walk_room && d->block == 1024 && grid >= d->walk_room_min_grid && walks_in_flight(d)) {
+    // leave the walks room on the compute units (see advance_beside_kernel)
+    hipLaunchKernelGGL((cbd::advance_beside_kernel<1024>), dim3(grid), dim3(1024), d->lds_bytes, d->stream, p);
+    return hipGetLastError();
+  }
   if (d->block == 256) return launch_advance_t<256>(p, grid, d->lds_bytes, d->stream);
   if (d->block == 512) return launch_advance_t<512>(p, grid, d->lds_bytes, d->stream);
   if (d->block == 960) return launch_advance_t<960>(p, grid, d->lds_bytes, d->stream);
@@ -806,8 +827,18 @@ int32_t cbd_decoder_create(const cbd_graph *g, const cbd_config *cfg, void *hip_
     // 5.6 ms).  A caller can still ask for 2 or 4 (the kernel is held to 128 vector registers for that).
     int wgs = cfg->workgroups_per_cu;
     if (wgs == 0) wgs = 1;
-    // (a little LDS per compute unit is left for the partial-result walks, which run beside the decoding)
-    const int budget = (lds_limit - 1024) / wgs;
+    // Result walks run beside the decoding (side stream).  Where a call's workgroups fill the device in one round
+    // (more than half of the compute units, not more than all), a walk that holds a compute unit delays that
+    // unit's channel and with it the whole call: such a decoder leaves 2 KB of LDS per compute unit free (half a
+    // KB per walk, but with 1 KB free none of them got onto a unit that held a decoding workgroup) and launches
+    // the 120-register kernel while walks are in flight (advance_beside_kernel).  With fewer channels the walks
+    // find free units, with more the workgroups are handed out as units come free and a late one costs little:
+    // there the 64 tokens of table capacity and the 8 registers are worth more (Stress +2 %, Dynamic +5 %).
+    int n_cu_all = 0;
+    DCHK(hipDeviceGetAttribute(&n_cu_all, hipDeviceAttributeMultiprocessorCount, g->device));
+    d->walk_room = wgs == 1 && cfg->block_threads == 0 && 2 * cfg->num_channels > n_cu_all && cfg->num_channels <= n_cu_all;
+    d->walk_room_min_grid = n_cu_all / 2 + 1;
+    const int budget = (lds_limit - (d->walk_room ? 2048 : 1024)) / wgs;
     // the lean frame code keeps a commit log per wave next to the tokens' rows (decided with the block size below)
     const int block_guess = cfg->block_threads != 0 ? cfg->block_threads : (wgs >= 4 ? 256 : (wgs >= 2 ? 512 : 1024));
     const int lean_entries = cfg->frame_code == 0 && cfg->table_location != 2 ? cbd::kLeanLogPerWave * (block_guess / 64) : 0;
@@ -1760,13 +1791,15 @@ int32_t cbd_selftest(void) {
 }
 
 #ifdef CBD_PROFILE
-// Diagnostic build only: the phase sums a channel's lean frames left (see CBD_STAMP), 15 values.
+// Diagnostic build only: the phase sums a channel's lean frames left (see CBD_STAMP), 15 values, then start, end,
+// hardware ids and list place of the workgroup of the channel's last call (ChanState::timeline): 19 values.
 int32_t cbd_debug_profile(cbd_decoder *d, int32_t channel, int64_t *out) {
   if (!d || !out || channel < 0 || channel >= d->C) return CBD_E_INVALID;
   HIPCHK(hipStreamSynchronize(d->stream));
   cbd::ChanState cs;
   HIPCHK(hipMemcpy(&cs, d->d_chan + channel, sizeof(cs), hipMemcpyDeviceToHost));
   for (int k = 0; k < 15; ++k) out[k] = cs.spare[k];
+  for (int k = 0; k < 4; ++k) out[15 + k] = cs.timeline[k];
   return CBD_OK;
 }
 #endif

@@ -109,8 +109,13 @@ struct __attribute__((aligned(128))) ChanState {
   int32_t n_fixed_words; // channel's fixed_arcs / fixed_words rows)
   long long lean_frames; // frames decoded by the lean code
   long long spare[15];
+#ifdef CBD_PROFILE
+  long long timeline[16];  // diagnostic build: the workgroup of the channel's last call with frames (start, end, ids)
+#endif
 };
+#ifndef CBD_PROFILE
 static_assert(sizeof(ChanState) == 256, "one channel's state fills two 128-byte lines");
+#endif
 
 struct AdvanceParams {
   const int4 *off2;        // [S]: x = first arc of the state, y = its first epsilon-input arc, z = end of those
@@ -1456,6 +1461,14 @@ __device__ __forceinline__ void advance_channel(const AdvanceParams &p, const in
       cs->spare[14] += packed;
     }
     cs->spare[9] += wall_clock64() - prof_k0;   // the workgroup's whole run
+    if (p.n_frames > 0) {
+      // when and where the workgroup ran: the 100 MHz counter is the same on all compute units; hardware register
+      // 4 (HW_ID) holds the compute unit, shader array and engine, register 20 (XCC_ID) the die
+      cs->timeline[0] = prof_k0; cs->timeline[1] = wall_clock64();
+      cs->timeline[2] = ((long long)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 20) << 32) |
+                        (unsigned)__builtin_amdgcn_s_getreg((32 - 1) << 11 | 4);
+      cs->timeline[3] = pos;
+    }
     cs->spare[10] += sh->a_lean;
     cs->spare[11] += (long long)sh->a_frames;
 #endif
@@ -1513,6 +1526,20 @@ __device__ __forceinline__ void advance_channel(const AdvanceParams &p, const in
 // The decode kernel: workgroup b takes place b of the call's channel list.
 template <int kBlock>
 __global__ __launch_bounds__(kBlock, 4) void advance_kernel(AdvanceParams p) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  advance_channel<kBlock>(p, (int)blockIdx.x, smem);
+}
+
+// The same with 120 instead of 128 vector registers per wave, for launches that start while result walks of
+// earlier calls are still on the side stream.  Sixteen waves of 128 registers take a compute unit's whole register
+// file: no wave of another kernel fits beside them, so a walk (two waves of 16 registers, half a KB of LDS) that
+// gets onto a compute unit first keeps the decoding workgroup off it until it is through, and the launch ends that
+// much later (Large, a partial result per chunk: 0.69 ms per launch against 0.59 without the walks).  With 8
+// registers per wave left over, and 2 KB of LDS left free by the decoder's layout, walk and decoding share the
+// unit: 0.63 ms.  The 8 registers cost 2-4 % where nothing runs beside the launch, hence two kernels.  (The
+// attribute counts registers of one kind; for this device's unified file the compiler doubles it: 60 -> 120.)
+template <int kBlock>
+__global__ __launch_bounds__(kBlock, 4) __attribute__((amdgpu_num_vgpr(60))) void advance_beside_kernel(AdvanceParams p) {
   extern __shared__ __align__(16) unsigned char smem[];
   advance_channel<kBlock>(p, (int)blockIdx.x, smem);
 }
