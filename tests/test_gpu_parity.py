@@ -184,6 +184,48 @@ def test_shared_compute_units_and_unstaged_rows(torch_cuda, wgs):
         assert s["info"]["lds_bytes"] <= 163_840 // wgs
 
 
+def test_decoding_beside_result_walks(torch_cuda):
+    """A decoder whose calls fill the device in one round (more than half of the compute units) leaves room for
+    result walks and decodes with the 120-register kernel while walks are in flight: every chunk's partial result
+    is requested asynchronously, the next chunk is decoded before the request is finished, and every partial
+    result, the final tables and the final paths are the checker's."""
+    n_cu = torch_cuda.cuda.get_device_properties(0).multi_processor_count
+    C = n_cu * 5 // 8
+    g, L, ctxs, offs = mid_inputs(torch_cuda, C=C, T=40, S=40_000, P=400, seed=23, ctx_k=40)
+    Lh = L.cpu().numpy()
+    T = L.shape[1]
+    dec = GH.GpuDecoder(g, C, 13.0, 0, max_frames=T, max_context_arcs=40, lookup_mode=1)
+    try:
+        assert B.cbd_decoder_info(dec.dh)["block_threads"] == 1024
+        og = OracleGraph.from_graph(g)
+        orcs = GH.oracle_channels(g, C, 13.0, 0, og=og)
+        dec.set_contexts(ctxs, offs)
+        for c in range(C):
+            orcs[c].set_context(ctxs[c], offs[c])
+            orcs[c].reset()
+        dec.reset()
+        pending = None   # (ticket, expected results)
+        t = 0
+        for n in (8, 8, 8, 8, 8):
+            dec.advance(L, t, t + n)     # (from the second chunk on: with the previous chunk's walks in flight)
+            if pending is not None:
+                st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, pending[0])
+                for c in range(C):
+                    GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), pending[1][c], f"partial t={t - n} ch={c}")
+            for c in range(C):
+                orcs[c].advance(Lh[c, t:t + n])
+            t += n
+            pending = (B.cbd_best_paths_begin(dec.dh, dec.all, False, capacity=4 * T + 16),
+                       [orcs[c].best_path(False) for c in range(C)])
+        st, wl, al, cost, na, nw = B.cbd_best_paths_finish(dec.dh, pending[0])
+        for c in range(C):
+            GH.assert_best_equal((int(st[c]), wl[c], al[c], float(cost[c])), pending[1][c], f"last partial ch={c}")
+        for c in range(0, C, 7):
+            GH.assert_tables_equal(dec.tokens(c), orcs[c].tokens(), f"final table ch={c}")
+    finally:
+        dec.close()
+
+
 def test_lexicon_loop_units_workload(torch_cuda):
     """Second workload (Sec. 6: end-to-end model units): a lexicon loop with a 3000-arc hub row, self-loops,
     thousands of tokens per frame, max-active pruning engaged,
