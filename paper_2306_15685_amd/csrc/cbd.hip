@@ -1471,7 +1471,7 @@ int32_t best_paths_begin_impl(cbd_decoder *d, const int32_t *channels, int32_t n
   } else {
     o.snap_slot = -1;
     // decode stream: pick the best tokens now, before a later call changes the channels
-    hipLaunchKernelGGL(cbd::best_snapshot_kernel, dim3((unsigned)n), dim3(64), 0, d->stream, bp);
+    hipLaunchKernelGGL(cbd::best_snapshot_kernel, dim3((unsigned)n), dim3(cbd::kSnapThreads), 0, d->stream, bp);
     HIPCHK(hipGetLastError());
     HIPCHK(d->ids.release(slot, d->stream));
   }

@@ -1676,15 +1676,19 @@ struct BestParams {
 };
 
 // Best token of a channel's current table (Sec. 1: the current best token sequence is read
-// directly, no lattice).  One wave.  Returns the record index or -1; key receives (cost, arc).
-__device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanState *cs, uint64_t &key, int lane) {
+// directly, no lattice).  All kThreads threads of the workgroup call it (a team's token list has tens of thousands
+// of places: one wave alone needed 200 us); s_key / s_idx: one LDS entry per wave.  Every thread returns the
+// record index or -1; key receives (cost, arc).  Keys are unique (an arc leads to one state, a state has one token).
+template <int kThreads>
+__device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanState *cs, uint64_t &key, int tid,
+                                         unsigned long long *s_key, int *s_idx) {
   const int n = cs->n_tok, base = cs->frame_base;
   const int32_t *ts = p.tok_state + (size_t)c * p.tok_cap;
   const float *tc = p.tok_cost + (size_t)c * p.tok_cap;
   const int2 *bp = p.bp + (size_t)c * p.bp_cap;
   uint64_t bestk = kEmptyVal;
   int besti = -1;
-  for (int t = lane; t < n; t += 64) {
+  for (int t = tid; t < n; t += kThreads) {
     float cost = tc[t];
     if (!(cost < __builtin_inff())) continue;   // dropped by the frame cutoff
     if (p.use_final && p.final_cost) cost = cost + p.final_cost[ts[t]];
@@ -1697,6 +1701,15 @@ __device__ __forceinline__ int find_best(const BestParams &p, int c, const ChanS
     uint64_t ok = (uint64_t)__shfl_xor((long long)bestk, d, 64);
     int oi = __shfl_xor(besti, d, 64);
     if (ok < bestk) { bestk = ok; besti = oi; }
+  }
+  if (kThreads > 64) {
+    if ((tid & 63) == 0) { s_key[tid >> 6] = bestk; s_idx[tid >> 6] = besti; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kThreads / 64; ++w) {
+      const uint64_t ok = s_key[w];
+      if (ok < bestk) { bestk = ok; besti = s_idx[w]; }
+    }
   }
   key = bestk;
   return besti < 0 ? -1 : base + besti;
@@ -1865,12 +1878,11 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
     if (threadIdx.x == 0) { meta[0] = cs->status; meta[1] = 0; meta[2] = 0; meta[3] = inf_bits; }
     return;
   }
+  __shared__ unsigned long long s_key[kWalkThreads / 64];
+  __shared__ int s_idx[kWalkThreads / 64];
   uint64_t key = kEmptyVal;
-  int rec = -1;
-  if (wave == 0) {
-    rec = find_best(p, c, cs, key, lane);
-    if (lane == 0) s_walk_pos = rec < 0 ? kWalkDone : rec;
-  }
+  const int rec = find_best<kWalkThreads>(p, c, cs, key, (int)threadIdx.x, s_key, s_idx);
+  if (threadIdx.x == 0) s_walk_pos = rec < 0 ? kWalkDone : rec;
   __syncthreads();
   if (wave == 1) {
     walk_read_ahead(p, c, lane, &s_walk_pos);
@@ -1889,18 +1901,21 @@ __global__ __launch_bounds__(kWalkThreads) void best_path_kernel(BestParams p) {
 
 // Two-stage form for results delivered beside later decoding.  Stage 1 (decode stream): pick the
 // best token and note everything the walk needs, before the next call changes the channel.
-__global__ __launch_bounds__(64) void best_snapshot_kernel(BestParams p) {
-  const int lane = threadIdx.x, i = blockIdx.x;
+constexpr int kSnapThreads = 512;
+__global__ __launch_bounds__(kSnapThreads) void best_snapshot_kernel(BestParams p) {
+  __shared__ unsigned long long s_key[kSnapThreads / 64];
+  __shared__ int s_idx[kSnapThreads / 64];
+  const int i = blockIdx.x;
   const int c = p.chan_ids[i];
   const ChanState *cs = p.chan + c;
   int32_t *snap = p.snap + (size_t)i * kSnapInts;
   int status = cs->status, rec = -1;
   uint64_t key = kEmptyVal;
-  if (status == kStatusOk) {
-    rec = find_best(p, c, cs, key, lane);
+  if (status == kStatusOk) {   // (uniform)
+    rec = find_best<kSnapThreads>(p, c, cs, key, (int)threadIdx.x, s_key, s_idx);
     if (rec < 0) status = kStatusNoTokens;
   }
-  if (lane == 0) {
+  if (threadIdx.x == 0) {
     snap[0] = status; snap[1] = rec; snap[2] = (int)(uint32_t)(key >> 32); snap[3] = cs->n_rec; snap[4] = c;
     snap[5] = cs->gc_base; snap[6] = cs->n_fixed_arcs; snap[7] = cs->n_fixed_words;
   }
