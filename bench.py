@@ -30,11 +30,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # profiled build: a run whose own launch time is more than 5 % away from it is another kernel (or another machine
 # state) and reports no traffic instead of a stale one.
 MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py reported in the profiled runs)
-    "large": (1290618333, 0.6249),
-    "stress": (14470884563, 5.4752),
-    "dynamic": (4623351035, 1.8902),
-    "medium": (438501661, 2.3161),
-    "words": (523579812, 0.5125),
+    "large": (1199877623, 0.6228),
+    "stress": (13698558361, 5.0273),
+    "dynamic": (4428769894, 1.9124),
+    "medium": (424933537, 2.2757),
+    "words": (517525311, 0.5227),
     "e2e": (4250525025, 4.0906),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
