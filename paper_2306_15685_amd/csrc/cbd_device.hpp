@@ -1357,7 +1357,8 @@ __device__ __forceinline__ void advance_channel(const AdvanceParams &p, const in
   const LeanMem LM = make_lean_mem(ML.log, p.lds_tok_cap, p.lds_slots, p.lean_log_per_wave);
   bool rows_in_lds = false;   // the current tokens' rows: in LDS (lean frames) or in the row buffer `cur`
   for (int f = p.do_reset ? -1 : 0; f < p.n_frames; ++f) {
-    const float *Lnext = (p.stage_rows && f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
+    // the next frame's row (staged rows: copied to LDS during this frame; others: only the lean code uses it)
+    const float *Lnext = (f >= 0 && f + 1 < p.n_frames) ? Lbase + (long long)(f + 1) * p.num_pdfs : nullptr;
     Rows rows;
     rows.lds = (lds_cfloat_ptr)Lrow; rows.glob = Lbase + (long long)(f < 0 ? 0 : f) * p.num_pdfs; rows.staged = p.stage_rows != 0;
     const bool last = f == p.n_frames - 1;
@@ -1385,7 +1386,7 @@ __device__ __forceinline__ void advance_channel(const AdvanceParams &p, const in
       }
       if (!lean || outcome == kFrameRedo) {
         if (rows_in_lds) { rows_to_device<kBlock>(ML, LM, sh->n_tok, cur); rows_in_lds = false; }
-        outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+        outcome = run_frame<true, kBlock>(p, ML, sh, cx, Lrow, rows, p.stage_rows ? Lnext : nullptr, hist, owner_maps, f, cur, bp, g_tok_state, last);
         if (outcome == kFrameOk) cur ^= 1;
 #ifdef CBD_PROFILE
         if (lean && tid == 0) sh->prof_general += wall_clock64();
@@ -1405,7 +1406,7 @@ __device__ __forceinline__ void advance_channel(const AdvanceParams &p, const in
     }
     if (slow) {
       const Mem<false> MG = make_MG();
-      outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, Lnext, hist, owner_maps, f, cur, bp, g_tok_state, last);
+      outcome = run_frame<false, kBlock>(p, MG, sh, cx, Lrow, rows, p.stage_rows ? Lnext : nullptr, hist, owner_maps, f, cur, bp, g_tok_state, last);
       if (outcome == kFrameOk) cur ^= 1;
     }
     if (outcome != kFrameOk) break;

@@ -494,7 +494,13 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
   }
   // The emit phase is long over: the next frame's row starts its way.  (Not earlier: loads return in order, and
   // the closure stages' reads would queue behind the row.)
-  if (Lnext) stage_row_async<kBlock>(Lstage, Lnext, p.num_pdfs, wave, lane);
+  // A row that is not staged is touched instead, one lane per 64 bytes: the next frame's emit phase then finds it
+  // in L2 (the value is asked for again at the end of the frame, so that the read is kept and nothing waits for it).
+  float touched = 0.0f;
+  if (Lnext) {
+    if (Lrow.staged) stage_row_async<kBlock>(Lstage, Lnext, p.num_pdfs, wave, lane);
+    else if (tid * 16 < p.num_pdfs) touched = Lnext[tid * 16];
+  }
   if (lane == 0) sh->wcount[wave] = W.n_claimed;
   CBD_STAMP(2);   // commit phase of wave 0
   wg_barrier<true>();
@@ -622,6 +628,7 @@ __device__ __forceinline__ int run_frame_lean(const AdvanceParams &p, const Mem<
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's pieces of the next row have arrived in LDS
   wg_barrier<true>();
   CBD_STAMP(5);   // its wait at the last barrier (with the closing of the frame by the last wave)
+  asm volatile("" ::"v"(touched));
   return kFrameOk;
 }
 
