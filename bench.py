@@ -30,11 +30,11 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # profiled build: a run whose own launch time is more than 5 % away from it is another kernel (or another machine
 # state) and reports no traffic instead of a stale one.
 MEASURED_TRAFFIC = {  # workload: (bytes per launch, ms per launch that bench.py reported in the profiled runs)
-    "large": (1199877623, 0.6228),
-    "stress": (13698558361, 5.0273),
-    "dynamic": (4428769894, 1.9124),
-    "medium": (424933537, 2.2757),
-    "words": (517525311, 0.5227),
+    "large": (1250044412, 0.6156),
+    "stress": (14224662745, 4.9539),
+    "dynamic": (4625691914, 1.8659),
+    "medium": (438157735, 2.2768),
+    "words": (523528186, 0.5160),
     "e2e": (4250525025, 4.0906),   # teams of four workgroups per channel
 }
 TRAFFIC_TOLERANCE = 0.05
