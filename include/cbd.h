@@ -115,10 +115,12 @@ typedef struct cbd_config {
   int32_t records_per_frame;  /* average back-pointer records per frame to reserve; 0 = table capacity / 2 */
   int32_t table_location;     /* 0 or 1 = LDS tables, frames that outgrow them are redone in device memory;
                                  2 = device-memory tables only */
-  int32_t lds_token_cap;      /* tokens per frame the LDS tables hold; 0 = as many as fit beside the row */
+  int32_t lds_token_cap;      /* tokens per frame the LDS tables hold; 0 = as many as fit (a log-likelihood row of
+                                 up to 1024 pdfs is kept in LDS beside them, a longer one is read from device memory) */
   int32_t max_pool_contexts;  /* pre-loaded contexts the decoder can hold besides one per channel (Sec. 4.3) */
   int32_t workgroups_per_cu;  /* channels decoded side by side on one compute unit (they share its LDS, so each
-                                 gets a smaller table): 1, 2 or 4; 0 = chosen by the library (1) */
+                                 gets a smaller table): 1, 2 or 4; 0 = chosen by the library (1).  CBD_E_INVALID if
+                                 the device cannot hold that many workgroups of the kernel on a compute unit */
   int32_t compact_records_above; /* 0 = records are only compacted on request (cbd_compact_records); N > 0 = a
                                  cbd_advance call first compacts those of its channels that hold more than N records
                                  above the part their paths share, and with them (so that a call is held up once,
